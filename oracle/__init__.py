@@ -1,0 +1,238 @@
+"""CPU oracle of the in-hindsight quantized-training layer path (test infrastructure).
+
+Thin ctypes front of ``hq_oracle.c`` plus the few lines that string its steps
+together in the order the paper gives them (Sec. 3.2 static / dynamic
+quantization, Sec. 4.1 in-hindsight min-max).  Only tests, the smoke check and
+the benchmark's CPU-baseline leg may import this package; the HIP library never
+does, and this package imports nothing from it.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+class Problem(C.Structure):
+    """Layer shape.  kind: 0 linear, 1 conv2d, 2 depthwise conv2d."""
+    _fields_ = [(n, C.c_int32) for n in
+                ("kind", "B", "H", "W", "C", "R", "S", "stride", "pad", "Cout")]
+
+    @staticmethod
+    def linear(M, K, N):
+        return Problem(0, M, 1, 1, K, 1, 1, 1, 0, N)
+
+    @staticmethod
+    def conv(B, H, W, Cin, Cout, R, S, stride, pad):
+        return Problem(1, B, H, W, Cin, R, S, stride, pad, Cout)
+
+    @staticmethod
+    def depthwise(B, H, W, Ch, R, S, stride, pad):
+        return Problem(2, B, H, W, Ch, R, S, stride, pad, Ch)
+
+    def out_hw(self):
+        oh, ow = C.c_int32(), C.c_int32()
+        lib().hqo_out_hw(C.byref(self), C.byref(oh), C.byref(ow))
+        return oh.value, ow.value
+
+    def out_shape(self):
+        oh, ow = self.out_hw()
+        return (self.B, oh, ow, self.Cout)
+
+    def in_shape(self):
+        return (self.B, self.H, self.W, self.C)
+
+    def w_shape(self):
+        if self.kind == 2:
+            return (self.R, self.S, self.C)
+        return (self.Cout, self.R, self.S, self.C)
+
+
+class Range(C.Structure):
+    """State of one quantizer: eq. (2)-(3) range, momentum, grid, derived (scale, zero point)."""
+    _fields_ = [("qmin", C.c_float), ("qmax", C.c_float), ("eta", C.c_float),
+                ("qlo", C.c_int32), ("qhi", C.c_int32), ("symmetric", C.c_int32),
+                ("initialized", C.c_int32), ("scale", C.c_float), ("zero_point", C.c_int32)]
+
+    @staticmethod
+    def new(eta=0.9, symmetric=False):
+        if symmetric:
+            return Range(0.0, 0.0, eta, -127, 127, 1, 0, 1.0, 0)
+        return Range(0.0, 0.0, eta, -128, 127, 0, 0, 1.0, 0)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        i8p, i32p, i64p, f32p = (C.POINTER(t) for t in (C.c_int8, C.c_int32, C.c_int64, C.c_float))
+        PP = C.POINTER(Problem)
+        L.hqo_num_threads.restype = C.c_int
+        L.hqo_out_hw.argtypes = [PP, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.hqo_fwd.argtypes = [PP, i8p, C.c_int, i8p, i32p]
+        L.hqo_fwd_rows.argtypes = [PP, i8p, C.c_int, i8p, i64p, C.c_int64, i32p]
+        L.hqo_dgrad.argtypes = [PP, i8p, C.c_int, i8p, i32p]
+        L.hqo_dgrad_rows.argtypes = [PP, i8p, C.c_int, i8p, i64p, C.c_int64, i32p]
+        L.hqo_wgrad.argtypes = [PP, i8p, C.c_int, i8p, C.c_int, i32p]
+        L.hqo_minmax.argtypes = [i32p, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.hqo_qparams.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int, C.c_int,
+                                  C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.hqo_requant.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, C.c_int, C.c_int, C.c_int,
+                                  i8p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.hqo_range_update.argtypes = [C.POINTER(Range), C.c_int32, C.c_int32, C.c_float]
+        L.hqo_wgrad_scale.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, f32p]
+        for f in ("hqo_fwd", "hqo_fwd_rows", "hqo_dgrad", "hqo_dgrad_rows", "hqo_wgrad"):
+            getattr(L, f).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def _chk(a, dtype, shape=None):
+    assert a.dtype == dtype and a.flags.c_contiguous, (a.dtype, a.flags)
+    if shape is not None:
+        assert tuple(a.shape) == tuple(shape), (a.shape, shape)
+    return a
+
+
+def num_threads():
+    return lib().hqo_num_threads()
+
+
+def fwd(p, X, zx, W):
+    """Zero-point-free forward accumulator, int32 [B,OH,OW,Cout] (Sec. 3.1)."""
+    _chk(X, np.int8, p.in_shape()); _chk(W, np.int8, p.w_shape())
+    out = np.empty(p.out_shape(), np.int32)
+    bad = lib().hqo_fwd(C.byref(p), _p(X, C.c_int8), int(zx), _p(W, C.c_int8), _p(out, C.c_int32))
+    assert bad == 0, "accumulator does not fit 32 bits"
+    return out
+
+
+def fwd_rows(p, X, zx, W, rows):
+    _chk(X, np.int8, p.in_shape()); _chk(W, np.int8, p.w_shape())
+    rows = np.ascontiguousarray(rows, np.int64)
+    out = np.empty((len(rows), p.Cout), np.int32)
+    bad = lib().hqo_fwd_rows(C.byref(p), _p(X, C.c_int8), int(zx), _p(W, C.c_int8),
+                             _p(rows, C.c_int64), len(rows), _p(out, C.c_int32))
+    assert bad == 0
+    return out
+
+
+def dgrad(p, dY, zg, W):
+    """Zero-point-free input-gradient accumulator, int32 [B,H,W,C] (Sec. 3.1)."""
+    _chk(dY, np.int8, p.out_shape()); _chk(W, np.int8, p.w_shape())
+    out = np.empty(p.in_shape(), np.int32)
+    bad = lib().hqo_dgrad(C.byref(p), _p(dY, C.c_int8), int(zg), _p(W, C.c_int8), _p(out, C.c_int32))
+    assert bad == 0
+    return out
+
+
+def dgrad_rows(p, dY, zg, W, rows):
+    _chk(dY, np.int8, p.out_shape()); _chk(W, np.int8, p.w_shape())
+    rows = np.ascontiguousarray(rows, np.int64)
+    out = np.empty((len(rows), p.C), np.int32)
+    bad = lib().hqo_dgrad_rows(C.byref(p), _p(dY, C.c_int8), int(zg), _p(W, C.c_int8),
+                               _p(rows, C.c_int64), len(rows), _p(out, C.c_int32))
+    assert bad == 0
+    return out
+
+
+def wgrad(p, X, zx, dY, zg):
+    """Zero-point-free weight-gradient accumulator, int32, shaped like the weights (Sec. 3.1)."""
+    _chk(X, np.int8, p.in_shape()); _chk(dY, np.int8, p.out_shape())
+    out = np.empty(p.w_shape(), np.int32)
+    bad = lib().hqo_wgrad(C.byref(p), _p(X, C.c_int8), int(zx), _p(dY, C.c_int8), int(zg),
+                          _p(out, C.c_int32))
+    assert bad == 0
+    return out
+
+
+def minmax(c):
+    """eq. (1) over the accumulator output."""
+    c = np.ascontiguousarray(c, np.int32)
+    mn, mx = C.c_int32(), C.c_int32()
+    lib().hqo_minmax(_p(c, C.c_int32), c.size, C.byref(mn), C.byref(mx))
+    return mn.value, mx.value
+
+
+def qparams(qmin, qmax, symmetric, qlo, qhi):
+    s, z = C.c_float(), C.c_int32()
+    lib().hqo_qparams(float(qmin), float(qmax), int(symmetric), int(qlo), int(qhi), C.byref(s), C.byref(z))
+    return np.float32(s.value), z.value
+
+
+def requant(c, acc_scale, s_y, z_y, qlo, qhi):
+    """Static quantization of accumulator outputs; returns (codes, clip_lo, clip_hi)."""
+    c = np.ascontiguousarray(c, np.int32)
+    out = np.empty(c.shape, np.int8)
+    lo, hi = C.c_uint64(), C.c_uint64()
+    lib().hqo_requant(_p(c, C.c_int32), c.size, float(acc_scale), float(s_y), int(z_y), int(qlo), int(qhi),
+                      _p(out, C.c_int8), C.byref(lo), C.byref(hi))
+    return out, lo.value, hi.value
+
+
+def range_update(r, acc_min, acc_max, acc_scale):
+    """eq. (2)-(3) in place on ``r``; the first call sets q^0."""
+    lib().hqo_range_update(C.byref(r), int(acc_min), int(acc_max), float(acc_scale))
+    return r
+
+
+def wgrad_scale(c, sx, sg):
+    c = np.ascontiguousarray(c, np.int32)
+    out = np.empty(c.shape, np.float32)
+    lib().hqo_wgrad_scale(_p(c, C.c_int32), c.size, float(sx), float(sg), _p(out, C.c_float))
+    return out
+
+
+def acc_scale(sa, sb):
+    """Real value of one accumulator unit: the fp32 product of the operand scales."""
+    return np.float32(np.float32(sa) * np.float32(sb))
+
+
+# ---------------------------------------------------------------------------
+# The two ways of quantizing an accumulator output (Sec. 3.2) and the
+# in-hindsight step built on the static one (Sec. 4.1).
+# ---------------------------------------------------------------------------
+
+def quantize_static(c, a_scale, r):
+    """Static quantization with the pre-computed range held in ``r`` (step 1 of Sec. 4);
+    the statistics of the current tensor are gathered on the side (step 2).
+    Returns dict(codes, scale, zero_point, acc_min, acc_max, clip_lo, clip_hi, count)."""
+    mn, mx = minmax(c)
+    codes, lo, hi = requant(c, a_scale, r.scale, r.zero_point, r.qlo, r.qhi)
+    return dict(codes=codes, scale=np.float32(r.scale), zero_point=r.zero_point,
+                acc_min=mn, acc_max=mx, clip_lo=lo, clip_hi=hi, count=c.size)
+
+
+def quantize_dynamic(c, a_scale, symmetric, qlo, qhi):
+    """Dynamic quantization: the range is the min-max of the tensor itself, eq. (1)."""
+    mn, mx = minmax(c)
+    gmin = np.float32(a_scale) * np.float32(mn)
+    gmax = np.float32(a_scale) * np.float32(mx)
+    s, z = qparams(gmin, gmax, symmetric, qlo, qhi)
+    codes, lo, hi = requant(c, a_scale, s, z, qlo, qhi)
+    return dict(codes=codes, scale=s, zero_point=z, acc_min=mn, acc_max=mx,
+                clip_lo=lo, clip_hi=hi, count=c.size)
+
+
+def in_hindsight_step(c, a_scale, r):
+    """One iteration of in-hindsight min-max for one tensor (Sec. 4.1).
+
+    t = 0 (``r`` not initialised): the range of the first batch is its own min-max,
+    so the tensor is quantized dynamically and q^0 is set from it.  Later iterations
+    quantize statically with q^t.  In both cases the statistics of this tensor then
+    move the range to q^{t+1} by eq. (2)-(3)."""
+    if not r.initialized:
+        out = quantize_dynamic(c, a_scale, r.symmetric, r.qlo, r.qhi)
+        range_update(r, out["acc_min"], out["acc_max"], a_scale)      # sets q^0
+    else:
+        out = quantize_static(c, a_scale, r)
+    range_update(r, out["acc_min"], out["acc_max"], a_scale)          # q^{t+1}
+    return out

@@ -1,0 +1,405 @@
+"""Pins of the CPU oracle against things other than itself: values the paper prints,
+closed forms, brute force in Python integers, NumPy int64 matmul on an explicit im2col
+matrix, adjoint identities.  No GPU needed."""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import traffic
+from oracle import Problem, Range
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+f32 = np.float32
+
+
+# --------------------------------------------------------------------------- P1
+def test_traffic_model_reproduces_table5():
+    """eq. (4)/(5) at b_w=b_a=8, b_acc=32 give the KB printed in Table 5 (rows 1,2,3,5 to the
+    printed integer; row 4's printed KB do not follow from its stated shape -- they are those of
+    a 144-channel 56x56 layer without the weight term -- so only its ratio is pinned)."""
+    rows = [l.split() for l in open(os.path.join(HERE, "golden", "table5_memory.txt"))
+            if not l.startswith("#") and l.strip()]
+    assert len(rows) == 5
+    for i, (net, kind, ci, co, w, h, s_kb, d_kb, delta) in enumerate(rows):
+        ci, co, w, h, s_kb, d_kb, delta = map(int, (ci, co, w, h, s_kb, d_kb, delta))
+        k, dw = int(kind[0]), kind.endswith("dw")
+        s = traffic.kib(traffic.static_bits(ci, co, k, w, h, depthwise=dw))
+        d = traffic.kib(traffic.dynamic_bits(ci, co, k, w, h, depthwise=dw))
+        assert round((d / s - 1) * 100) == delta
+        if i != 3:
+            assert abs(s - s_kb) <= 0.5 and abs(d - d_kb) <= 0.5, (net, kind, s, d)
+        else:
+            assert 2 * 144 * 56 * 56 / 1024 == s_kb and 10 * 144 * 56 * 56 / 1024 == d_kb
+
+
+def test_traffic_model_terms():
+    # dynamic - static is exactly one save and one load of the accumulator output
+    assert traffic.dynamic_bits(3, 5, 3, 7, 11) - traffic.static_bits(3, 5, 3, 7, 11) == 2 * 5 * 7 * 11 * 32
+    assert traffic.static_bits(3, 5, 3, 7, 11) == (3 * 5 * 9 + 3 * 77 + 5 * 77) * 8
+
+
+# --------------------------------------------------------------------------- P6
+def test_linear_brute_force_tiny():
+    cases = []
+    g = np.random.default_rng(0)
+    for M, K, N in [(1, 1, 1), (2, 3, 4), (4, 4, 4), (3, 5, 2)]:
+        cases.append((g.integers(-128, 128, (M, K)), g.integers(-128, 128, (N, K)), int(g.integers(-128, 128))))
+    cases.append((np.full((4, 4), -128), np.full((4, 4), -128), 0))
+    cases.append((np.full((4, 4), 127), np.full((4, 4), 127), -128))
+    cases.append((np.eye(4, dtype=np.int64) * 127, np.arange(16).reshape(4, 4) - 8, 0))
+    for A, Wt, z in cases:
+        M, K = A.shape; N = Wt.shape[0]
+        p = Problem.linear(M, K, N)
+        got = oracle.fwd(p, A.astype(np.int8).reshape(p.in_shape()), z, Wt.astype(np.int8).reshape(p.w_shape()))
+        for m in range(M):
+            for n in range(N):
+                want = sum((int(A[m, k]) - z) * int(Wt[n, k]) for k in range(K))
+                assert got.reshape(M, N)[m, n] == want
+
+
+def test_linear_matches_numpy_int64_matmul():
+    g = np.random.default_rng(1)
+    for M, K, N in [(37, 129, 53), (256, 512, 64), (5, 1000, 7)]:
+        A = g.integers(-128, 128, (M, K), dtype=np.int8)
+        Wt = g.integers(-128, 128, (N, K), dtype=np.int8)
+        z = -128
+        p = Problem.linear(M, K, N)
+        got = oracle.fwd(p, A.reshape(p.in_shape()), z, Wt.reshape(p.w_shape())).reshape(M, N)
+        want = (A.astype(np.int64) - z) @ Wt.astype(np.int64).T
+        assert np.array_equal(got, want)
+        # linear dgrad and wgrad are the two other matmuls
+        G = g.integers(-128, 128, (M, N), dtype=np.int8)
+        dx = oracle.dgrad(p, G.reshape(p.out_shape()), 3, Wt.reshape(p.w_shape())).reshape(M, K)
+        assert np.array_equal(dx, (G.astype(np.int64) - 3) @ Wt.astype(np.int64))
+        dw = oracle.wgrad(p, A.reshape(p.in_shape()), z, G.reshape(p.out_shape()), 3).reshape(N, K)
+        assert np.array_equal(dw, (G.astype(np.int64) - 3).T @ (A.astype(np.int64) - z))
+
+
+# --------------------------------------------------------------------------- P7
+def im2col(X, z, R, S, stride, pad):
+    """Explicit patch matrix [B*OH*OW, R*S*C] of (X - z) with zeros outside the image."""
+    B, H, W, C = X.shape
+    OH, OW = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    Xp = np.zeros((B, H + 2 * pad, W + 2 * pad, C), np.int64)
+    Xp[:, pad:pad + H, pad:pad + W, :] = X.astype(np.int64) - z
+    cols = np.empty((B, OH, OW, R, S, C), np.int64)
+    for r in range(R):
+        for s in range(S):
+            cols[:, :, :, r, s, :] = Xp[:, r:r + stride * OH:stride, s:s + stride * OW:stride, :]
+    return cols.reshape(B * OH * OW, R * S * C), OH, OW
+
+
+CONV_CASES = [  # B, H, W, Cin, Cout, R, S, stride, pad
+    (2, 5, 6, 3, 4, 3, 3, 1, 1),
+    (1, 7, 7, 4, 5, 3, 3, 2, 1),
+    (2, 8, 6, 2, 3, 1, 1, 2, 0),
+    (1, 9, 9, 4, 2, 7, 7, 2, 3),
+    (3, 4, 4, 5, 6, 1, 1, 1, 0),
+    (1, 6, 5, 3, 2, 3, 3, 1, 0),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_fwd_matches_im2col_matmul(case):
+    B, H, W, Cin, Cout, R, S, stride, pad = case
+    g = np.random.default_rng(hash(case) % 2**32)
+    X = g.integers(-128, 128, (B, H, W, Cin), dtype=np.int8)
+    Wt = g.integers(-128, 128, (Cout, R, S, Cin), dtype=np.int8)
+    z = int(g.integers(-128, 128))
+    p = Problem.conv(B, H, W, Cin, Cout, R, S, stride, pad)
+    cols, OH, OW = im2col(X, z, R, S, stride, pad)
+    assert p.out_hw() == (OH, OW)
+    want = cols @ Wt.astype(np.int64).reshape(Cout, -1).T
+    got = oracle.fwd(p, X, z, Wt)
+    assert np.array_equal(got.reshape(-1, Cout), want)
+    rows = g.permutation(B * OH * OW)[:7]
+    assert np.array_equal(oracle.fwd_rows(p, X, z, Wt, rows), want[rows])
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_dgrad_wgrad_adjoint_identities(case):
+    """<conv(X,W), G> = <X, dgrad(G,W)> = <W, wgrad(X,G)> in exact integers, for one-hot probes of
+    every position: this fixes every element of dgrad and wgrad, not just an inner product."""
+    B, H, W, Cin, Cout, R, S, stride, pad = case
+    g = np.random.default_rng(hash(case) % 2**32 + 1)
+    X = g.integers(-128, 128, (B, H, W, Cin), dtype=np.int8)
+    Wt = g.integers(-128, 128, (Cout, R, S, Cin), dtype=np.int8)
+    p = Problem.conv(B, H, W, Cin, Cout, R, S, stride, pad)
+    OH, OW = p.out_hw()
+    G = g.integers(-128, 128, (B, OH, OW, Cout), dtype=np.int8)
+    zx, zg = int(g.integers(-128, 128)), int(g.integers(-20, 20))
+    cols, _, _ = im2col(X, zx, R, S, stride, pad)
+    Gm = G.astype(np.int64).reshape(-1, Cout) - zg
+    # wgrad = G^T . cols   (textbook: derivative of cols @ W^T w.r.t. W)
+    want_dw = (Gm.T @ cols).reshape(Cout, R, S, Cin)
+    assert np.array_equal(oracle.wgrad(p, X, zx, G, zg), want_dw)
+    # dgrad = col2im(G . W): scatter-add of the patch-matrix gradient
+    dcols = (Gm @ Wt.astype(np.int64).reshape(Cout, -1)).reshape(B, OH, OW, R, S, Cin)
+    dXp = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin), np.int64)
+    for r in range(R):
+        for s in range(S):
+            dXp[:, r:r + stride * OH:stride, s:s + stride * OW:stride, :] += dcols[:, :, :, r, s, :]
+    want_dx = dXp[:, pad:pad + H, pad:pad + W, :]
+    got_dx = oracle.dgrad(p, G, zg, Wt)
+    assert np.array_equal(got_dx, want_dx)
+    rows = g.permutation(B * H * W)[:9]
+    assert np.array_equal(oracle.dgrad_rows(p, G, zg, Wt, rows), want_dx.reshape(-1, Cin)[rows])
+    # the scalar identities
+    y = oracle.fwd(p, X, zx, Wt).astype(np.int64)
+    assert int((y * (G.astype(np.int64) - zg)).sum()) == int(((X.astype(np.int64) - zx) * want_dx).sum()) \
+        == int((Wt.astype(np.int64) * want_dw).sum())
+
+
+DW_CASES = [(2, 5, 6, 3, 3, 3, 1, 1), (1, 7, 8, 4, 3, 3, 2, 1), (1, 6, 6, 2, 5, 5, 1, 2)]
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+def test_depthwise_is_per_channel_conv(case):
+    """A depthwise layer is C independent single-channel convolutions."""
+    B, H, W, Ch, R, S, stride, pad = case
+    g = np.random.default_rng(hash(case) % 2**32)
+    X = g.integers(-128, 128, (B, H, W, Ch), dtype=np.int8)
+    Wd = g.integers(-128, 128, (R, S, Ch), dtype=np.int8)
+    p = Problem.depthwise(B, H, W, Ch, R, S, stride, pad)
+    OH, OW = p.out_hw()
+    G = g.integers(-128, 128, (B, OH, OW, Ch), dtype=np.int8)
+    zx, zg = -128, 5
+    y, dx, dw = oracle.fwd(p, X, zx, Wd), oracle.dgrad(p, G, zg, Wd), oracle.wgrad(p, X, zx, G, zg)
+    rows = g.permutation(B * OH * OW)[:5]
+    assert np.array_equal(oracle.fwd_rows(p, X, zx, Wd, rows), y.reshape(-1, Ch)[rows])
+    rows = g.permutation(B * H * W)[:5]
+    assert np.array_equal(oracle.dgrad_rows(p, G, zg, Wd, rows), dx.reshape(-1, Ch)[rows])
+    for c in range(Ch):
+        cols, _, _ = im2col(X[..., c:c + 1], zx, R, S, stride, pad)
+        wc = Wd[..., c].astype(np.int64).reshape(-1)
+        assert np.array_equal(y[..., c].reshape(-1), cols @ wc)
+        gm = G[..., c].astype(np.int64).reshape(-1) - zg
+        assert np.array_equal(dw[..., c].reshape(-1), gm @ cols)
+        dcols = np.outer(gm, wc).reshape(B, OH, OW, R, S)
+        dXp = np.zeros((B, H + 2 * pad, W + 2 * pad), np.int64)
+        for r in range(R):
+            for s in range(S):
+                dXp[:, r:r + stride * OH:stride, s:s + stride * OW:stride] += dcols[:, :, :, r, s]
+        assert np.array_equal(dx[..., c], dXp[:, pad:pad + H, pad:pad + W])
+
+
+def test_minmax_brute():
+    g = np.random.default_rng(3)
+    c = g.integers(-2**31, 2**31, 1001).astype(np.int32)
+    assert oracle.minmax(c) == (int(min(c.tolist())), int(max(c.tolist())))
+    assert oracle.minmax(np.array([7], np.int32)) == (7, 7)
+
+
+# --------------------------------------------------------------------------- P8
+def test_qparams_hand_values():
+    # asymmetric: [0, 255 s] -> scale s, zero point at the bottom of the grid
+    s, z = oracle.qparams(0.0, 255 * 0.5, 0, -128, 127)
+    assert s == f32(0.5) and z == -128
+    # [-1, 3]: width 4, scale 4/255, zero point rne(-128 + 63.75) = -64
+    s, z = oracle.qparams(-1.0, 3.0, 0, -128, 127)
+    assert s == f32(4.0) / f32(255.0) and z == -64
+    # range not containing zero is widened to it: [2, 4] behaves as [0, 4]
+    assert oracle.qparams(2.0, 4.0, 0, -128, 127) == oracle.qparams(0.0, 4.0, 0, -128, 127)
+    assert oracle.qparams(-4.0, -2.0, 0, -128, 127) == (f32(4.0) / f32(255.0), 127)
+    # symmetric: scale = max|.|/127, zero point 0
+    s, z = oracle.qparams(-2.54, 1.0, 1, -127, 127)
+    assert s == f32(2.54) / f32(127) and z == 0
+    s, z = oracle.qparams(-1.0, 12.7, 1, -127, 127)
+    assert s == f32(12.7) / f32(127) and z == 0
+    # degenerate ranges
+    assert oracle.qparams(0.0, 0.0, 0, -128, 127) == (f32(1.0), -128)
+    assert oracle.qparams(0.0, 0.0, 1, -127, 127) == (f32(1.0), 0)
+
+
+def test_quantize_dequantize_idempotent_monotone_in_grid():
+    g = np.random.default_rng(4)
+    for sym in (0, 1):
+        qlo, qhi = (-127, 127) if sym else (-128, 127)
+        for _ in range(20):
+            lo, hi = -abs(g.normal()) * 10 ** g.uniform(-3, 3), abs(g.normal()) * 10 ** g.uniform(-3, 3)
+            s, z = oracle.qparams(lo, hi, sym, qlo, qhi)
+            assert s > 0 and qlo <= z <= qhi
+            codes = np.arange(qlo, qhi + 1)
+            # dequantized code, re-expressed in accumulator units of size s, quantizes back to itself
+            back, nlo, nhi = oracle.requant((codes - z).astype(np.int32), s, s, z, qlo, qhi)
+            assert np.array_equal(back, codes) and nlo == 0 and nhi == 0
+            # real zero is exactly representable: accumulator 0 -> zero point
+            assert oracle.requant(np.zeros(1, np.int32), s, s, z, qlo, qhi)[0][0] == z
+            # monotone and inside the grid on a wide sweep, acc unit = s/7
+            c = np.arange(-4000, 4000, dtype=np.int32)
+            q, nlo, nhi = oracle.requant(c, f32(s) / f32(7), s, z, qlo, qhi)
+            assert np.all(np.diff(q.astype(int)) >= 0) and q.min() >= qlo and q.max() <= qhi
+
+
+# --------------------------------------------------------------------------- P9
+def round_half_even(fr):
+    fl = math.floor(fr)
+    d = fr - fl
+    if d > Fraction(1, 2) or (d == Fraction(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
+@pytest.mark.parametrize("num,den", [(1, 2), (1, 4), (3, 8), (5, 16), (1, 1), (3, 2), (7, 64), (1, 1024)])
+def test_requant_rounding_exhaustive_vs_integer_arithmetic(num, den):
+    """m = num/den is exact in fp32 and c*m is exact for |c| < 2^17, so the rounded value has an
+    integer-arithmetic definition: round_half_even(c*num/den).  Includes every .5 tie."""
+    c = np.arange(-70000, 70000, dtype=np.int32)
+    z, qlo, qhi = 3, -(2**20), 2**20          # grid wide open: nothing clamps
+    # int8 output would wrap; use a narrow window for codes and a wide one for counting
+    got, nlo, nhi = oracle.requant(c, f32(num), f32(den), z, -128, 127)
+    want = np.array([min(max(round_half_even(Fraction(int(v) * num, den)) + z, -128), 127) for v in c.tolist()])
+    assert np.array_equal(got, want)
+    r = np.array([round_half_even(Fraction(int(v) * num, den)) + z for v in c.tolist()])
+    assert nlo == int((r < -128).sum()) and nhi == int((r > 127).sum())
+
+
+# --------------------------------------------------------------------------- P10
+def test_clip_counts_brute_force_and_saturation_ratio():
+    g = np.random.default_rng(5)
+    c = g.integers(-3000, 3000, 5000).astype(np.int32)
+    a_scale = f32(0.01)
+    for lo, hi, sym in [(-10.0, 10.0, 0), (-5.0, 20.0, 0), (-3.0, 3.0, 1), (-100.0, 100.0, 0), (0.0, 12.0, 0)]:
+        qlo, qhi = (-127, 127) if sym else (-128, 127)
+        s, z = oracle.qparams(lo, hi, sym, qlo, qhi)
+        codes, nlo, nhi = oracle.requant(c, a_scale, s, z, qlo, qhi)
+        m = f32(a_scale) / f32(s)
+        r = np.rint((c.astype(np.float32) * m).astype(np.float32)).astype(np.int64) + z
+        assert nlo == int((r < qlo).sum()) and nhi == int((r > qhi).sum())
+        inside = int(((r >= qlo) & (r <= qhi)).sum())
+        assert nlo + nhi + inside == c.size
+        assert np.array_equal(codes, np.clip(r, qlo, qhi))
+        # saturation ratio (Sec. 4 footnote): share of values outside the grid; real-valued count
+        # may differ only by values within half a step of an edge
+        real = c.astype(np.float64) * float(a_scale)
+        rlo, rhi = float(s) * (qlo - z), float(s) * (qhi - z)
+        outside = int((real < rlo - 0.5 * float(s)).sum() + (real > rhi + 0.5 * float(s)).sum())
+        assert abs((nlo + nhi) - outside) <= int((np.abs(real - rlo) <= 0.51 * float(s)).sum()
+                                                 + (np.abs(real - rhi) <= 0.51 * float(s)).sum())
+    # a range that contains the data clips nothing
+    s, z = oracle.qparams(-30.0, 30.0, 0, -128, 127)
+    assert oracle.requant(c, a_scale, s, z, -128, 127)[1:] == (0, 0)
+
+
+# --------------------------------------------------------------------------- P2-P4
+def test_range_update_init_and_special_momenta():
+    r = Range.new(eta=0.9)
+    assert r.initialized == 0
+    oracle.range_update(r, -100, 300, f32(0.5))            # t = 0: q^0 = min/max of first batch
+    assert r.initialized == 1 and (r.qmin, r.qmax) == (-50.0, 150.0)
+    assert (f32(r.scale), r.zero_point) == oracle.qparams(-50.0, 150.0, 0, -128, 127)
+    # q^1 from the same statistics stays at q^0 (up to fp32 rounding of the two products)
+    oracle.range_update(r, -100, 300, f32(0.5))
+    assert abs(r.qmin + 50.0) <= 50.0 * 2e-7 and abs(r.qmax - 150.0) <= 150.0 * 2e-7
+    # eta = 0: the range is the previous tensor's min-max
+    r0 = Range.new(eta=0.0); oracle.range_update(r0, -1, 1, f32(1.0)); oracle.range_update(r0, -7, 9, f32(2.0))
+    assert (r0.qmin, r0.qmax) == (-14.0, 18.0)
+    # eta = 1: the range never leaves q^0
+    r1 = Range.new(eta=1.0); oracle.range_update(r1, -1, 1, f32(1.0))
+    for k in range(5):
+        oracle.range_update(r1, -1000 * k, 1000 * k, f32(3.0))
+    assert (r1.qmin, r1.qmax) == (-1.0, 1.0)
+
+
+def test_range_update_one_step_by_hand():
+    r = Range.new(eta=0.75, symmetric=True)
+    oracle.range_update(r, -8, 16, f32(0.25))              # q^0 = (-2, 4)
+    oracle.range_update(r, -16, 40, f32(0.25))             # g = (-4, 10)
+    # (1-0.75)*(-4) + 0.75*(-2) = -2.5 ; 0.25*10 + 0.75*4 = 5.5  (all exact in fp32)
+    assert (r.qmin, r.qmax) == (-2.5, 5.5)
+    assert f32(r.scale) == f32(5.5) / f32(127) and r.zero_point == 0
+
+
+def test_range_update_constant_statistics_is_a_fixed_point():
+    r = Range.new(eta=0.9)
+    oracle.range_update(r, -10, 10, f32(1.0))
+    oracle.range_update(r, -1000, 3000, f32(0.01))
+    for _ in range(400):
+        oracle.range_update(r, -1000, 3000, f32(0.01))
+    assert abs(r.qmin + 10.0) < 1e-4 and abs(r.qmax - 30.0) < 1e-4
+
+
+@pytest.mark.parametrize("ratio,eta", [(1.05, 0.9), (0.8, 0.9), (1.3, 0.5), (0.5, 0.3)])
+def test_range_update_geometric_drift_closed_form(ratio, eta):
+    """Statistics g_t = g_0 r^t.  The recursion q^{t+1} = (1-eta) g_t + eta q^t with q^0 = g_0 solves to
+    q^t = eta^t g_0 + (1-eta) g_0 (eta^t - r^t)/(eta - r)."""
+    r = Range.new(eta=eta)
+    g0 = 2.0
+    oracle.range_update(r, -1000, 1000, f32(g0 / 1000))     # q^0 = (-2, 2)
+    for t in range(0, 30):
+        # state now holds q^t; feed the statistics of tensor t
+        want = eta ** t * g0 + (1 - eta) * g0 * (eta ** t - ratio ** t) / (eta - ratio)
+        assert abs(r.qmax - want) <= 1e-5 * abs(want), (t, r.qmax, want)
+        assert abs(r.qmin + want) <= 1e-5 * abs(want)
+        oracle.range_update(r, -1000, 1000, f32(g0 * ratio ** t / 1000))
+    if ratio > eta and ratio > 1:
+        # growing tensors: the in-hindsight range settles at (1-eta)/(r-eta) of the current one
+        assert abs(r.qmax / (g0 * ratio ** 30) - (1 - eta) / (ratio - eta)) < 0.02
+
+
+# --------------------------------------------------------------------------- P5
+def test_static_with_current_range_equals_dynamic():
+    """Static and dynamic quantization differ only in when the range is known (Sec. 3.2):
+    handing the static path the tensor's own min-max must reproduce the dynamic result."""
+    g = np.random.default_rng(6)
+    for sym in (0, 1):
+        c = (g.laplace(0, 300, 20000)).astype(np.int32)
+        a_scale = f32(3e-4)
+        dyn = oracle.quantize_dynamic(c, a_scale, sym, *((-127, 127) if sym else (-128, 127)))
+        r = Range.new(symmetric=bool(sym))
+        oracle.range_update(r, dyn["acc_min"], dyn["acc_max"], a_scale)
+        st = oracle.quantize_static(c, a_scale, r)
+        assert np.array_equal(st["codes"], dyn["codes"])
+        assert (st["scale"], st["zero_point"]) == (dyn["scale"], dyn["zero_point"])
+        assert st["clip_lo"] == dyn["clip_lo"] == 0 and st["clip_hi"] == dyn["clip_hi"] == 0
+        # the extreme values land on the ends of the grid that the range touches
+        codes = dyn["codes"].astype(int)
+        if sym:
+            assert max(abs(codes.min()), abs(codes.max())) == 127
+        else:
+            assert codes.min() == -128 and codes.max() == 127
+
+
+def test_in_hindsight_sequence_uses_previous_range():
+    """At iteration t >= 1 the codes must come from q^t, which depends only on tensors 0..t-1."""
+    g = np.random.default_rng(7)
+    a_scale = f32(1e-3)
+    tensors = [(g.normal(0, 1000 * 1.5 ** t, 4096)).astype(np.int32) for t in range(4)]
+    r = Range.new(eta=0.9)
+    hist = []
+    for t, c in enumerate(tensors):
+        before = (r.scale, r.zero_point, r.initialized)
+        out = oracle.in_hindsight_step(c, a_scale, r)
+        if t == 0:
+            assert np.array_equal(out["codes"], oracle.quantize_dynamic(c, a_scale, 0, -128, 127)["codes"])
+        else:
+            want, _, _ = oracle.requant(c, a_scale, before[0], before[1], -128, 127)
+            assert np.array_equal(out["codes"], want)
+            assert out["clip_lo"] + out["clip_hi"] > 0          # growing tensors overflow yesterday's range
+        hist.append((r.qmin, r.qmax))
+    # independent replay of eq. (2)-(3) in float64
+    mn = [float(a_scale) * int(c.min()) for c in tensors]
+    q = mn[0]
+    q = 0.1 * mn[0] + 0.9 * q
+    for t in range(1, 4):
+        q = 0.1 * mn[t] + 0.9 * q
+    assert abs(hist[-1][0] - q) <= 1e-5 * abs(q)
+
+
+def test_workload_shapes_match_the_configurations():
+    import workloads as wl
+    L = wl.c2_layer()
+    assert (L.B * 56 * 56, 9 * 64, 64) == (401408, 576, 64)
+    assert wl.fused_bytes(L, "fwd") == 2 * 128 * 56 * 56 * 64 + 576 * 64
+    assert wl.dynamic_bytes(L, "fwd") - wl.fused_bytes(L, "fwd") == 8 * 128 * 56 * 56 * 64
+    assert 2 * wl.macs(L) == 2 * 401408 * 576 * 64
+    layers = wl.resnet18_layers()
+    assert len(layers) == 21
+    assert [l.Cout for l in layers if l.name.endswith("conv0")] == [64, 128, 256, 512]
+    assert wl.out_hw(layers[0]) == (112, 112) and wl.out_hw(layers[5]) == (28, 28)
+    assert abs(wl.c3_grad_scale(49) - 1e-3) < 1e-12 and wl.c3_grad_scale(0) == 1.0
