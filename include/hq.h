@@ -1,0 +1,187 @@
+/*
+ * hq.h -- C ABI of the in-hindsight quantized-training layer library for MI355X (gfx950).
+ *
+ * The library runs the three linear operations of a fully quantized layer on 8-bit codes
+ * with 32-bit accumulation (paper Sec. 3.1, Fig. 1; Sec. 3.2, Fig. 2) and quantizes each
+ * accumulator output in the kernel's epilogue, either
+ *   - statically, with the range estimated on earlier iterations, while tracking the
+ *     min/max of the current output on the side (in-hindsight min-max, Sec. 4, Sec. 4.1), or
+ *   - dynamically, by writing the 32-bit output to memory, deriving the range from it and
+ *     reading it back (Sec. 3.2, eq. (1)): the baseline whose traffic eq. (5) counts.
+ *
+ * General rules
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns all
+ *     buffers; the library allocates nothing and keeps no state between calls.
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and never synchronises with the host.  Quantizer parameters, range state and
+ *     statistics live in device memory so that a training step needs no host round trip.
+ *   - Return value: HQ_OK or a negative HQ_E_* code.  Shapes the kernels do not support are
+ *     reported (HQ_E_BADSHAPE), never padded silently.  Nothing is launched on error.
+ *   - Codes are signed 8-bit.  A real value is scale * (code - zero_point).  An unsigned grid
+ *     0..255 is stored shifted by -128 together with its zero point.
+ *   - Tensors are NHWC, row-major, densely packed, and their base pointers 16-byte aligned.
+ *   - Taps of a convolution that fall outside the image hold real zero.
+ *   - Weight operands are taken as symmetric (zero point 0); `scale` is the only field of
+ *     their hq_qparams that is read.
+ *   - Rounding is round-half-to-even in fp32; the multiplier is (s_a * s_b) / s_out with
+ *     each operation rounded once.
+ */
+#ifndef HQ_H
+#define HQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HQ_OK            0
+#define HQ_E_BADARG    (-1)   /* null / misaligned pointer, bad enum value                  */
+#define HQ_E_BADSHAPE  (-2)   /* shape outside what the kernels support (see each call)     */
+#define HQ_E_WORKSPACE (-3)   /* workspace missing or smaller than hq_workspace_bytes()     */
+#define HQ_E_HIP       (-4)   /* a HIP call failed (launch error)                           */
+
+#define HQ_LINEAR    0        /* out[M,N] = A[M,K] . W[N,K]^T ; problem: B=M, C=K, Cout=N   */
+#define HQ_CONV2D    1        /* NHWC convolution as implicit-im2col GEMM                   */
+#define HQ_DEPTHWISE 2        /* one R x S filter per channel (Cout == C), no MFMA          */
+
+/* Quantizer parameters that travel with a quantized tensor. */
+typedef struct { float scale; int32_t zero_point; } hq_qparams;
+
+/* State of one in-hindsight quantizer (Sec. 4.1).  (qmin, qmax) is the range q^t of
+ * eq. (2)-(3) in real units; qp is the quantizer derived from it and is what the fused
+ * kernels read.  Asymmetric grid: qlo..qhi = -128..127, range widened to contain 0.
+ * Symmetric grid: -127..127, scale = max(|qmin|,|qmax|)/qhi, zero point 0.                 */
+typedef struct {
+    float      qmin, qmax;
+    float      eta;           /* momentum; the paper uses 0.9 (Sec. 5.2)                     */
+    int32_t    qlo, qhi;
+    int32_t    symmetric;     /* 0 asymmetric, 1 symmetric                                   */
+    int32_t    initialized;   /* 0 until q^0 has been set from the first batch (Sec. 4.1)    */
+    hq_qparams qp;
+} hq_range;
+
+/* Online statistics of one output tensor, gathered from the accumulator before the
+ * quantization step (Sec. 4).  acc_min/acc_max are over the zero-point-corrected 32-bit
+ * accumulator outputs; one accumulator unit is worth acc_scale in real units.
+ * clip_lo/clip_hi count the outputs whose rounded code fell below qlo / above qhi
+ * (saturation ratio = (clip_lo + clip_hi) / count, Sec. 4 footnote).
+ * Kernels only ever merge into this struct; hq_stats_reset / hq_range_update empty it.      */
+typedef struct {
+    int32_t  acc_min, acc_max;
+    float    acc_scale;
+    uint32_t reserved;
+    uint64_t clip_lo, clip_hi, count;
+} hq_stats;
+
+/* Layer shape (host struct).  Linear: kind=HQ_LINEAR, B=M, C=K, Cout=N, H=W=R=S=stride=1,
+ * pad=0.  Output spatial size: OH = (H + 2*pad - R)/stride + 1, same for OW.
+ * Layouts:  X  [B][H][W][C]           dY [B][OH][OW][Cout]
+ *           W  [Cout][R][S][C]        (depthwise: [R][S][C])
+ *           Wd [C][R][S][Cout]        the same weights re-laid for hq_gemm_dgrad (depthwise: = W)
+ * Supported: C % 4 == 0 and Cout % 4 == 0 for HQ_LINEAR / HQ_CONV2D (full-rate path when the
+ * reduced channel count is a multiple of 16); C % 4 == 0 for HQ_DEPTHWISE; B*H*W and
+ * B*OH*OW below 2^31.                                                                        */
+typedef struct {
+    int32_t kind;
+    int32_t B, H, W, C;
+    int32_t R, S, stride, pad;
+    int32_t Cout;
+} hq_problem;
+
+/* Entry indices for hq_workspace_bytes. */
+#define HQ_ENTRY_FWD      0
+#define HQ_ENTRY_DGRAD    1
+#define HQ_ENTRY_WGRAD    2
+#define HQ_ENTRY_DYNAMIC_FWD   3
+#define HQ_ENTRY_DYNAMIC_DGRAD 4
+
+/* Bytes of device workspace an entry point needs for this problem (host, pure; 0 = none).
+ * Returns 0 also for an invalid problem; the entry point itself reports the error.          */
+size_t hq_workspace_bytes(int32_t entry, const hq_problem *p /* host */);
+
+/* Forward Y~ = Q_Y(X~ . W~) with in-hindsight static quantization (Sec. 3.1 forward pass;
+ * Sec. 3.2 static quantization; Sec. 4 steps 1 and 2).
+ *   X, xq    input codes and their quantizer (xq->zero_point may be non-zero)
+ *   W, wq    weight codes [Cout][R][S][C] (depthwise [R][S][C]) and their scale
+ *   wsum     int32 [Cout]: sum of the weight codes of each output channel, from
+ *            hq_weight_prepare; used to remove the input zero point
+ *   yr       range state q^t of the output quantizer, read only (must be initialized)
+ *   Y        output codes [B][OH][OW][Cout], written once
+ *   yq       out: the quantizer actually used for Y (a copy of yr->qp), so that consumers
+ *            never race with a later hq_range_update
+ *   st       statistics of this output, merged in place (min, max, clips, count) and
+ *            st->acc_scale set to xq->scale * wq->scale                                      */
+int hq_gemm_fwd(const hq_problem *p /* host */,
+                const int8_t *X, const hq_qparams *xq,
+                const int8_t *W, const hq_qparams *wq, const int32_t *wsum,
+                const hq_range *yr, int8_t *Y, hq_qparams *yq, hq_stats *st, void *stream);
+
+/* Input gradient G~_X = Q_G(G~_Y . W~^T), same epilogue as the forward pass with the
+ * gradient quantizer's own range state (Sec. 3.1 backward pass).
+ *   dY, gq   output-gradient codes [B][OH][OW][Cout] and their quantizer
+ *   Wd, wq   weights in [C][R][S][Cout] order (depthwise: [R][S][C]) and their scale
+ *   wdsum    int32 [C]: sum over (r,s,cout) of the weight codes of each input channel
+ *   gr       range state of Q_G, read only;  dX [B][H][W][C];  dxq, st as in hq_gemm_fwd    */
+int hq_gemm_dgrad(const hq_problem *p /* host */,
+                  const int8_t *dY, const hq_qparams *gq,
+                  const int8_t *Wd, const hq_qparams *wq, const int32_t *wdsum,
+                  const hq_range *gr, int8_t *dX, hq_qparams *dxq, hq_stats *st, void *stream);
+
+/* Weight gradient G_W = X~^T . G~_Y, kept in FP32 (Sec. 3.1): no quantizer, no range state.
+ *   X, xq / dY, gq   both operands may carry a non-zero zero point
+ *   dW       fp32, shaped like W: (xq->scale * gq->scale) * float(integer sum)
+ *   dW_acc   optional int32 copy of the zero-point-free integer sum (NULL to skip)
+ *   ws       workspace of hq_workspace_bytes(HQ_ENTRY_WGRAD, p) bytes, 16-byte aligned;
+ *            contents are scratch                                                            */
+int hq_gemm_wgrad(const hq_problem *p /* host */,
+                  const int8_t *X, const hq_qparams *xq,
+                  const int8_t *dY, const hq_qparams *gq,
+                  float *dW, int32_t *dW_acc, void *ws, size_t ws_bytes, void *stream);
+
+/* In-hindsight min-max update, eq. (2)-(3): folds the statistics of the tensor just
+ * produced into the range for the next iteration and re-derives r->qp.  If r is not
+ * initialized the statistics become q^0 (Sec. 4.1).  Empties *st afterwards.  With
+ * st->count == 0 the range is left as it is.  One thread; run it on the stream that
+ * produced the tensor, any time after the producing kernel.                                  */
+int hq_range_update(hq_range *r, hq_stats *st, void *stream);
+
+/* Dynamic-quantization baseline (Sec. 3.2; eq. (1); traffic of eq. (5)): pass 1 runs the
+ * same GEMM and writes every zero-point-corrected 32-bit output to `ws` while gathering
+ * min/max; a one-thread kernel derives the quantizer; pass 2 reads the 32-bit tensor back,
+ * quantizes and writes the codes.
+ *   op        HQ_ENTRY_DYNAMIC_FWD (A=X, Bw=W, bsum=wsum) or HQ_ENTRY_DYNAMIC_DGRAD
+ *             (A=dY, Bw=Wd, bsum=wdsum)
+ *   mode      HQ_DYN_CURRENT: range = min-max of this tensor, eq. (1); r's (qmin,qmax) are
+ *             touched only if r is not initialized, in which case they become q^0 (Sec. 4.1).
+ *             HQ_DYN_RUNNING: running min-max (Sec. 4.1, last paragraph): r is first moved by
+ *             eq. (2)-(3) with THIS tensor's statistics, then used to quantize it.
+ *   r         supplies the grid (qlo, qhi, symmetric) and eta; see `mode` for what is written
+ *   st        as in hq_gemm_fwd (left filled, so hq_range_update can follow)
+ *   ws        >= hq_workspace_bytes(op, p) bytes: the 32-bit round trip                     */
+#define HQ_DYN_CURRENT 0
+#define HQ_DYN_RUNNING 1
+int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p /* host */,
+                    const int8_t *A, const hq_qparams *aq,
+                    const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum,
+                    hq_range *r, int8_t *out, hq_qparams *outq, hq_stats *st,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* Empties n statistics records (min = INT32_MAX, max = INT32_MIN, counters 0). */
+int hq_stats_reset(hq_stats *st, int32_t n, void *stream);
+
+/* Weight-side preparation, once per weight update (the weight quantizer's output does not
+ * depend on the batch, Sec. 3.1): from W [Cout][R][S][C] writes the dgrad layout
+ * Wd [C][R][S][Cout] (skipped if Wd is NULL or the layer is depthwise), wsum [Cout] and
+ * wdsum [C] (each skipped if NULL).  Depthwise: wsum == wdsum == per-channel tap sum.         */
+int hq_weight_prepare(const hq_problem *p /* host */, const int8_t *W,
+                      int8_t *Wd, int32_t *wsum, int32_t *wdsum, void *stream);
+
+/* Static text for a return code (host pointer, never NULL). */
+const char *hq_error_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HQ_H */

@@ -1,0 +1,284 @@
+// C-ABI entry points of the hq library: argument checks, dispatch, and the small kernels
+// around the GEMMs (range update, statistics reset, dynamic-baseline middle and second
+// pass, weight-side preparation).
+#include "hq_device.h"
+#include "hq_internal.h"
+
+namespace {
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+inline int launch_status() { return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP; }
+
+// ---------------------------------------------------------------------------------------
+// eq. (2)-(3): q <- (1 - eta) * g + eta * q, each product and the sum rounded once.
+// ---------------------------------------------------------------------------------------
+__device__ inline void ema_update(hq_range *r, float gmin, float gmax)
+{
+    if (!r->initialized) {
+        r->qmin = gmin; r->qmax = gmax; r->initialized = 1;
+    } else {
+        const float w = __fsub_rn(1.0f, r->eta);
+        r->qmin = __fadd_rn(__fmul_rn(w, gmin), __fmul_rn(r->eta, r->qmin));
+        r->qmax = __fadd_rn(__fmul_rn(w, gmax), __fmul_rn(r->eta, r->qmax));
+    }
+    r->qp = hq_qparams_from_range(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi);
+}
+
+__device__ inline void stats_clear(hq_stats *st)
+{
+    st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
+    st->clip_lo = 0; st->clip_hi = 0; st->count = 0;
+}
+
+__global__ void range_update_kernel(hq_range *r, hq_stats *st)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    if (st->count != 0) {
+        const float gmin = __fmul_rn(st->acc_scale, (float)st->acc_min);
+        const float gmax = __fmul_rn(st->acc_scale, (float)st->acc_max);
+        ema_update(r, gmin, gmax);
+    }
+    stats_clear(st);
+}
+
+__global__ void stats_reset_kernel(hq_stats *st, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) stats_clear(st + i);
+}
+
+// Dynamic baseline, between the passes: the quantizer of the tensor just written.
+__global__ void dynamic_mid_kernel(int mode, hq_range *r, const hq_stats *st, hq_qparams *outq)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const float gmin = __fmul_rn(st->acc_scale, (float)st->acc_min);
+    const float gmax = __fmul_rn(st->acc_scale, (float)st->acc_max);
+    if (mode == HQ_DYN_RUNNING) {
+        ema_update(r, gmin, gmax);                 // running min-max: this tensor moves the range first
+        *outq = r->qp;
+    } else {
+        if (!r->initialized) ema_update(r, gmin, gmax);          // q^0 = min-max of the first batch
+        *outq = hq_qparams_from_range(gmin, gmax, r->symmetric, r->qlo, r->qhi);   // eq. (1)
+    }
+}
+
+// Dynamic baseline, pass 2: load the 32-bit outputs back (eq. (5), "load acc output"),
+// quantize, store codes.  16 outputs per thread: 64 B in, 16 B out.
+__global__ __launch_bounds__(HQ_THREADS) void dynamic_pass2_kernel(const int32_t *__restrict__ c, size_t n,
+                                                                   const hq_stats *st, const hq_range *r,
+                                                                   const hq_qparams *outq, int8_t *__restrict__ out,
+                                                                   hq_stats *st_out)
+{
+    __shared__ int red[4 * (HQ_THREADS / 64)];
+    const HqRequant rq = hq_make_requant(st->acc_scale, *outq, r->qlo, r->qhi);
+    unsigned nlo = 0, nhi = 0;
+    const size_t groups = n / 16, step = (size_t)gridDim.x * blockDim.x;
+    for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += step) {
+        const v4i *src = reinterpret_cast<const v4i *>(c) + 4 * g;
+        v4i packed;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            v4i v = src[k];
+            packed[k] = (int)hq_pack4(hq_requant(v[0], rq, nlo, nhi), hq_requant(v[1], rq, nlo, nhi),
+                                      hq_requant(v[2], rq, nlo, nhi), hq_requant(v[3], rq, nlo, nhi));
+        }
+        reinterpret_cast<v4i *>(out)[g] = packed;
+    }
+    // tail (n % 16 elements), one thread
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        for (size_t i = groups * 16; i < n; i++) out[i] = (int8_t)hq_requant(c[i], rq, nlo, nhi);
+    hq_block_stats_commit(INT_MAX, INT_MIN, nlo, nhi, st_out, red);
+}
+
+// Weight-side preparation: per-output-channel and per-input-channel code sums and the
+// [C][R][S][Cout] re-layout.  Small tensors, run once per weight update: plain kernels.
+__global__ void weight_rowsum_kernel(const int8_t *W, int rows, int len, int32_t *sum)
+{
+    // one wavefront per row
+    int row = blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    int s = 0;
+    for (int i = lane; i < len; i += 64) s += W[(size_t)row * len + i];
+    s = hq_wave_reduce(s, HqAdd());
+    if (lane == 0) sum[row] = s;
+}
+
+__global__ void weight_colsum_kernel(const int8_t *W, int rows, int taps, int C, int32_t *sum)
+{
+    // sum over (row, tap) for each channel c of W[rows][taps][C]
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    int s = 0;
+    for (int i = 0; i < rows * taps; i++) s += W[(size_t)i * C + c];
+    sum[c] = s;
+}
+
+__global__ void weight_relayout_kernel(const int8_t *W, int Cout, int taps, int C, int8_t *Wd)
+{
+    // Wd[c][tap][n] = W[n][tap][c]
+    size_t total = (size_t)Cout * taps * C;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        int n = (int)(i % Cout); size_t t = i / Cout; int tap = (int)(t % taps); int c = (int)(t / taps);
+        Wd[i] = W[((size_t)n * taps + tap) * C + c];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Argument checks
+// ---------------------------------------------------------------------------------------
+int check_problem(const hq_problem *p)
+{
+    if (!p) return HQ_E_BADARG;
+    if (p->kind != HQ_LINEAR && p->kind != HQ_CONV2D && p->kind != HQ_DEPTHWISE) return HQ_E_BADARG;
+    if (p->B <= 0 || p->H <= 0 || p->W <= 0 || p->C <= 0 || p->Cout <= 0 || p->R <= 0 || p->S <= 0 ||
+        p->stride <= 0 || p->pad < 0) return HQ_E_BADSHAPE;
+    if (p->kind == HQ_LINEAR && (p->H != 1 || p->W != 1 || p->R != 1 || p->S != 1 || p->stride != 1 || p->pad != 0))
+        return HQ_E_BADSHAPE;
+    if (p->kind == HQ_DEPTHWISE && p->Cout != p->C) return HQ_E_BADSHAPE;
+    if (p->H + 2 * p->pad < p->R || p->W + 2 * p->pad < p->S) return HQ_E_BADSHAPE;
+    if (p->pad >= p->R || p->pad >= p->S) return HQ_E_BADSHAPE;       // every output has a real tap
+    if ((p->C % 4) != 0 || (p->Cout % 4) != 0) return HQ_E_BADSHAPE;
+    const long OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
+    const long lim = 0x7fffffffL;
+    if ((long)p->B * p->H * p->W >= lim || (long)p->B * OH * OW >= lim) return HQ_E_BADSHAPE;
+    if ((long)p->B * p->H * p->W * p->C >= lim * 2 || (long)p->B * OH * OW * p->Cout >= lim * 2) return HQ_E_BADSHAPE;
+    if ((long)p->R * p->S * p->C * (p->kind == HQ_DEPTHWISE ? 1 : p->Cout) >= lim) return HQ_E_BADSHAPE;
+    return HQ_OK;
+}
+
+size_t out_elems(const hq_problem *p, bool dgrad)
+{
+    const size_t OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
+    return dgrad ? (size_t)p->B * p->H * p->W * p->C : (size_t)p->B * OH * OW * p->Cout;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *hq_error_string(int code)
+{
+    switch (code) {
+    case HQ_OK: return "ok";
+    case HQ_E_BADARG: return "bad argument (null or misaligned pointer, bad enum)";
+    case HQ_E_BADSHAPE: return "unsupported shape";
+    case HQ_E_WORKSPACE: return "workspace missing or too small";
+    case HQ_E_HIP: return "HIP launch failed";
+    default: return "unknown hq error code";
+    }
+}
+
+size_t hq_workspace_bytes(int32_t entry, const hq_problem *p)
+{
+    if (check_problem(p) != HQ_OK) return 0;
+    switch (entry) {
+    case HQ_ENTRY_WGRAD: return hq_wgrad_workspace_bytes(p);
+    case HQ_ENTRY_DYNAMIC_FWD: return 4 * out_elems(p, false);
+    case HQ_ENTRY_DYNAMIC_DGRAD: return 4 * out_elems(p, true);
+    default: return 0;
+    }
+}
+
+static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
+                       const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out,
+                       int32_t *out32, hq_qparams *outq, hq_stats *st, void *stream)
+{
+    int rc = check_problem(p);
+    if (rc != HQ_OK) return rc;
+    if (!A || !aq || !Bw || !bq || !bsum || !range || !st || (!out && !out32) || (out && !outq)) return HQ_E_BADARG;
+    if (misaligned(A, 16) || misaligned(Bw, 16) || misaligned(bsum, 16) || misaligned(out, 16) ||
+        misaligned(out32, 16) || misaligned(st, 8) || misaligned(range, 4) || misaligned(aq, 4) ||
+        misaligned(bq, 4) || misaligned(outq, 4)) return HQ_E_BADARG;
+    if (p->kind == HQ_DEPTHWISE)
+        return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
+    return hq_launch_gemm(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
+}
+
+int hq_gemm_fwd(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *W, const hq_qparams *wq,
+                const int32_t *wsum, const hq_range *yr, int8_t *Y, hq_qparams *yq, hq_stats *st, void *stream)
+{
+    return gemm_common(p, 0, X, xq, W, wq, wsum, yr, Y, nullptr, yq, st, stream);
+}
+
+int hq_gemm_dgrad(const hq_problem *p, const int8_t *dY, const hq_qparams *gq, const int8_t *Wd, const hq_qparams *wq,
+                  const int32_t *wdsum, const hq_range *gr, int8_t *dX, hq_qparams *dxq, hq_stats *st, void *stream)
+{
+    return gemm_common(p, 1, dY, gq, Wd, wq, wdsum, gr, dX, nullptr, dxq, st, stream);
+}
+
+int hq_gemm_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY, const hq_qparams *gq,
+                  float *dW, int32_t *dW_acc, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_problem(p);
+    if (rc != HQ_OK) return rc;
+    if (!X || !xq || !dY || !gq || !dW) return HQ_E_BADARG;
+    if (misaligned(X, 16) || misaligned(dY, 16) || misaligned(dW, 16) || misaligned(dW_acc, 16) ||
+        misaligned(xq, 4) || misaligned(gq, 4)) return HQ_E_BADARG;
+    const size_t need = hq_wgrad_workspace_bytes(p);
+    if (need && (!ws || ws_bytes < need || misaligned(ws, 16))) return HQ_E_WORKSPACE;
+    if (p->kind == HQ_DEPTHWISE)
+        return hq_launch_depthwise_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream));
+    return hq_launch_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream));
+}
+
+int hq_range_update(hq_range *r, hq_stats *st, void *stream)
+{
+    if (!r || !st || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
+    hipLaunchKernelGGL(range_update_kernel, dim3(1), dim3(64), 0, as_stream(stream), r, st);
+    return launch_status();
+}
+
+int hq_stats_reset(hq_stats *st, int32_t n, void *stream)
+{
+    if (!st || n <= 0 || misaligned(st, 8)) return HQ_E_BADARG;
+    hipLaunchKernelGGL(stats_reset_kernel, dim3((n + 63) / 64), dim3(64), 0, as_stream(stream), st, n);
+    return launch_status();
+}
+
+int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p, const int8_t *A, const hq_qparams *aq,
+                    const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum, hq_range *r, int8_t *out,
+                    hq_qparams *outq, hq_stats *st, void *ws, size_t ws_bytes, void *stream)
+{
+    if (op != HQ_ENTRY_DYNAMIC_FWD && op != HQ_ENTRY_DYNAMIC_DGRAD) return HQ_E_BADARG;
+    if (mode != HQ_DYN_CURRENT && mode != HQ_DYN_RUNNING) return HQ_E_BADARG;
+    int rc = check_problem(p);
+    if (rc != HQ_OK) return rc;
+    if (!out || !outq || !r) return HQ_E_BADARG;
+    const bool dgrad = op == HQ_ENTRY_DYNAMIC_DGRAD;
+    const size_t n = out_elems(p, dgrad);
+    if (!ws || ws_bytes < 4 * n || misaligned(ws, 16)) return HQ_E_WORKSPACE;
+    int32_t *c32 = static_cast<int32_t *>(ws);
+    // pass 1: GEMM, 32-bit outputs to memory, min/max on the way
+    rc = gemm_common(p, dgrad ? 1 : 0, A, aq, Bw, bq, bsum, r, nullptr, c32, outq, st, stream);
+    if (rc != HQ_OK) return rc;
+    hipLaunchKernelGGL(dynamic_mid_kernel, dim3(1), dim3(64), 0, as_stream(stream), mode, r, st, outq);
+    // pass 2: read back, quantize, store codes
+    size_t groups = n / 16;
+    unsigned blocks = (unsigned)((groups + HQ_THREADS - 1) / HQ_THREADS);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 256u * 16u) blocks = 256u * 16u;
+    hipLaunchKernelGGL(dynamic_pass2_kernel, dim3(blocks), dim3(HQ_THREADS), 0, as_stream(stream),
+                       c32, n, st, r, outq, out, st);
+    return launch_status();
+}
+
+int hq_weight_prepare(const hq_problem *p, const int8_t *W, int8_t *Wd, int32_t *wsum, int32_t *wdsum, void *stream)
+{
+    int rc = check_problem(p);
+    if (rc != HQ_OK) return rc;
+    if (!W) return HQ_E_BADARG;
+    hipStream_t s = as_stream(stream);
+    const int taps = p->R * p->S;
+    if (p->kind == HQ_DEPTHWISE) {
+        if (wsum) hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64), dim3(64), 0, s, W, 1, taps, p->C, wsum);
+        if (wdsum) hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64), dim3(64), 0, s, W, 1, taps, p->C, wdsum);
+        return launch_status();
+    }
+    if (wsum) hipLaunchKernelGGL(weight_rowsum_kernel, dim3((p->Cout + 3) / 4), dim3(256), 0, s, W, p->Cout, taps * p->C, wsum);
+    if (wdsum) hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64), dim3(64), 0, s, W, p->Cout, taps, p->C, wdsum);
+    if (Wd) hipLaunchKernelGGL(weight_relayout_kernel, dim3(1024), dim3(256), 0, s, W, p->Cout, taps, p->C, Wd);
+    return launch_status();
+}
+
+} // extern "C"

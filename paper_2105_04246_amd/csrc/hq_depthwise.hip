@@ -1,0 +1,236 @@
+// Depthwise convolution (one R x S filter per channel) with the same fused epilogue as the
+// GEMMs.  No matrix cores: per output there are only R*S multiply-accumulates against ~2
+// bytes of traffic, so the layer is bound by memory, not arithmetic (the depthwise rows of
+// the paper's Table 5).  Forward and input gradient are the same gather with the tap offsets
+// mirrored; the weight gradient reduces over all pixels per (tap, channel).
+#include "hq_device.h"
+#include "hq_internal.h"
+
+namespace {
+
+struct DwArgs {
+    const int8_t *A, *Wt;
+    const int32_t *wsum;
+    const hq_qparams *aq, *bq;
+    const hq_range *range;
+    int8_t *out8;
+    int32_t *out32;
+    hq_qparams *outq;
+    hq_stats *st;
+    int M, C;                      // output pixels, channels
+    int R, S, Hs, Ws, Ho, Wo, stride, pad, dgrad;
+};
+
+__device__ inline int sbyte(int v, int k) { return (v << (24 - 8 * k)) >> 24; }
+
+// One thread: one output pixel, four consecutive channels (one 32-bit word of codes).
+__global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_kernel(const DwArgs a)
+{
+    __shared__ int red[4 * (HQ_THREADS / 64)];
+    const int c4n = a.C >> 2;
+    const size_t total = (size_t)a.M * c4n;
+    const int za = a.aq->zero_point;
+    const int fill = (za & 0xff) * 0x01010101;
+    const bool fused = a.out32 == nullptr;
+    const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
+    HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
+    if (fused) rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
+    int mn = INT_MAX, mx = INT_MIN;
+    unsigned nlo = 0, nhi = 0;
+
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(idx % c4n) * 4;
+        const int m = (int)(idx / c4n);
+        const int x = m % a.Wo, y = (m / a.Wo) % a.Ho, b = m / (a.Wo * a.Ho);
+        const int8_t *img = a.A + (size_t)b * a.Hs * a.Ws * a.C;
+        const int y0 = a.dgrad ? y + a.pad : y * a.stride - a.pad;
+        const int x0 = a.dgrad ? x + a.pad : x * a.stride - a.pad;
+        int acc[4] = {0, 0, 0, 0};
+        for (int r = 0; r < a.R; r++) {
+            for (int s = 0; s < a.S; s++) {
+                int iy, ix; bool ok = true;
+                if (!a.dgrad) { iy = y0 + r; ix = x0 + s; }
+                else {
+                    iy = y0 - r; ix = x0 - s;
+                    if (a.stride != 1) {
+                        ok = iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
+                        iy /= a.stride; ix /= a.stride;
+                    }
+                }
+                ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
+                const int xv = ok ? *reinterpret_cast<const int *>(img + ((size_t)iy * a.Ws + ix) * a.C + c) : fill;
+                const int wv = *reinterpret_cast<const int *>(a.Wt + (size_t)(r * a.S + s) * a.C + c);
+#pragma unroll
+                for (int e = 0; e < 4; e++) acc[e] += sbyte(xv, e) * sbyte(wv, e);
+            }
+        }
+        const v4i ws = *reinterpret_cast<const v4i *>(a.wsum + c);
+        int q[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int cv = acc[e] - za * ws[e];
+            mn = min(mn, cv); mx = max(mx, cv);
+            q[e] = cv;
+        }
+        if (fused) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) q[e] = hq_requant(q[e], rq, nlo, nhi);
+            *reinterpret_cast<unsigned *>(a.out8 + (size_t)m * a.C + c) = hq_pack4(q[0], q[1], q[2], q[3]);
+        } else {
+            v4i v = {q[0], q[1], q[2], q[3]};
+            *reinterpret_cast<v4i *>(a.out32 + (size_t)m * a.C + c) = v;
+        }
+    }
+    hq_block_stats_commit(mn, mx, nlo, nhi, a.st, red);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        a.st->acc_scale = acc_scale;
+        atomicAdd((unsigned long long *)&a.st->count, (unsigned long long)a.M * (unsigned long long)a.C);
+        if (fused) *a.outq = a.range->qp;
+    }
+}
+
+// Weight gradient: acc[tap][c] = sum_m Xg[m][tap][c] * G[m][c], plus the column sums that
+// remove the zero points.  Each workgroup takes a run of pixels; a thread owns four channels
+// and strides over the run; partial sums meet in LDS and leave with one atomic per value.
+constexpr int DW_MAX_TAPS = 9;
+
+struct DwWgradArgs {
+    const int8_t *X, *G;
+    const hq_qparams *xq;
+    int32_t *acc, *gsum, *xsum;
+    int M, C, R, S, H, W, OH, OW, stride, pad;
+    int m_per_block;
+    int CT;                        // channels per workgroup (multiple of 4, <= 256)
+};
+
+__global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_wgrad_kernel(const DwWgradArgs a)
+{
+    extern __shared__ int lds[];                 // [taps][CT] acc, [CT] gsum, [taps][CT] xsum
+    const int taps = a.R * a.S, CT = a.CT;
+    const int ct0 = blockIdx.y * CT, ct = min(CT, a.C - ct0);      // this workgroup's channel tile
+    const int words = (2 * taps + 1) * CT;
+    for (int i = threadIdx.x; i < words; i += blockDim.x) lds[i] = 0;
+    __syncthreads();
+    const int zx = a.xq->zero_point;
+    const int fill = (zx & 0xff) * 0x01010101;
+    const int lanes_per_pixel = ct >> 2;                           // <= 64
+    const int pixels_per_pass = HQ_THREADS / lanes_per_pixel;
+    const int cg = threadIdx.x % lanes_per_pixel, prow = threadIdx.x / lanes_per_pixel;
+    const int cl = cg * 4, c = ct0 + cl;
+    const int m_begin = blockIdx.x * a.m_per_block, m_end = min(a.M, m_begin + a.m_per_block);
+    if (prow < pixels_per_pass) {
+        int acc[DW_MAX_TAPS][4], xs[DW_MAX_TAPS][4], gs[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < DW_MAX_TAPS; t++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) { acc[t][e] = 0; xs[t][e] = 0; }
+        for (int m = m_begin + prow; m < m_end; m += pixels_per_pass) {
+            const int ow = m % a.OW, oh = (m / a.OW) % a.OH, b = m / (a.OW * a.OH);
+            const int gv = *reinterpret_cast<const int *>(a.G + (size_t)m * a.C + c);
+            int g[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) { g[e] = sbyte(gv, e); gs[e] += g[e]; }
+#pragma unroll
+            for (int t = 0; t < DW_MAX_TAPS; t++) {
+                if (t < taps) {
+                    const int r = t / a.S, s = t % a.S;
+                    const int iy = oh * a.stride - a.pad + r, ix = ow * a.stride - a.pad + s;
+                    const bool ok = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+                    const int xv = ok ? *reinterpret_cast<const int *>(a.X + (((size_t)b * a.H + iy) * a.W + ix) * a.C + c) : fill;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) { const int x = sbyte(xv, e); acc[t][e] += x * g[e]; xs[t][e] += x; }
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < DW_MAX_TAPS; t++)
+            if (t < taps)
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    atomicAdd(&lds[t * CT + cl + e], acc[t][e]);
+                    atomicAdd(&lds[(taps + 1 + t) * CT + cl + e], xs[t][e]);
+                }
+#pragma unroll
+        for (int e = 0; e < 4; e++) atomicAdd(&lds[taps * CT + cl + e], gs[e]);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < words; i += blockDim.x) {
+        const int v = lds[i];
+        const int row = i / CT, col = i % CT;
+        if (v == 0 || col >= ct) continue;
+        if (row < taps) atomicAdd(a.acc + row * a.C + ct0 + col, v);
+        else if (row == taps) atomicAdd(a.gsum + ct0 + col, v);
+        else atomicAdd(a.xsum + (row - taps - 1) * a.C + ct0 + col, v);
+    }
+}
+
+__global__ void dw_zero_kernel(int32_t *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+__global__ void dw_wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, const int32_t *xsum,
+                                         const hq_qparams *xq, const hq_qparams *gq, unsigned M, int K, int C,
+                                         float *dW, int32_t *dW_acc)
+{
+    const unsigned zx = (unsigned)xq->zero_point, zg = (unsigned)gq->zero_point;
+    const float s = __fmul_rn(xq->scale, gq->scale);
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    const unsigned c = (unsigned)acc[k] - zx * (unsigned)gsum[k % C] - zg * (unsigned)xsum[k] + M * zx * zg;
+    if (dW_acc) dW_acc[k] = (int)c;
+    dW[k] = __fmul_rn(s, (float)(int)c);
+}
+
+size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+} // namespace
+
+int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
+                        const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
+                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
+{
+    const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
+    DwArgs a;
+    a.A = A; a.Wt = Wt; a.wsum = wsum; a.aq = aq; a.bq = bq; a.range = range;
+    a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
+    a.C = p->C; a.R = p->R; a.S = p->S; a.stride = p->stride; a.pad = p->pad; a.dgrad = dgrad;
+    if (!dgrad) { a.M = p->B * OH * OW; a.Hs = p->H; a.Ws = p->W; a.Ho = OH; a.Wo = OW; }
+    else        { a.M = p->B * p->H * p->W; a.Hs = OH; a.Ws = OW; a.Ho = p->H; a.Wo = p->W; }
+    const size_t total = (size_t)a.M * (a.C / 4);
+    size_t blocks = (total + HQ_THREADS - 1) / HQ_THREADS;
+    if (blocks > 256u * 64u) blocks = 256u * 64u;
+    hipLaunchKernelGGL(hq_depthwise_kernel, dim3((unsigned)blocks), dim3(HQ_THREADS), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+}
+
+int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
+                              const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream)
+{
+    if (p->R * p->S > DW_MAX_TAPS) return HQ_E_BADSHAPE;
+    const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
+    const int taps = p->R * p->S;
+    const size_t K = (size_t)taps * p->C;
+    DwWgradArgs a;
+    a.X = X; a.G = dY; a.xq = xq;
+    char *w = static_cast<char *>(ws);
+    a.acc = reinterpret_cast<int32_t *>(w);
+    a.gsum = reinterpret_cast<int32_t *>(w + align16(4 * K));
+    a.xsum = reinterpret_cast<int32_t *>(w + align16(4 * K) + align16(4 * (size_t)p->C));
+    a.M = p->B * OH * OW; a.C = p->C; a.R = p->R; a.S = p->S; a.H = p->H; a.W = p->W; a.OH = OH; a.OW = OW;
+    a.stride = p->stride; a.pad = p->pad;
+    const size_t ws_words = hq_wgrad_workspace_bytes(p) / 4;
+    hipLaunchKernelGGL(dw_zero_kernel, dim3(16), dim3(256), 0, stream, a.acc, ws_words);
+    a.CT = p->C < 256 ? p->C : 256;
+    const int ctiles = (p->C + a.CT - 1) / a.CT;
+    int blocks = (2048 + ctiles - 1) / ctiles;
+    a.m_per_block = (a.M + blocks - 1) / blocks;
+    if (a.m_per_block < 1) a.m_per_block = 1;
+    blocks = (a.M + a.m_per_block - 1) / a.m_per_block;
+    const size_t lds_bytes = (size_t)(2 * taps + 1) * a.CT * 4;       // at most 19 KiB
+    hipLaunchKernelGGL(hq_depthwise_wgrad_kernel, dim3((unsigned)blocks, (unsigned)ctiles), dim3(HQ_THREADS),
+                       lds_bytes, stream, a);
+    hipLaunchKernelGGL(dw_wgrad_finalize_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream,
+                       a.acc, a.gsum, a.xsum, xq, gq, (unsigned)a.M, (int)K, p->C, dW, dW_acc);
+    return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+}

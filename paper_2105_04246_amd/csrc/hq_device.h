@@ -1,0 +1,121 @@
+// Device-side helpers shared by the HIP kernels of the hq library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <limits.h>
+#include "../../include/hq.h"
+
+typedef int v4i  __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+#define HQ_THREADS 256                     // every compute kernel runs 4 wavefronts of 64 lanes
+
+// ---------------------------------------------------------------------------------------
+// Quantizer arithmetic.  Each fp32 operation rounds once (no contraction), so that the
+// result is a function of the operands alone.
+// ---------------------------------------------------------------------------------------
+
+// Quantizer of a range (qmin, qmax): asymmetric grids are widened to contain real zero.
+__device__ inline hq_qparams hq_qparams_from_range(float qmin, float qmax, int symmetric, int qlo, int qhi)
+{
+    hq_qparams q;
+    if (symmetric) {
+        float amax = fmaxf(fabsf(qmin), fabsf(qmax));
+        q.scale = amax > 0.0f ? __fdiv_rn(amax, (float)qhi) : 1.0f;
+        q.zero_point = 0;
+        return q;
+    }
+    float lo = fminf(qmin, 0.0f), hi = fmaxf(qmax, 0.0f);
+    float width = __fsub_rn(hi, lo);
+    float s = width > 0.0f ? __fdiv_rn(width, (float)(qhi - qlo)) : 1.0f;
+    float z = rintf(__fsub_rn((float)qlo, __fdiv_rn(lo, s)));
+    z = fminf(fmaxf(z, (float)qlo), (float)qhi);
+    q.scale = s;
+    q.zero_point = (int)z;
+    return q;
+}
+
+// Everything the epilogue needs to turn a zero-point-corrected accumulator into a code.
+struct HqRequant {
+    float mult;        // (s_a * s_b) / s_out
+    float flo, fhi;    // grid bounds relative to the zero point, as floats
+    int   z;
+};
+
+__device__ inline HqRequant hq_make_requant(float acc_scale, hq_qparams out, int qlo, int qhi)
+{
+    HqRequant r;
+    r.mult = __fdiv_rn(acc_scale, out.scale);
+    r.flo = (float)(qlo - out.zero_point);
+    r.fhi = (float)(qhi - out.zero_point);
+    r.z = out.zero_point;
+    return r;
+}
+
+// One fp32 multiply, round half to even, clamp in float, then the zero point.
+__device__ inline int hq_requant(int c, const HqRequant &q, unsigned &nlo, unsigned &nhi)
+{
+    float r = rintf(__fmul_rn((float)c, q.mult));
+    nlo += (r < q.flo) ? 1u : 0u;
+    nhi += (r > q.fhi) ? 1u : 0u;
+    r = fminf(fmaxf(r, q.flo), q.fhi);
+    return (int)r + q.z;
+}
+
+__device__ inline unsigned hq_pack4(int a, int b, int c, int d)
+{
+    return (unsigned)(a & 0xff) | ((unsigned)(b & 0xff) << 8) | ((unsigned)(c & 0xff) << 16) | ((unsigned)d << 24);
+}
+
+// ---------------------------------------------------------------------------------------
+// Wavefront and workgroup reductions for the online statistics.
+// ---------------------------------------------------------------------------------------
+
+// Exchange with the lane whose index differs in bit `k` (k < 32: ds_swizzle inside each
+// half of the wavefront; k == 32: across the halves).
+template <int K> __device__ inline int hq_lane_xor(int v)
+{
+    if (K < 32) return __builtin_amdgcn_ds_swizzle(v, (K << 10) | 0x1f);
+    return __shfl_xor(v, 32);
+}
+
+template <typename Op> __device__ inline int hq_wave_reduce(int v, Op op)
+{
+    v = op(v, hq_lane_xor<1>(v));
+    v = op(v, hq_lane_xor<2>(v));
+    v = op(v, hq_lane_xor<4>(v));
+    v = op(v, hq_lane_xor<8>(v));
+    v = op(v, hq_lane_xor<16>(v));
+    v = op(v, hq_lane_xor<32>(v));
+    return v;
+}
+
+struct HqMin { __device__ int operator()(int a, int b) const { return a < b ? a : b; } };
+struct HqMax { __device__ int operator()(int a, int b) const { return a > b ? a : b; } };
+struct HqAdd { __device__ int operator()(int a, int b) const { return a + b; } };
+
+// Merges one workgroup's statistics into the tensor's record: wavefront reduction, a
+// second level through LDS, then one atomic per field from one lane.  `red` is LDS space
+// for 4 * (HQ_THREADS / 64) ints.  Must be called by all HQ_THREADS threads.
+__device__ inline void hq_block_stats_commit(int mn, int mx, unsigned nlo, unsigned nhi,
+                                             hq_stats *st, int *red)
+{
+    mn = hq_wave_reduce(mn, HqMin());
+    mx = hq_wave_reduce(mx, HqMax());
+    nlo = (unsigned)hq_wave_reduce((int)nlo, HqAdd());
+    nhi = (unsigned)hq_wave_reduce((int)nhi, HqAdd());
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    constexpr int NW = HQ_THREADS / 64;
+    if (lane == 0) { red[wave] = mn; red[NW + wave] = mx; red[2 * NW + wave] = (int)nlo; red[3 * NW + wave] = (int)nhi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long lo = 0, hi = 0;
+        for (int w = 0; w < NW; w++) {
+            mn = min(mn, red[w]); mx = max(mx, red[NW + w]);
+            lo += (unsigned)red[2 * NW + w]; hi += (unsigned)red[3 * NW + w];
+        }
+        if (mn <= mx) { atomicMin(&st->acc_min, mn); atomicMax(&st->acc_max, mx); }
+        if (lo) atomicAdd((unsigned long long *)&st->clip_lo, lo);
+        if (hi) atomicAdd((unsigned long long *)&st->clip_hi, hi);
+    }
+}

@@ -1,0 +1,20 @@
+// Host-side launchers shared between the translation units of the hq library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "../../include/hq.h"
+
+int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
+                   const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
+                   int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+
+int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
+                        const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
+                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+
+size_t hq_wgrad_workspace_bytes(const hq_problem *p);
+
+int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
+                    const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream);
+
+int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
+                              const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream);

@@ -1,0 +1,256 @@
+"""GPU parity: the HIP library (through its C-ABI binding) against the CPU oracle, element by
+element, on the same seeded inputs.  Integer results (codes, accumulators, min/max, clip
+counts) must match bit for bit; the fp32 range state within 1e-6 relative."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H(hq):
+    import hq_harness
+    return hq_harness
+
+
+def rand_layer_inputs(L, seed, x_asym=True, g_asym=False):
+    g = np.random.default_rng(seed)
+    X = wl.relu_activation(g, wl.in_shape(L)) if x_asym else \
+        wl.to_symmetric_codes(g.standard_normal(wl.in_shape(L), dtype=np.float32), 3.0 / 127)
+    W = wl.he_weight(g, L)
+    if g_asym:
+        dY = wl.to_asymmetric_codes(g.laplace(0, 1e-3, wl.out_shape(L)).astype(np.float32) + np.float32(4e-4))
+    else:
+        dY = wl.laplace_gradient(g, wl.out_shape(L), 1e-3)
+    return X, W, dY
+
+
+# ---------------------------------------------------------------------------------------
+# Config 1: single linear layer, 4 iterations, forward + dgrad + wgrad
+# ---------------------------------------------------------------------------------------
+def test_c1_linear_four_iterations(H, hq):
+    y_track = H.TensorTrack(0.9, symmetric=False)
+    g_track = H.TensorTrack(0.9, symmetric=True)
+    Wdev = None
+    for t in range(4):
+        L, X, W, dY = wl.c1_inputs(t)
+        if Wdev is None:
+            Wdev = H.DevWeights(L, W)
+        Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+        y_track.step(L, "fwd", X, W, Xd, Wdev)
+        g_track.step(L, "dgrad", dY, W, dYd, Wdev)
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref)
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+
+
+# ---------------------------------------------------------------------------------------
+# Small shapes spanning several tiles with ragged tails, strides, 1x1, odd channel counts
+# ---------------------------------------------------------------------------------------
+SMALL = [
+    wl.linear("lin_ragged", 300, 80, 72),            # M, N tails; K not a multiple of 64
+    wl.linear("lin_fc", 37, 512, 1000),              # N = 1000: dgrad reduces over 1000 (not /16)
+    wl.linear("lin_k24", 130, 24, 36),               # K % 16 != 0 forward
+    wl.conv("c3x3_16", 2, 9, 16, 32, 3),             # small conv, ragged M
+    wl.conv("c3x3_s2", 2, 12, 32, 48, 3, stride=2),  # stride 2: dgrad with missing taps
+    wl.conv("c1x1_s2", 3, 10, 16, 64, 1, stride=2, pad=0),
+    wl.conv("c3x3_c24", 1, 7, 24, 40, 3),            # channels % 16 != 0 on both sides
+    wl.conv("c3x3_wide", 1, 10, 64, 160, 3),         # N > 128: two column tiles, second ragged
+    wl.conv("c5x5", 1, 9, 16, 16, 5),
+    wl.conv("c3x3_nopad", 2, 8, 16, 16, 3, pad=0),
+    wl.conv("c3x3_big", 4, 28, 128, 128, 3),         # the 128x128-tile paths of all three kernels
+]
+
+
+@pytest.mark.parametrize("L", SMALL, ids=[l.name for l in SMALL])
+def test_small_shapes_all_ops(H, hq, L):
+    y_track, g_track = H.TensorTrack(0.9, False), H.TensorTrack(0.9, True)
+    Wdev = None
+    for t in range(3):
+        X, W, dY = rand_layer_inputs(L, 1000 + t)
+        if Wdev is None:
+            W0, Wdev = W, H.DevWeights(L, W)
+        Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+        y_track.step(L, "fwd", X, W0, Xd, Wdev)
+        g_track.step(L, "dgrad", dY, W0, dYd, Wdev)
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref)
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+
+
+def test_weight_prepare_layouts_and_sums(H, hq):
+    L = wl.conv("prep", 1, 6, 24, 40, 3)
+    W = wl.he_weight(np.random.default_rng(5), L)
+    Wd = H.DevWeights(L, W)
+    torch.cuda.synchronize()
+    w = W.codes.astype(np.int64)
+    assert np.array_equal(Wd.wsum.cpu().numpy(), w.sum(axis=(1, 2, 3)))
+    assert np.array_equal(Wd.wdsum.cpu().numpy(), w.sum(axis=(0, 1, 2)))
+    assert np.array_equal(Wd.Wd.cpu().numpy().reshape(L.C, L.R, L.S, L.Cout), W.codes.transpose(3, 1, 2, 0))
+
+
+def test_asymmetric_gradients_and_symmetric_inputs(H, hq):
+    """Zero points on the gradient side (the paper quantizes gradients asymmetrically in its
+    ablations, Sec. 5.1) and none on the input side."""
+    for L in (wl.conv("asym_g", 2, 8, 16, 32, 3), wl.conv("asym_g_s2", 1, 9, 32, 16, 3, stride=2),
+              wl.depthwise("asym_dw", 2, 9, 24)):
+        X, W, dY = rand_layer_inputs(L, 77, x_asym=False, g_asym=True)
+        assert dY.zero_point != 0 and X.zero_point == 0
+        Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
+        g_track = H.TensorTrack(0.9, symmetric=False)
+        for _ in range(2):
+            g_track.step(L, "dgrad", dY, W, dYd, Wdev)
+        y_track = H.TensorTrack(0.9, symmetric=True)
+        for _ in range(2):
+            y_track.step(L, "fwd", X, W, Xd, Wdev)
+        for Xq, Xdev in ((X, Xd), (wl.relu_activation(np.random.default_rng(3), wl.in_shape(L)), None)):
+            Xdev = Xdev or H.DevTensor(Xq)
+            dW, dWa = H.gpu_wgrad(L, Xdev, dYd)
+            ref = oracle.wgrad(H.oracle_problem(L), Xq.codes, Xq.zero_point, dY.codes, dY.zero_point)
+            assert np.array_equal(dWa, ref)
+            assert np.array_equal(dW, oracle.wgrad_scale(ref, Xq.scale, dY.scale))
+
+
+# ---------------------------------------------------------------------------------------
+# Depthwise (config 4's middle layer, small)
+# ---------------------------------------------------------------------------------------
+DW = [wl.depthwise("dw3", 2, 11, 24), wl.depthwise("dw3_s2", 2, 12, 32, stride=2),
+      wl.depthwise("dw3_192", 1, 14, 192), wl.depthwise("dw3_320", 1, 7, 320)]
+
+
+@pytest.mark.parametrize("L", DW, ids=[l.name for l in DW])
+def test_depthwise_all_ops(H, hq, L):
+    y_track, g_track = H.TensorTrack(0.9, False), H.TensorTrack(0.9, True)
+    X0, W, dY0 = rand_layer_inputs(L, 31)
+    Wdev = H.DevWeights(L, W)
+    for t in range(3):
+        X, _, dY = rand_layer_inputs(L, 31 + t)
+        Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+        y_track.step(L, "fwd", X, W, Xd, Wdev)
+        g_track.step(L, "dgrad", dY, W, dYd, Wdev)
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref)
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+
+
+# ---------------------------------------------------------------------------------------
+# Invariants on the GPU path
+# ---------------------------------------------------------------------------------------
+def test_fused_with_current_range_equals_dynamic(H, hq):
+    """Sec. 3.2: static and dynamic quantization differ only in when the range is known."""
+    L = wl.conv("p5", 2, 14, 32, 64, 3)
+    X, W, _ = rand_layer_inputs(L, 9)
+    Wdev, Xd = H.DevWeights(L, W), H.DevTensor(X)
+    for sym in (False, True):
+        r, st = hq.new_range(0.9, sym), hq.new_stats()
+        dyn_codes, dyn_q = H.gpu_quantized_op(L, "fwd", Xd, Wdev, r, st, "dynamic")   # also sets q^0 = current min-max
+        st_dyn = H.read_stats(st)
+        hq.hq_stats_reset(st)
+        codes, q = H.gpu_quantized_op(L, "fwd", Xd, Wdev, r, st, "fused")
+        st_f = H.read_stats(st)
+        assert np.array_equal(codes, dyn_codes) and q == dyn_q
+        for f in ("acc_min", "acc_max", "clip_lo", "clip_hi", "count"):
+            assert st_f[f] == st_dyn[f]
+        assert st_f["clip_lo"] == 0 and st_f["clip_hi"] == 0
+
+
+def test_running_min_max_mode(H, hq):
+    """Sec. 4.1, last paragraph: eq. (2)-(3) with the current tensor's statistics, then quantize."""
+    L = wl.linear("run", 64, 64, 32)
+    r, st = hq.new_range(0.9, False), hq.new_stats()
+    ref = oracle.Range.new(0.9, False)
+    for t in range(3):
+        g = np.random.default_rng(50 + t)
+        X = wl.relu_activation(g, wl.in_shape(L), gain=1.5 ** t)
+        W = wl.he_weight(np.random.default_rng(50), L)
+        Wdev, Xd = H.DevWeights(L, W), H.DevTensor(X)
+        codes, q = H.gpu_quantized_op(L, "fwd", Xd, Wdev, r, st, "dynamic", hq.HQ_DYN_RUNNING)
+        stats = H.read_stats(st)
+        hq.hq_stats_reset(st)
+        c = H.oracle_acc(L, "fwd", X, W)
+        a_scale = oracle.acc_scale(X.scale, W.scale)
+        mn, mx = oracle.minmax(c)
+        oracle.range_update(ref, mn, mx, a_scale)
+        want, lo, hi = oracle.requant(c, a_scale, ref.scale, ref.zero_point, ref.qlo, ref.qhi)
+        assert np.array_equal(codes, want)
+        assert (int(stats["clip_lo"]), int(stats["clip_hi"])) == (lo, hi)
+        H.assert_range_close(H.read_range(r), ref)
+
+
+def test_statistics_merge_until_consumed(H, hq):
+    """Two launches into the same statistics record give the union; hq_range_update with an
+    empty record leaves the range alone."""
+    L = wl.linear("merge", 96, 32, 32)
+    W = wl.he_weight(np.random.default_rng(1), L)
+    Wdev = H.DevWeights(L, W)
+    r, st = hq.new_range(0.9, False), hq.new_stats()
+    Xs = [wl.relu_activation(np.random.default_rng(s), wl.in_shape(L), gain=g) for s, g in ((1, 1.0), (2, 3.0))]
+    H.gpu_quantized_op(L, "fwd", H.DevTensor(Xs[0]), Wdev, r, st, "dynamic")
+    hq.hq_range_update(r, st)
+    before = H.read_range(r).copy()
+    hq.hq_range_update(r, st)                      # empty record: no change
+    assert H.read_range(r) == before
+    mins, maxs = [], []
+    for X in Xs:
+        H.gpu_quantized_op(L, "fwd", H.DevTensor(X), Wdev, r, st, "fused")
+        mn, mx = oracle.minmax(H.oracle_acc(L, "fwd", X, W))
+        mins.append(mn); maxs.append(mx)
+    s = H.read_stats(st)
+    assert int(s["acc_min"]) == min(mins) and int(s["acc_max"]) == max(maxs) and int(s["count"]) == 2 * 96 * 32
+
+
+def test_repeat_runs_are_bit_identical(H, hq):
+    L = wl.conv("rep", 2, 14, 64, 64, 3)
+    X, W, dY = rand_layer_inputs(L, 4)
+    Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
+    r, st = hq.new_range(0.9, False), hq.new_stats()
+    H.gpu_quantized_op(L, "fwd", Xd, Wdev, r, st, "dynamic")
+    outs = []
+    for _ in range(3):
+        hq.hq_stats_reset(st)
+        codes, _ = H.gpu_quantized_op(L, "fwd", Xd, Wdev, r, st, "fused")
+        outs.append((codes, H.read_stats(st), H.gpu_wgrad(L, Xd, dYd)[1]))
+    for o in outs[1:]:
+        assert np.array_equal(o[0], outs[0][0]) and o[1] == outs[0][1] and np.array_equal(o[2], outs[0][2])
+
+
+# ---------------------------------------------------------------------------------------
+# Error behaviour (nothing is launched on error)
+# ---------------------------------------------------------------------------------------
+def test_error_codes(H, hq):
+    L = wl.conv("err", 1, 8, 16, 16, 3)
+    X, W, dY = rand_layer_inputs(L, 2)
+    Wdev, Xd = H.DevWeights(L, W), H.DevTensor(X)
+    r, st = hq.new_range(), hq.new_stats()
+    out = torch.empty(wl.out_shape(L), dtype=torch.int8, device="cuda")
+    outq = hq.new_qparams(0, 0)
+    bad = hq.problem(hq.HQ_CONV2D, 1, 8, 8, 18, 3, 3, 1, 1, 16)         # C % 4 != 0
+    with pytest.raises(hq.HqError) as e:
+        hq.hq_gemm_fwd(bad, Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, r, out, outq, st)
+    assert e.value.code == hq.HQ_E_BADSHAPE
+    with pytest.raises(hq.HqError) as e:
+        hq.hq_gemm_fwd(H.hq_problem(L), None, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, r, out, outq, st)
+    assert e.value.code == hq.HQ_E_BADARG
+    with pytest.raises(hq.HqError) as e:                                   # misaligned codes
+        hq.hq_gemm_fwd(H.hq_problem(L), Xd.codes.data_ptr() + 4, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, r, out, outq, st)
+    assert e.value.code == hq.HQ_E_BADARG
+    ws = torch.empty(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(hq.HqError) as e:
+        hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_FWD, 0, H.hq_problem(L), Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum,
+                           r, out, outq, st, ws, 64)
+    assert e.value.code == hq.HQ_E_WORKSPACE
+    with pytest.raises(hq.HqError) as e:
+        hq.hq_gemm_dynamic(7, 0, H.hq_problem(L), Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, r, out, outq, st, ws, 64)
+    assert e.value.code == hq.HQ_E_BADARG
+    lin_bad = hq.problem(hq.HQ_LINEAR, 8, 2, 1, 16, 1, 1, 1, 0, 16)
+    assert hq.hq_workspace_bytes(hq.HQ_ENTRY_WGRAD, lin_bad) == 0
+    torch.cuda.synchronize()
+    s = H.read_stats(st)
+    assert int(s["count"]) == 0                                             # nothing ran
