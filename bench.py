@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the in-hindsight quantized layer path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of the ResNet-style 3x3 conv
+64->64 at 56x56, batch 128 (M=401408, K=576, N=64): forward GEMM with the fused
+in-hindsight epilogue, its range update, input-gradient GEMM with the same epilogue and its
+range update, and the FP32 weight-gradient GEMM.  Inputs are seeded synthetic tensors that
+are resident in HBM before the timed region.  The dynamic two-pass baseline, the depthwise
+stencil and the other layer shapes are timed next to it and reported in the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--calibrate-copy]
+
+One GPU only: this build has no multi-GPU path.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch plain device copies of known size (counter calibration under rocprofv3 --pmc)")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device-side operands and state of one layer (torch holds the memory, nothing else)."""
+
+    def __init__(self, hq, torch, wl, L, X, W, dY):
+        self.hq, self.torch, self.L = hq, torch, L
+        self.p = hq.problem(L.kind, L.B, L.H, L.W, L.C, L.R, L.S, L.stride, L.pad, L.Cout)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.X, self.xq = dev(X.codes), hq.new_qparams(X.scale, X.zero_point)
+        self.dY, self.gq = dev(dY.codes), hq.new_qparams(dY.scale, dY.zero_point)
+        self.W, self.wq = dev(W.codes), hq.new_qparams(W.scale, 0)
+        self.wsum = torch.empty(L.Cout, dtype=torch.int32, device="cuda")
+        self.wdsum = torch.empty(L.C, dtype=torch.int32, device="cuda")
+        if L.kind == wl.DEPTHWISE:
+            self.Wd = self.W
+            hq.hq_weight_prepare(self.p, self.W, None, self.wsum, self.wdsum)
+        else:
+            self.Wd = torch.empty(self.W.numel(), dtype=torch.int8, device="cuda")
+            hq.hq_weight_prepare(self.p, self.W, self.Wd, self.wsum, self.wdsum)
+        self.Y = torch.empty(wl.out_shape(L), dtype=torch.int8, device="cuda")
+        self.dX = torch.empty(wl.in_shape(L), dtype=torch.int8, device="cuda")
+        self.dW = torch.empty(wl.w_shape(L), dtype=torch.float32, device="cuda")
+        self.yq, self.dxq = hq.new_qparams(0, 0), hq.new_qparams(0, 0)
+        self.yr, self.gr = hq.new_range(0.9, False), hq.new_range(0.9, True)
+        self.yst, self.gst = hq.new_stats(), hq.new_stats()
+        self.ws_w = hq.hq_workspace_bytes(hq.HQ_ENTRY_WGRAD, self.p)
+        self.ws_f = hq.hq_workspace_bytes(hq.HQ_ENTRY_DYNAMIC_FWD, self.p)
+        self.ws_d = hq.hq_workspace_bytes(hq.HQ_ENTRY_DYNAMIC_DGRAD, self.p)
+        self.ws = torch.empty(max(self.ws_w, self.ws_f, self.ws_d, 16), dtype=torch.uint8, device="cuda")
+
+    # the five entry points ------------------------------------------------------------
+    def fwd(self):
+        self.hq.hq_gemm_fwd(self.p, self.X, self.xq, self.W, self.wq, self.wsum, self.yr, self.Y, self.yq, self.yst)
+
+    def dgrad(self):
+        self.hq.hq_gemm_dgrad(self.p, self.dY, self.gq, self.Wd, self.wq, self.wdsum, self.gr, self.dX, self.dxq, self.gst)
+
+    def wgrad(self):
+        self.hq.hq_gemm_wgrad(self.p, self.X, self.xq, self.dY, self.gq, self.dW, None, self.ws, self.ws_w)
+
+    def upd_y(self):
+        self.hq.hq_range_update(self.yr, self.yst)
+
+    def upd_g(self):
+        self.hq.hq_range_update(self.gr, self.gst)
+
+    def dyn_fwd(self):
+        hq = self.hq
+        hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_FWD, hq.HQ_DYN_CURRENT, self.p, self.X, self.xq, self.W, self.wq,
+                           self.wsum, self.yr, self.Y, self.yq, self.yst, self.ws, self.ws_f)
+
+    def dyn_dgrad(self):
+        hq = self.hq
+        hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_DGRAD, hq.HQ_DYN_CURRENT, self.p, self.dY, self.gq, self.Wd, self.wq,
+                           self.wdsum, self.gr, self.dX, self.dxq, self.gst, self.ws, self.ws_d)
+
+    def init_ranges(self):
+        """Iteration 0: the first batch sets q^0 through the dynamic path (Sec. 4.1)."""
+        self.dyn_fwd(); self.upd_y(); self.dyn_dgrad(); self.upd_g()
+
+    def fused_step(self):
+        self.fwd(); self.upd_y(); self.dgrad(); self.upd_g(); self.wgrad()
+
+    def dynamic_step(self):
+        self.dyn_fwd(); self.upd_y(); self.dyn_dgrad(); self.upd_g(); self.wgrad()
+
+
+def time_calls(torch, fn, reps, warmup=2):
+    """Average milliseconds of fn() over `reps` back-to-back launches, HIP events on the launch stream."""
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def cpu_baseline(wl, sample_B, min_seconds=10.0):
+    """The oracle as it stands, timed on the host cores on a slice of the same workload:
+    whole passes of the layer step until at least `min_seconds` of CPU work are done."""
+    import oracle
+    L, X, W = wl.c2_inputs(1, B=sample_B)
+    dY = wl.laplace_gradient(wl.rng(2, 1, 2), wl.out_shape(L), 1e-3)
+    p = oracle.Problem(L.kind, L.B, L.H, L.W, L.C, L.R, L.S, L.stride, L.pad, L.Cout)
+    ry, rg = oracle.Range.new(0.9, False), oracle.Range.new(0.9, True)
+    passes, t0 = 0, time.perf_counter()
+    while passes == 0 or time.perf_counter() - t0 < min_seconds:
+        c = oracle.fwd(p, X.codes, X.zero_point, W.codes)
+        oracle.in_hindsight_step(c, oracle.acc_scale(X.scale, W.scale), ry)
+        c = oracle.dgrad(p, dY.codes, dY.zero_point, W.codes)
+        oracle.in_hindsight_step(c, oracle.acc_scale(dY.scale, W.scale), rg)
+        c = oracle.wgrad(p, X.codes, X.zero_point, dY.codes, dY.zero_point)
+        oracle.wgrad_scale(c, X.scale, dY.scale)
+        passes += 1
+    dt = time.perf_counter() - t0
+    ops = passes * 3 * 2 * wl.macs(L)
+    return {"value": ops / dt / 1e12, "unit": "TOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "same layer and step at batch %d of 128, %d whole passes (%.1f GOP) in %.1f s"
+                      % (sample_B, passes, ops / 1e9, dt)}
+
+
+def stored_traffic(kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        return json.load(open(path)).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    import paper_2105_04246_amd as hq
+    import workloads as wl
+
+    torch.cuda.set_device(0)
+    L, X, W = wl.c2_inputs(1)
+    dY = wl.laplace_gradient(wl.rng(2, 1, 2), wl.out_shape(L), 1e-3)
+    lay = Layer(hq, torch, wl, L, X, W, dY)
+    lay.init_ranges()
+    torch.cuda.synchronize()
+
+    # ---- headline: W warm-up steps, then exactly K timed steps -----------------------------
+    K, Wm = args.steps, args.warmup
+    for _ in range(Wm):
+        lay.fused_step()
+    calls = [("fwd", lay.fwd), ("upd_y", lay.upd_y), ("dgrad", lay.dgrad), ("upd_g", lay.upd_g), ("wgrad", lay.wgrad)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        ev[k][0].record()
+        for i, (_, fn) in enumerate(calls):
+            fn()
+            ev[k][i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / K
+    per_call = {name: sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K for i, (name, _) in enumerate(calls)}
+
+    ops_gemm = 2 * wl.macs(L)
+    step_ops = 3 * ops_gemm
+    value = step_ops / (wall_ms * 1e-3) / 1e12
+
+    # ---- roofline of the dominant kernel: the slowest of the three GEMM launches ------------
+    names = {"fwd": "hq_gemm_kernel<256,64,4,1> (forward)", "dgrad": "hq_gemm_kernel<256,64,4,1> (dgrad)",
+             "wgrad": "hq_wgrad_kernel (+zero, finalize)"}
+    dom = max(("fwd", "dgrad", "wgrad"), key=lambda n: per_call[n])
+    achieved = ops_gemm / (per_call[dom] * 1e-3) / 1e12
+    roofline = {"kernel": names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": achieved / PEAK_INT8_TOPS, "traffic": stored_traffic(dom),
+                "algorithmic_bytes": wl.fused_bytes(L, dom), "avg_launch_ms": per_call[dom],
+                "hbm_frac_of_8TBs": wl.fused_bytes(L, dom) / (per_call[dom] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+    out = {"metric": "int8 GEMM TOPS + HBM bytes/step, in-hindsight fused vs dynamic 2-pass", "value": value,
+           "unit": "TOP/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": wall_ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+           "config": {"workload": "ResNet-style conv3x3 64->64 @56x56, batch 128 (M=401408,K=576,N=64): "
+                                  "fwd + dgrad + wgrad with in-hindsight ranges (eta 0.9), one layer step",
+                      "global_batch": 128, "parallelism": "single GPU"},
+           "roofline": roofline,
+           "per_call_ms": per_call,
+           "per_call_tops": {n: ops_gemm / (per_call[n] * 1e-3) / 1e12 for n in ("fwd", "dgrad", "wgrad")}}
+
+    # ---- the dynamic two-pass baseline on the same layer -----------------------------------
+    if not args.no_extras:
+        reps = max(5, min(K, 20))
+        dyn_ms = time_calls(torch, lay.dynamic_step, reps)
+        fus_ms = time_calls(torch, lay.fused_step, reps)
+        fb = sum(wl.fused_bytes(L, o) for o in ("fwd", "dgrad", "wgrad"))
+        db = sum(wl.dynamic_bytes(L, o) for o in ("fwd", "dgrad", "wgrad"))
+        out["fused_vs_dynamic"] = {
+            "fused_ms_per_step": fus_ms, "dynamic_ms_per_step": dyn_ms, "speedup": dyn_ms / fus_ms,
+            "fwd_fused_ms": time_calls(torch, lay.fwd, reps), "fwd_dynamic_ms": time_calls(torch, lay.dyn_fwd, reps),
+            "dgrad_fused_ms": time_calls(torch, lay.dgrad, reps), "dgrad_dynamic_ms": time_calls(torch, lay.dyn_dgrad, reps),
+            "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb},
+            "measured_hbm_bytes_per_step": stored_traffic("step")}
+        lay.upd_y(); lay.upd_g()
+
+        # ---- other layer shapes of the configurations (same kernels, single launches) ------
+        extra = {}
+        del lay
+        torch.cuda.empty_cache()
+        shapes = [("c3_conv3x3_128_b128", wl.c3_layer())] + [(l.name + "_b128", l) for l in wl.c4_layers()]
+        for name, Ls in shapes:
+            g = wl.rng(9, 0, len(extra))
+            Xs = wl.relu6_activation(g, wl.in_shape(Ls)) if name.startswith("c4") else wl.relu_activation(g, wl.in_shape(Ls))
+            ly = Layer(hq, torch, wl, Ls, Xs, wl.he_weight(g, Ls), wl.laplace_gradient(g, wl.out_shape(Ls), 1e-3))
+            ly.init_ranges()
+            row = {}
+            for op, f, fd in (("fwd", ly.fwd, ly.dyn_fwd), ("dgrad", ly.dgrad, ly.dyn_dgrad), ("wgrad", ly.wgrad, None)):
+                ms = time_calls(torch, f, 10)
+                row[op] = {"ms": ms, "tops": 2 * wl.macs(Ls) / (ms * 1e-3) / 1e12,
+                           "alg_GBs": wl.fused_bytes(Ls, op) / (ms * 1e-3) / 1e9}
+                if fd is not None:
+                    dms = time_calls(torch, fd, 10)
+                    row[op]["dynamic_ms"] = dms
+                    row[op]["dynamic_alg_GBs"] = wl.dynamic_bytes(Ls, op) / (dms * 1e-3) / 1e9
+            extra[name] = row
+            del ly
+            torch.cuda.empty_cache()
+        out["other_layers"] = extra
+
+    if args.calibrate_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = {"read": a.numel(), "write": a.numel()}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, 64)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
