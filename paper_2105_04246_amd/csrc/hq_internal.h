@@ -7,6 +7,11 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
                    const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
                    int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
 
+// Fast path for layers whose weights fit in LDS; HQ_E_BADSHAPE means "not covered, use hq_launch_gemm".
+int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
+                       const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
+                       int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+
 int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
                         const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
                         int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);

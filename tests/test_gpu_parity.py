@@ -64,6 +64,12 @@ SMALL = [
     wl.conv("c5x5", 1, 9, 16, 16, 5),
     wl.conv("c3x3_nopad", 2, 8, 16, 16, 3, pad=0),
     wl.conv("c3x3_big", 4, 28, 128, 128, 3),         # the 128x128-tile paths of all three kernels
+    wl.conv("band_c64", 3, 30, 64, 64, 3),           # weights-resident path, one-row bands
+    wl.conv("band_c64_n48", 2, 17, 64, 48, 3),       # ... with a ragged column tile
+    wl.conv("band_c64_s2", 2, 22, 64, 64, 3, stride=2),
+    wl.conv("band_1x1_c32", 2, 20, 32, 192, 1),      # three column chunks per tile
+    wl.conv("band_1x1_c192", 2, 20, 192, 32, 1),
+    wl.conv("band_multi_tile", 128, 36, 64, 64, 3),  # 4 bands per image of 9 rows: two tiles per band, second ragged
 ]
 
 
