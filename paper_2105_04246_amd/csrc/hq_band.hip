@@ -1,26 +1,31 @@
 // Weights-resident implicit-GEMM convolution for gfx950: the fast path of hq_gemm_fwd /
 // hq_gemm_dgrad (and of pass 1 of the dynamic baseline) for layers whose quantized weights fit
-// in LDS next to an input patch (paper Sec. 3.1 forward / backward linear op; Sec. 3.2 and Sec. 4
-// for what the epilogue does).
+// in LDS next to two input patches (paper Sec. 3.1 forward / backward linear op; Sec. 3.2 and
+// Sec. 4 for what the epilogue does).
 //
 // Mapping to the machine
-//   * One workgroup (4 wavefronts) owns a band of output rows of one image and walks it in
-//     tiles of 256 consecutive output pixels.  The layer's weights are copied to LDS once per
-//     workgroup; two workgroups share a CU, so while one loads its next patch the other one
-//     keeps the matrix cores busy.
-//   * Per tile, the input rows the tile touches (with the zero-point code in the padding ring)
-//     are staged in LDS once, as they lie in memory.  im2col never exists: each lane forms
-//     the address of "its" pixel under tap (r,s) when it reads the MFMA fragment, so an input
-//     byte crosses L2->LDS once per tile instead of once per tap.  The next tile's rows are
-//     prefetched into registers while the current tile is multiplied.
+//   * One workgroup of 8 wavefronts per CU owns a band of output rows of one image and walks
+//     it in tiles of 256 consecutive output pixels.  The layer's weights are copied to LDS once
+//     per workgroup.
+//   * The 8 wavefronts form two groups of 4 (one wavefront of each group per SIMD) that work
+//     half a step apart: while one group feeds the matrix cores with its tile, the other runs
+//     the vector-ALU epilogue of the tile it multiplied in the previous half step.  A
+//     workgroup barrier closes every half step, so MFMA and epilogue phases of the two groups
+//     stay interleaved instead of colliding on the same pipe.
+//   * Each group has its own input patch in LDS: the input rows its tile touches (padding ring
+//     filled with the zero-point code), staged once, as they lie in memory.  im2col never
+//     exists: a lane forms the address of "its" pixel under tap (r,s) when it reads the MFMA
+//     fragment, so an input byte crosses L2->LDS once per tile, not once per tap.  The next
+//     patch of a group is requested at the start of its MFMA phase (into registers) and written
+//     to LDS at the start of its epilogue phase, when nobody reads that patch.
 //   * v_mfma_i32_32x32x32_i8 with the weights as first operand: a lane then holds one output
-//     pixel and, because the weight rows are stored in LDS in permuted order, 16 CONSECUTIVE
-//     output channels, so the epilogue stores 16 codes (or 16 accumulators) per lane at once.
-//   * Epilogue per accumulator: subtract z_a * bsum[n]; fold into per-lane min / max; count
-//     clipped values with two integer compares against thresholds found once per kernel by
-//     bisection on the exact fp32 requantization formula (it is monotone), the counts
-//     accumulating in scalar registers through wavefront ballots; requantize with one fp32
-//     multiply, round-half-even, clamp, and pack.
+//     pixel and, because weight rows sit in LDS in permuted order, 16 CONSECUTIVE output
+//     channels, so the epilogue stores 16 codes (or 16 accumulators) per lane at once.
+//   * Epilogue per accumulator: subtract z_a * bsum[n]; fold into min / max; requantize with
+//     one fp32 multiply, round-half-even, clamp and pack (v_cvt_pk_u8_f32 saturates, which is
+//     the clamp on the full 8-bit grid).  Clipped values are counted exactly, but only in
+//     16-value groups whose own min / max cross integer thresholds found once per kernel by
+//     bisection on the fp32 requantization formula (it is monotone in the accumulator).
 #include "hq_device.h"
 #include "hq_internal.h"
 
@@ -40,11 +45,12 @@ struct BandArgs {
     int stride, pad, flip;         // effective padding; flip = weight taps mirrored (dgrad)
     int PW, PRmax;                 // patch width (pixels), most patch rows any tile needs
     int rows_per_band, bands_per_image;
-    unsigned magic_Wo, magic_row;  // ceil(2^32 / Wo), ceil(2^32 / (PW * C/16))
+    unsigned magic_Wo;             // ceil(2^32 / Wo)
     unsigned long long count;      // outputs of the whole tensor
 };
 
 constexpr int BM = 256;            // output pixels per tile: 4 wavefronts x 2 MFMA row blocks
+constexpr int BAND_THREADS = 512;  // two groups of four wavefronts
 
 __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
@@ -69,41 +75,32 @@ __device__ inline int clip_threshold(float mult, float bound, bool high)
     return (int)good;
 }
 
-template <int C, int KSZ, int NT, int NPF, bool FUSED>
-__global__ __launch_bounds__(HQ_THREADS, 2) void hq_band_kernel(const BandArgs a)
+// PR: patch rows prefetched per tile (>= PRmax), PJ: 16-byte column chunks per thread and row.
+template <int C, int KSZ, int NT, int PR, int PJ, bool FUSED>
+__global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
 {
     constexpr int NCH = C / 16, KS = C / 32, PP = C + 16, BN = 32 * NT, TAPS = KSZ * KSZ;
     constexpr int WROW = TAPS * C;                        // bytes per weight row in LDS
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+    const int patch_bytes = a.PRmax * a.PW * PP;
     int8_t *Wl = smem;                                     // [npad][TAPS][C], chunks swizzled
     int *bz = reinterpret_cast<int *>(smem + (size_t)a.npad * WROW);     // [npad]  z_a * bsum[n]
-    int8_t *Pl = reinterpret_cast<int8_t *>(bz + a.npad);  // [PRmax * PW][PP]
-    int *red = reinterpret_cast<int *>(Pl + (size_t)a.PRmax * a.PW * PP);
+    int8_t *Pl = reinterpret_cast<int8_t *>(bz + a.npad);  // two patches [PRmax * PW][PP]
+    int *red = reinterpret_cast<int *>(Pl + 2 * (size_t)patch_bytes);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = wave >> 2, gwave = wave & 3, gtid = tid & 255;
+    int8_t *Pg = Pl + grp * patch_bytes;                   // this group's patch
     const int za = a.aq->zero_point;
     const int fillw = (za & 0xff) * 0x01010101;
     const v4i fill = {fillw, fillw, fillw, fillw};
 
-    // ---- weights and zero-point terms: once per workgroup
-    for (int idx = tid; idx < a.npad * TAPS * NCH; idx += HQ_THREADS) {
-        const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
-        const int i = row & 31, n = (row & ~31) + sigma32(i);
-        const int tsrc = a.flip ? TAPS - 1 - t : t;
-        v4i v = {0, 0, 0, 0};
-        if (n < a.N) v = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
-        *reinterpret_cast<v4i *>(Wl + row * WROW + t * C + 16 * (cq ^ wswz<C>(i))) = v;
-    }
-    for (int n = tid; n < a.npad; n += HQ_THREADS) bz[n] = n < a.N ? za * a.bsum[n] : 0;
-
-    // ---- requantization constants
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
     HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
-    int c_lo = INT_MIN, c_hi = INT_MAX;
+    bool full_grid = true;
     if (FUSED) {
         rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
-        c_hi = clip_threshold(rq.mult, rq.fhi, true);
-        c_lo = clip_threshold(rq.mult, rq.flo, false);
+        full_grid = a.range->qlo == -128 && a.range->qhi == 127;
     }
     const float zoff = (float)(rq.z + 128);
 
@@ -111,36 +108,84 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_band_kernel(const BandArgs a
     const int img = blockIdx.x / a.bands_per_image, band = blockIdx.x % a.bands_per_image;
     const int row0 = band * a.rows_per_band, row1 = min(a.Ho, row0 + a.rows_per_band);
     const int p0 = row0 * a.Wo, p1 = row1 * a.Wo;
+    const int ntile = (p1 - p0 + BM - 1) / BM;
+    const int nchunk = a.npad / BN;
+    const int nitem = ntile * nchunk;                      // work items: (tile, column chunk)
     const int8_t *Aimg = a.A + (size_t)img * a.Hs * a.Ws * C;
     const size_t out_img = (size_t)img * a.Ho * a.Wo;
-    const int rowchunks = a.PW * NCH;
 
-    v4i pf[NPF];
-    auto prefetch = [&](int ps) {
+    // ---- patch loader: thread <-> fixed column chunk(s) of a patch row; slot <-> patch row
+    int col_src[PJ], col_lds[PJ];
+    bool col_ok[PJ], col_in[PJ];
+#pragma unroll
+    for (int j = 0; j < PJ; j++) {
+        const int cidx = gtid + 256 * j, ixp = cidx / NCH, q = cidx % NCH, ix = ixp - a.pad;
+        col_in[j] = cidx < a.PW * NCH;                     // inside the patch row at all
+        col_ok[j] = col_in[j] && ix >= 0 && ix < a.Ws;     // ... and inside the image
+        col_src[j] = ix * C + q * 16;
+        col_lds[j] = ixp * PP + q * 16;
+    }
+    v4i pf[PR][PJ];
+    auto prefetch = [&](int tile) {
+        const int ps = p0 + tile * BM;
         const int oy0 = ps / a.Wo, oy1 = (min(ps + BM, p1) - 1) / a.Wo;
-        const int total = ((oy1 - oy0) * a.stride + KSZ) * rowchunks;
+        const int nrows = (oy1 - oy0) * a.stride + KSZ;
         const int iy_base = oy0 * a.stride - a.pad;
 #pragma unroll
-        for (int k = 0; k < NPF; k++) {
-            const int idx = tid + HQ_THREADS * k;
-            v4i v = fill;
-            if (idx < total) {
-                const int vr = (int)__umulhi((unsigned)idx, a.magic_row), rem = idx - vr * rowchunks;
-                const int iy = iy_base + vr, ix = rem / NCH - a.pad, q = rem % NCH;
-                if (iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws)
-                    v = *reinterpret_cast<const v4i *>(Aimg + ((size_t)iy * a.Ws + ix) * C + q * 16);
+        for (int k = 0; k < PR; k++) {
+            const int iy = iy_base + k;
+            const bool row_ok = k < nrows && iy >= 0 && iy < a.Hs;       // uniform
+            const int8_t *rowp = Aimg + (size_t)(row_ok ? iy : 0) * a.Ws * C;
+#pragma unroll
+            for (int j = 0; j < PJ; j++) {
+                v4i v = fill;
+                if (row_ok && col_ok[j]) v = *reinterpret_cast<const v4i *>(rowp + col_src[j]);
+                pf[k][j] = v;
             }
-            pf[k] = v;
         }
     };
     auto stash = [&]() {
-        const int cap = a.PRmax * rowchunks;
 #pragma unroll
-        for (int k = 0; k < NPF; k++) {
-            const int idx = tid + HQ_THREADS * k;
-            if (idx < cap) *reinterpret_cast<v4i *>(Pl + (idx / NCH) * PP + (idx % NCH) * 16) = pf[k];
-        }
+        for (int k = 0; k < PR; k++)
+#pragma unroll
+            for (int j = 0; j < PJ; j++)
+                if (k < a.PRmax && col_in[j])
+                    *reinterpret_cast<v4i *>(Pg + k * a.PW * PP + col_lds[j]) = pf[k][j];
     };
+
+    // ---- start-up: request the group's first patch and the weights before anything waits;
+    // search the clip thresholds while the loads are in flight.
+    if (grp < nitem) prefetch(grp / nchunk);
+    constexpr int WB = 6;
+    const int wchunks = a.npad * TAPS * NCH;
+    int c_lo = INT_MIN, c_hi = INT_MAX;
+    for (int base = 0; base < wchunks; base += BAND_THREADS * WB) {
+        v4i wv[WB];
+#pragma unroll
+        for (int k = 0; k < WB; k++) {
+            const int idx = base + tid + BAND_THREADS * k;
+            const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
+            const int n = (row & ~31) + sigma32(row & 31);
+            const int tsrc = a.flip ? TAPS - 1 - t : t;
+            wv[k] = v4i{0, 0, 0, 0};
+            if (idx < wchunks && n < a.N)
+                wv[k] = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
+        }
+        if (FUSED && base == 0) {
+            c_hi = clip_threshold(rq.mult, rq.fhi, true);
+            c_lo = clip_threshold(rq.mult, rq.flo, false);
+        }
+#pragma unroll
+        for (int k = 0; k < WB; k++) {
+            const int idx = base + tid + BAND_THREADS * k;
+            const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
+            if (idx < wchunks)
+                *reinterpret_cast<v4i *>(Wl + row * WROW + t * C + 16 * (cq ^ wswz<C>(row & 31))) = wv[k];
+        }
+    }
+    for (int n = tid; n < a.npad; n += BAND_THREADS) bz[n] = n < a.N ? za * a.bsum[n] : 0;
+    if (grp < nitem) stash();
+    __syncthreads();
 
     // per-lane weight fragment addresses (row i = lane % 32 of each 32-row block)
     int wbase[NT][KS];
@@ -151,102 +196,134 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_band_kernel(const BandArgs a
             wbase[j][ks] = (j * 32 + (lane & 31)) * WROW + 16 * ((ks * 2 + (lane >> 5)) ^ wswz<C>(lane & 31));
 
     int mn = INT_MAX, mx = INT_MIN;
-    unsigned s_lo = 0, s_hi = 0;                           // wavefront-uniform clip counts
+    unsigned nlo = 0, nhi = 0;
+    v16i acc[2][NT];
+    int pix[2] = {0, 0};
+    bool ok[2] = {false, false};
+    bool have_pf = false;
 
-    prefetch(p0);
-    for (int ps = p0; ps < p1; ps += BM) {
-        __syncthreads();                                   // previous patch no longer read
-        stash();
-        __syncthreads();
-        if (ps + BM < p1) prefetch(ps + BM);
-        if (ps + wave * 64 >= p1) continue;                // this wavefront has no pixel in the tile
-
-        const int oy0 = ps / a.Wo;
-        int abase[2], pix[2];
-        bool ok[2];
+    // Half step h: item h is multiplied (by group h & 1) while item h-1 goes through the
+    // epilogue (in the other group, which multiplied it during half step h-1).
+    for (int h = 0; h <= nitem; h++) {
+        const bool mfma_phase = (h & 1) == grp;
+        const int item = mfma_phase ? h : h - 1;           // this group's item in this half step
+        if (item >= 0 && item < nitem) {
+            const int tile = item / nchunk, nc = item - tile * nchunk;
+            const int ps = p0 + tile * BM;
+            if (mfma_phase) {
+                // -------------------------------------------------- matrix-core phase
+                const int nxt = item + 2;
+                have_pf = nxt < nitem && nxt / nchunk != tile;
+                if (have_pf) prefetch(nxt / nchunk);
+                const bool active = ps + gwave * 64 < p1;
+                const int oy0 = ps / a.Wo;
+                int abase[2];
 #pragma unroll
-        for (int i = 0; i < 2; i++) {
-            const int p = ps + wave * 64 + i * 32 + (lane & 31);
-            ok[i] = p < p1;
-            pix[i] = ok[i] ? p : ps;
-            const int oy = (int)__umulhi((unsigned)pix[i], a.magic_Wo), ox = pix[i] - oy * a.Wo;
-            abase[i] = (((oy - oy0) * a.stride) * a.PW + ox * a.stride) * PP + (lane >> 5) * 16;
-        }
-
-        for (int nc = 0; nc < a.npad / BN; nc++) {
-            v16i acc[2][NT];
-#pragma unroll
-            for (int i = 0; i < 2; i++)
-#pragma unroll
-                for (int j = 0; j < NT; j++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
-            const int8_t *Wc = Wl + nc * BN * WROW;
-#pragma unroll 1
-            for (int r = 0; r < KSZ; r++)
-#pragma unroll 1
-                for (int s = 0; s < KSZ; s++) {
-                    const int toff = (r * a.PW + s) * PP;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ks++) {
-                        v4i wf[NT], af[2];
-#pragma unroll
-                        for (int j = 0; j < NT; j++)
-                            wf[j] = *reinterpret_cast<const v4i *>(Wc + wbase[j][ks] + (r * KSZ + s) * C);
-#pragma unroll
-                        for (int i = 0; i < 2; i++)
-                            af[i] = *reinterpret_cast<const v4i *>(Pl + abase[i] + toff + ks * 32);
-#pragma unroll
-                        for (int i = 0; i < 2; i++)
-#pragma unroll
-                            for (int j = 0; j < NT; j++)
-                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
-                    }
+                for (int i = 0; i < 2; i++) {
+                    const int p = ps + gwave * 64 + i * 32 + (lane & 31);
+                    ok[i] = p < p1;
+                    pix[i] = ok[i] ? p : ps;
+                    const int oy = (int)__umulhi((unsigned)pix[i], a.magic_Wo), ox = pix[i] - oy * a.Wo;
+                    abase[i] = (((oy - oy0) * a.stride) * a.PW + ox * a.stride) * PP + (lane >> 5) * 16;
                 }
-
-            // ---- epilogue: lane = one pixel, 16 consecutive channels per (row block, column block)
 #pragma unroll
-            for (int i = 0; i < 2; i++) {
-                if (!ok[i]) continue;
-                const size_t m = out_img + pix[i];
+                for (int i = 0; i < 2; i++)
 #pragma unroll
-                for (int j = 0; j < NT; j++) {
-                    const int nb = nc * BN + j * 32 + 16 * (lane >> 5);
-                    if (nb >= a.N) continue;
-                    v4i packed;
+                    for (int j = 0; j < NT; j++)
 #pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        const v4i bzv = *reinterpret_cast<const v4i *>(bz + nb + 4 * g);
-                        int c[4];
+                        for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
+                if (active) {
+                    const int8_t *Wc = Wl + nc * BN * WROW;
+#pragma unroll 1
+                    for (int r = 0; r < KSZ; r++)
+#pragma unroll 1
+                        for (int s = 0; s < KSZ; s++) {
+                            const int toff = (r * a.PW + s) * PP;
 #pragma unroll
-                        for (int e = 0; e < 4; e++) {
-                            c[e] = acc[i][j][4 * g + e] - bzv[e];
-                            mn = min(mn, c[e]); mx = max(mx, c[e]);
-                        }
-                        if (FUSED) {
-                            unsigned w = 0;
+                            for (int ks = 0; ks < KS; ks++) {
+                                v4i wf[NT], af[2];
 #pragma unroll
-                            for (int e = 0; e < 4; e++) {
-                                s_hi += (unsigned)__popcll(__ballot(c[e] > c_hi));
-                                s_lo += (unsigned)__popcll(__ballot(c[e] < c_lo));
-                                float f = rintf(__fmul_rn((float)c[e], rq.mult));
-                                f = __builtin_amdgcn_fmed3f(f, rq.flo, rq.fhi) + zoff;
-                                w = __builtin_amdgcn_cvt_pk_u8_f32(f, e, w);
+                                for (int j = 0; j < NT; j++)
+                                    wf[j] = *reinterpret_cast<const v4i *>(Wc + wbase[j][ks] + (r * KSZ + s) * C);
+#pragma unroll
+                                for (int i = 0; i < 2; i++)
+                                    af[i] = *reinterpret_cast<const v4i *>(Pg + abase[i] + toff + ks * 32);
+#pragma unroll
+                                for (int i = 0; i < 2; i++)
+#pragma unroll
+                                    for (int j = 0; j < NT; j++)
+                                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
                             }
-                            packed[g] = (int)(w ^ 0x80808080u);
+                        }
+                }
+            } else {
+                // -------------------------------------------------- vector-ALU phase
+                if (have_pf) stash();                      // nobody reads this group's patch now
+#pragma unroll
+                for (int i = 0; i < 2; i++) {
+                    if (!ok[i]) continue;
+                    const size_t m = out_img + pix[i];
+#pragma unroll
+                    for (int j = 0; j < NT; j++) {
+                        const int nb = nc * BN + j * 32 + 16 * (lane >> 5);
+                        if (nb >= a.N) continue;
+                        int c[16];
+#pragma unroll
+                        for (int g = 0; g < 4; g++) {
+                            const v4i bzv = *reinterpret_cast<const v4i *>(bz + nb + 4 * g);
+#pragma unroll
+                            for (int e = 0; e < 4; e++) c[4 * g + e] = acc[i][j][4 * g + e] - bzv[e];
+                        }
+                        int gmn = c[0], gmx = c[0];
+#pragma unroll
+                        for (int e = 1; e < 16; e++) { gmn = min(gmn, c[e]); gmx = max(gmx, c[e]); }
+                        mn = min(mn, gmn); mx = max(mx, gmx);
+                        if (FUSED) {
+                            if (__any(gmx > c_hi || gmn < c_lo)) {
+#pragma unroll
+                                for (int e = 0; e < 16; e++) { nhi += c[e] > c_hi ? 1u : 0u; nlo += c[e] < c_lo ? 1u : 0u; }
+                            }
+                            v4i packed;
+                            if (full_grid) {
+#pragma unroll
+                                for (int g = 0; g < 4; g++) {
+                                    unsigned w = 0;
+#pragma unroll
+                                    for (int e = 0; e < 4; e++) {
+                                        const float f = rintf(__fmul_rn((float)c[4 * g + e], rq.mult)) + zoff;
+                                        w = __builtin_amdgcn_cvt_pk_u8_f32(f, e, w);        // saturates to 0..255
+                                    }
+                                    packed[g] = (int)(w ^ 0x80808080u);
+                                }
+                            } else {
+#pragma unroll
+                                for (int g = 0; g < 4; g++) {
+                                    unsigned w = 0;
+#pragma unroll
+                                    for (int e = 0; e < 4; e++) {
+                                        float f = rintf(__fmul_rn((float)c[4 * g + e], rq.mult));
+                                        f = __builtin_amdgcn_fmed3f(f, rq.flo, rq.fhi) + zoff;
+                                        w = __builtin_amdgcn_cvt_pk_u8_f32(f, e, w);
+                                    }
+                                    packed[g] = (int)(w ^ 0x80808080u);
+                                }
+                            }
+                            *reinterpret_cast<v4i *>(a.out8 + m * a.N + nb) = packed;
                         } else {
-                            const v4i v = {c[0], c[1], c[2], c[3]};
-                            *reinterpret_cast<v4i *>(a.out32 + m * a.N + nb + 4 * g) = v;
+#pragma unroll
+                            for (int g = 0; g < 4; g++) {
+                                const v4i v = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
+                                *reinterpret_cast<v4i *>(a.out32 + m * a.N + nb + 4 * g) = v;
+                            }
                         }
                     }
-                    if (FUSED) *reinterpret_cast<v4i *>(a.out8 + m * a.N + nb) = packed;
                 }
             }
         }
+        __syncthreads();
     }
 
-    __syncthreads();
-    hq_block_stats_commit(mn, mx, lane == 0 ? s_lo : 0u, lane == 0 ? s_hi : 0u, a.st, red);
+    hq_block_stats_commit_n<BAND_THREADS>(mn, mx, nlo, nhi, a.st, red);
     if (blockIdx.x == 0 && tid == 0) {
         a.st->acc_scale = acc_scale;
         atomicAdd((unsigned long long *)&a.st->count, a.count);
@@ -256,22 +333,24 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_band_kernel(const BandArgs a
 
 unsigned magic32(unsigned d) { return (unsigned)(((1ull << 32) + d - 1) / d); }
 
-template <int C, int KSZ, int NT, int NPF>
+constexpr size_t BAND_LDS_MAX = 160 * 1024;
+
+template <int C, int KSZ, int NT, int PR, int PJ>
 int launch_band(const BandArgs &a, int blocks, size_t lds, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, NPF, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, NPF, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX) != hipSuccess)
             return HQ_E_HIP;
         configured = true;
     }
     if (a.out32 == nullptr)
-        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, NPF, true>), dim3(blocks), dim3(HQ_THREADS), lds, s, a);
+        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, true>), dim3(blocks), dim3(BAND_THREADS), lds, s, a);
     else
-        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, NPF, false>), dim3(blocks), dim3(HQ_THREADS), lds, s, a);
+        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, false>), dim3(blocks), dim3(BAND_THREADS), lds, s, a);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }
 
@@ -298,18 +377,19 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
         a.stride = 1; a.pad = p->R - 1 - p->pad; a.flip = 1;
     }
     const int KSZ = p->R;
-    int NT, NPF;
-    if (C == 64 && KSZ == 3) { NT = 2; NPF = 8; }
-    else if (C == 32 && KSZ == 1) { NT = 2; NPF = 4; }
-    else if (C == 192 && KSZ == 1) { NT = 1; NPF = 16; }
+    int NT, PJ;
+    if (C == 64 && KSZ == 3) { NT = 2; PJ = 1; }
+    else if (C == 32 && KSZ == 1) { NT = 2; PJ = 1; }
+    else if (C == 192 && KSZ == 1) { NT = 1; PJ = 3; }
     else return HQ_E_BADSHAPE;
     if ((a.N % 16) != 0 || a.Ho * a.Wo >= 65536) return HQ_E_BADSHAPE;
     const int BN = 32 * NT;
     a.npad = (a.N + BN - 1) / BN * BN;
     a.PW = (a.Wo - 1) * a.stride + KSZ;
+    if (a.PW * (C / 16) > 256 * PJ) return HQ_E_BADSHAPE;
 
-    // bands: at least two workgroups per CU when the batch allows it
-    int bpi = (512 + p->B - 1) / p->B;
+    // bands: one workgroup per CU when the batch allows it
+    int bpi = (256 + p->B - 1) / p->B;
     if (bpi > a.Ho) bpi = a.Ho;
     if (bpi < 1) bpi = 1;
     a.rows_per_band = (a.Ho + bpi - 1) / bpi;
@@ -325,16 +405,21 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
         }
     }
     a.PRmax = prmax;
-    const int rowchunks = a.PW * (C / 16);
-    if ((long)prmax * rowchunks > (long)NPF * HQ_THREADS) return HQ_E_BADSHAPE;
-    if ((long)prmax * rowchunks >= 65536 || rowchunks >= 65536) return HQ_E_BADSHAPE;
-    const size_t lds = (size_t)a.npad * KSZ * KSZ * C + (size_t)a.npad * 4 + (size_t)prmax * a.PW * (C + 16) + 64;
-    if (lds > 80 * 1024) return HQ_E_BADSHAPE;
+    const size_t lds = (size_t)a.npad * KSZ * KSZ * C + (size_t)a.npad * 4 + 2 * (size_t)prmax * a.PW * (C + 16) + 128;
+    if (lds > BAND_LDS_MAX) return HQ_E_BADSHAPE;
     a.magic_Wo = magic32((unsigned)a.Wo);
-    a.magic_row = magic32((unsigned)rowchunks);
     a.count = (unsigned long long)p->B * a.Ho * a.Wo * a.N;
     const int blocks = p->B * a.bands_per_image;
-    if (C == 64) return launch_band<64, 3, 2, 8>(a, blocks, lds, stream);
-    if (C == 32) return launch_band<32, 1, 2, 4>(a, blocks, lds, stream);
-    return launch_band<192, 1, 1, 16>(a, blocks, lds, stream);
+    if (C == 64) {
+        if (prmax <= 8) return launch_band<64, 3, 2, 8, 1>(a, blocks, lds, stream);
+        if (prmax <= 12) return launch_band<64, 3, 2, 12, 1>(a, blocks, lds, stream);
+        return HQ_E_BADSHAPE;
+    }
+    if (C == 32) {
+        if (prmax <= 6) return launch_band<32, 1, 2, 6, 1>(a, blocks, lds, stream);
+        if (prmax <= 14) return launch_band<32, 1, 2, 14, 1>(a, blocks, lds, stream);
+        return HQ_E_BADSHAPE;
+    }
+    if (prmax <= 6) return launch_band<192, 1, 1, 6, 3>(a, blocks, lds, stream);
+    return HQ_E_BADSHAPE;
 }

@@ -96,16 +96,17 @@ struct HqAdd { __device__ int operator()(int a, int b) const { return a + b; } }
 
 // Merges one workgroup's statistics into the tensor's record: wavefront reduction, a
 // second level through LDS, then one atomic per field from one lane.  `red` is LDS space
-// for 4 * (HQ_THREADS / 64) ints.  Must be called by all HQ_THREADS threads.
-__device__ inline void hq_block_stats_commit(int mn, int mx, unsigned nlo, unsigned nhi,
-                                             hq_stats *st, int *red)
+// for 4 * (NTHREADS / 64) ints.  Must be called by all NTHREADS threads of the workgroup.
+template <int NTHREADS>
+__device__ inline void hq_block_stats_commit_n(int mn, int mx, unsigned nlo, unsigned nhi,
+                                               hq_stats *st, int *red)
 {
     mn = hq_wave_reduce(mn, HqMin());
     mx = hq_wave_reduce(mx, HqMax());
     nlo = (unsigned)hq_wave_reduce((int)nlo, HqAdd());
     nhi = (unsigned)hq_wave_reduce((int)nhi, HqAdd());
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    constexpr int NW = HQ_THREADS / 64;
+    constexpr int NW = NTHREADS / 64;
     if (lane == 0) { red[wave] = mn; red[NW + wave] = mx; red[2 * NW + wave] = (int)nlo; red[3 * NW + wave] = (int)nhi; }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -118,4 +119,9 @@ __device__ inline void hq_block_stats_commit(int mn, int mx, unsigned nlo, unsig
         if (lo) atomicAdd((unsigned long long *)&st->clip_lo, lo);
         if (hi) atomicAdd((unsigned long long *)&st->clip_hi, hi);
     }
+}
+
+__device__ inline void hq_block_stats_commit(int mn, int mx, unsigned nlo, unsigned nhi, hq_stats *st, int *red)
+{
+    hq_block_stats_commit_n<HQ_THREADS>(mn, mx, nlo, nhi, st, red);
 }
