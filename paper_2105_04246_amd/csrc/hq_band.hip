@@ -59,20 +59,25 @@ template <int C> __device__ inline int wswz(int i)
     return (C % 128 == 0) ? (i & 7) : (C % 64 == 0) ? ((i >> 1) & 3) : ((i >> 2) & 1);
 }
 
-// Largest accumulator value that does not clip high / smallest that does not clip low.
+// Largest accumulator value that does not clip high / smallest that does not clip low:
+// bisection on the exact requantization formula (monotone in c; c = 0 never clips because the
+// zero point lies on the grid).
 __device__ inline int clip_threshold(float mult, float bound, bool high)
 {
-    auto inside = [&](long long c) {
-        float r = rintf(__fmul_rn((float)(int)c, mult));
+    auto inside = [&](int c) {
+        const float r = rintf(__fmul_rn((float)c, mult));
         return high ? r <= bound : r >= bound;
     };
-    long long good = 0, bad = high ? (long long)INT_MAX + 1 : (long long)INT_MIN - 1;   // c = 0 never clips
     if (inside(high ? INT_MAX : INT_MIN)) return high ? INT_MAX : INT_MIN;
-    while ((high ? bad - good : good - bad) > 1) {
-        long long mid = good + (bad - good) / 2;
+    // invariant: inside(good), !inside(bad); distances fit 32 bits as unsigned
+    int good = 0, bad = high ? INT_MAX : INT_MIN;
+    while (true) {
+        const unsigned dist = high ? (unsigned)bad - (unsigned)good : (unsigned)good - (unsigned)bad;
+        if (dist <= 1u) break;
+        const int mid = high ? (int)((unsigned)good + dist / 2) : (int)((unsigned)good - dist / 2);
         if (inside(mid)) good = mid; else bad = mid;
     }
-    return (int)good;
+    return good;
 }
 
 // PR: patch rows prefetched per tile (>= PRmax), PJ: 16-byte column chunks per thread and row.
@@ -233,31 +238,54 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
 #pragma unroll
                         for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
                 if (active) {
+                    // Fragments of tap t+1 are requested before the MFMAs of tap t are issued, so
+                    // LDS latency hides behind the matrix cores (two register buffers).
                     const int8_t *Wc = Wl + nc * BN * WROW;
-#pragma unroll 1
-                    for (int r = 0; r < KSZ; r++)
-#pragma unroll 1
-                        for (int s = 0; s < KSZ; s++) {
-                            const int toff = (r * a.PW + s) * PP;
+                    v4i wfA[KS][NT], afA[KS][2], wfB[KS][NT], afB[KS][2];
+                    auto load_tap = [&](int t, v4i (&wf)[KS][NT], v4i (&af)[KS][2]) {
+                        const int toff = ((t / KSZ) * a.PW + (t % KSZ)) * PP;
 #pragma unroll
-                            for (int ks = 0; ks < KS; ks++) {
-                                v4i wf[NT], af[2];
+                        for (int ks = 0; ks < KS; ks++) {
+#pragma unroll
+                            for (int j = 0; j < NT; j++)
+                                wf[ks][j] = *reinterpret_cast<const v4i *>(Wc + wbase[j][ks] + t * C);
+#pragma unroll
+                            for (int i = 0; i < 2; i++)
+                                af[ks][i] = *reinterpret_cast<const v4i *>(Pg + abase[i] + toff + ks * 32);
+                        }
+                    };
+                    auto mfma_tap = [&](v4i (&wf)[KS][NT], v4i (&af)[KS][2]) {
+#pragma unroll
+                        for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+                            for (int i = 0; i < 2; i++)
 #pragma unroll
                                 for (int j = 0; j < NT; j++)
-                                    wf[j] = *reinterpret_cast<const v4i *>(Wc + wbase[j][ks] + (r * KSZ + s) * C);
+                                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+                    };
+                    load_tap(0, wfA, afA);
 #pragma unroll
-                                for (int i = 0; i < 2; i++)
-                                    af[i] = *reinterpret_cast<const v4i *>(Pg + abase[i] + toff + ks * 32);
-#pragma unroll
-                                for (int i = 0; i < 2; i++)
-#pragma unroll
-                                    for (int j = 0; j < NT; j++)
-                                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
-                            }
-                        }
+                    for (int t = 0; t < TAPS; t += 2) {
+                        if (t + 1 < TAPS) load_tap(t + 1, wfB, afB);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mfma_tap(wfA, afA);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (t + 2 < TAPS) load_tap(t + 2, wfA, afA);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (t + 1 < TAPS) mfma_tap(wfB, afB);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             } else {
                 // -------------------------------------------------- vector-ALU phase
+                v4i bzv[NT][4];                            // z_a * bsum of this lane's 16 channels per column block
+#pragma unroll
+                for (int j = 0; j < NT; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const int nb = nc * BN + j * 32 + 16 * (lane >> 5);   // < npad
+                        bzv[j][g] = *reinterpret_cast<const v4i *>(bz + nb + 4 * g);
+                    }
                 if (have_pf) stash();                      // nobody reads this group's patch now
 #pragma unroll
                 for (int i = 0; i < 2; i++) {
@@ -269,19 +297,31 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                         if (nb >= a.N) continue;
                         int c[16];
 #pragma unroll
+                        for (int g = 0; g < 4; g++)
+#pragma unroll
+                            for (int e = 0; e < 4; e++) c[4 * g + e] = acc[i][j][4 * g + e] - bzv[j][g][e];
+                        // min / max per quad, then per group; clipped values are counted exactly but
+                        // only inside quads whose own extremes cross the thresholds
+                        int qmn[4], qmx[4];
+#pragma unroll
                         for (int g = 0; g < 4; g++) {
-                            const v4i bzv = *reinterpret_cast<const v4i *>(bz + nb + 4 * g);
-#pragma unroll
-                            for (int e = 0; e < 4; e++) c[4 * g + e] = acc[i][j][4 * g + e] - bzv[e];
+                            qmn[g] = min(min(c[4 * g], c[4 * g + 1]), min(c[4 * g + 2], c[4 * g + 3]));
+                            qmx[g] = max(max(c[4 * g], c[4 * g + 1]), max(c[4 * g + 2], c[4 * g + 3]));
                         }
-                        int gmn = c[0], gmx = c[0];
-#pragma unroll
-                        for (int e = 1; e < 16; e++) { gmn = min(gmn, c[e]); gmx = max(gmx, c[e]); }
+                        const int gmn = min(min(qmn[0], qmn[1]), min(qmn[2], qmn[3]));
+                        const int gmx = max(max(qmx[0], qmx[1]), max(qmx[2], qmx[3]));
                         mn = min(mn, gmn); mx = max(mx, gmx);
                         if (FUSED) {
                             if (__any(gmx > c_hi || gmn < c_lo)) {
 #pragma unroll
-                                for (int e = 0; e < 16; e++) { nhi += c[e] > c_hi ? 1u : 0u; nlo += c[e] < c_lo ? 1u : 0u; }
+                                for (int g = 0; g < 4; g++)
+                                    if (__any(qmx[g] > c_hi || qmn[g] < c_lo)) {
+#pragma unroll
+                                        for (int e = 0; e < 4; e++) {
+                                            nhi += c[4 * g + e] > c_hi ? 1u : 0u;
+                                            nlo += c[4 * g + e] < c_lo ? 1u : 0u;
+                                        }
+                                    }
                             }
                             v4i packed;
                             if (full_grid) {
