@@ -34,6 +34,7 @@ struct WgradArgs {
     int R, S, H, W, OH, OW, stride, pad;
     int m_per_split;               // multiple of MB
     int ctiles;                    // tiles along C inside one tap
+    int xt, yt, splits;            // tile columns (taps * ctiles), tile rows, pixel splits
     int g16, x16;                  // rows of G / X are 16-byte aligned (N % 16 == 0 / C % 16 == 0)
 };
 
@@ -65,7 +66,7 @@ template <int P> __device__ inline v4i read_frag_tr(const int8_t *tile, int lane
 template <int TN, int TK>
 __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 {
-    constexpr int PG = TN + 16, PX = TK + 16;           // LDS pitches
+    constexpr int PG = TN + 32, PX = TK + 32;           // LDS pitches (32 mod 64: best for the transposing reads)
     constexpr int WTN = TN / 2, WTK = TK / 2;           // 2 x 2 wavefronts
     constexpr int NT = WTN / 32, KT = WTK / 32;
     constexpr int GCH = TN / 16, XCH = TK / 16;         // 16-byte chunks per tile row
@@ -77,15 +78,33 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave >> 1, wk = wave & 1;
-    const int tap = blockIdx.x / a.ctiles, c0 = (blockIdx.x % a.ctiles) * TK;
+    // Workgroup -> (tile column bx, tile row by, pixel split bz).  All tile columns and rows of
+    // one pixel split read the same X / dY rows; consecutive workgroup ids go round-robin over
+    // the 8 XCDs, so the ids are re-mapped to keep one split's tiles on one XCD, back to back,
+    // where its L2 serves the re-reads.
+    int bx, by, bz;
+    {
+        const int per_split = a.xt * a.yt, total = per_split * a.splits;
+        const int full = (total / (8 * per_split)) * (8 * per_split);   // ids covered by complete groups of 8 splits
+        int split, tile;
+        if ((int)blockIdx.x < full) {
+            const int grp = blockIdx.x / (8 * per_split), r = blockIdx.x % (8 * per_split);
+            split = grp * 8 + (r & 7); tile = r >> 3;
+        } else {
+            const int r = blockIdx.x - full;
+            split = full / per_split + r / per_split; tile = r % per_split;
+        }
+        bx = tile % a.xt; by = tile / a.xt; bz = split;
+    }
+    const int tap = bx / a.ctiles, c0 = (bx % a.ctiles) * TK;
     const int tr = tap / a.S, ts = tap % a.S;
-    const int n0 = blockIdx.y * TN;
-    const int m_begin = blockIdx.z * a.m_per_split;
+    const int n0 = by * TN;
+    const int m_begin = bz * a.m_per_split;
     const int m_end = min(a.M, m_begin + a.m_per_split);
     const int zx = a.xq->zero_point;
     const int fill = (zx & 0xff) * 0x01010101;
-    const bool do_gsum = blockIdx.x == 0 && wk == 0;     // column sums of G: first tile column
-    const bool do_xsum = blockIdx.y == 0 && wn == 0;     // column sums of Xg: first tile row
+    const bool do_gsum = bx == 0 && wk == 0;     // column sums of G: first tile column
+    const bool do_xsum = by == 0 && wn == 0;     // column sums of Xg: first tile row
 
     v4i greg[GLD], xreg[XLD];
     auto load_stage = [&](int mb) {
@@ -277,11 +296,11 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     int splits = (2048 + xt * yt - 1) / (xt * yt);          // aim at ~8 workgroups per CU
     if (splits > stages_total) splits = stages_total;
     if (splits < 1) splits = 1;
-    if (splits > 65535) splits = 65535;
     const int stages_per = (stages_total + splits - 1) / splits;
     a.m_per_split = stages_per * MB;
     splits = (stages_total + stages_per - 1) / stages_per;
-    dim3 grid((unsigned)xt, (unsigned)yt, (unsigned)splits);
+    a.xt = xt; a.yt = yt; a.splits = splits;
+    dim3 grid((unsigned)(xt * yt * splits));
     if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128>), grid, dim3(HQ_THREADS), 0, stream, a);
     else     hipLaunchKernelGGL((hq_wgrad_kernel<64, 64>), grid, dim3(HQ_THREADS), 0, stream, a);
 
