@@ -59,27 +59,6 @@ template <int C> __device__ inline int wswz(int i)
     return (C % 128 == 0) ? (i & 7) : (C % 64 == 0) ? ((i >> 1) & 3) : ((i >> 2) & 1);
 }
 
-// Largest accumulator value that does not clip high / smallest that does not clip low:
-// bisection on the exact requantization formula (monotone in c; c = 0 never clips because the
-// zero point lies on the grid).
-__device__ inline int clip_threshold(float mult, float bound, bool high)
-{
-    auto inside = [&](int c) {
-        const float r = rintf(__fmul_rn((float)c, mult));
-        return high ? r <= bound : r >= bound;
-    };
-    if (inside(high ? INT_MAX : INT_MIN)) return high ? INT_MAX : INT_MIN;
-    // invariant: inside(good), !inside(bad); distances fit 32 bits as unsigned
-    int good = 0, bad = high ? INT_MAX : INT_MIN;
-    while (true) {
-        const unsigned dist = high ? (unsigned)bad - (unsigned)good : (unsigned)good - (unsigned)bad;
-        if (dist <= 1u) break;
-        const int mid = high ? (int)((unsigned)good + dist / 2) : (int)((unsigned)good - dist / 2);
-        if (inside(mid)) good = mid; else bad = mid;
-    }
-    return good;
-}
-
 // PR: patch rows prefetched per tile (>= PRmax), PJ: 16-byte column chunks per thread and row.
 template <int C, int KSZ, int NT, int PR, int PJ, bool FUSED>
 __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
@@ -177,8 +156,8 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                 wv[k] = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
         }
         if (FUSED && base == 0) {
-            c_hi = clip_threshold(rq.mult, rq.fhi, true);
-            c_lo = clip_threshold(rq.mult, rq.flo, false);
+            c_hi = hq_clip_threshold(rq.mult, rq.fhi, true);
+            c_lo = hq_clip_threshold(rq.mult, rq.flo, false);
         }
 #pragma unroll
         for (int k = 0; k < WB; k++) {

@@ -89,6 +89,148 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_kernel(const DwArgs a
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// 3x3, stride 1 (forward, and input gradient as the same stencil with mirrored taps): the
+// shape of the depthwise layers of MobileNetV2-style blocks (Table 5, DW rows).
+// A thread owns four channels of one output column and slides down a strip of rows, keeping
+// the 3x3 window unpacked in registers: per output row it loads three new words (one input
+// row of the window), so an input byte is requested 3 times (by the three neighbouring
+// columns, which sit in adjacent lanes and hit the same cache lines) instead of 9.  Lanes run
+// along (column, channel) of a row, which is how NHWC lies in memory: loads and the 4-code
+// stores are contiguous across the wavefront.  The next row's words are requested before the
+// current row is multiplied.
+// ---------------------------------------------------------------------------------------
+struct Dw3Args {
+    const int8_t *A, *Wt;
+    const int32_t *wsum;
+    const hq_qparams *aq, *bq;
+    const hq_range *range;
+    int8_t *out8;
+    int32_t *out32;
+    hq_qparams *outq;
+    hq_stats *st;
+    int B, H, W, C;                // input and output have the same size (pad 1)
+    int rows_per_strip, flip;
+};
+
+__device__ inline void dw_unpack(int v, int *dst)
+{
+#pragma unroll
+    for (int e = 0; e < 4; e++) dst[e] = sbyte(v, e);
+}
+
+__global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
+{
+    __shared__ int red[4 * (HQ_THREADS / 64)];
+    const int c4n = a.C >> 2, rowwords = a.W * c4n;
+    const int q = blockIdx.x * HQ_THREADS + threadIdx.x;           // word inside an output row
+    const bool live = q < rowwords;
+    const int qq = live ? q : 0;
+    const int ox = qq / c4n, c = (qq - ox * c4n) * 4;
+    const int y0 = blockIdx.y * a.rows_per_strip, y1 = min(a.H, y0 + a.rows_per_strip);
+    const int8_t *img = a.A + (size_t)blockIdx.z * a.H * a.W * a.C;
+    const size_t out_img = (size_t)blockIdx.z * a.H * a.W;
+
+    const int za = a.aq->zero_point;
+    const int fill = (za & 0xff) * 0x01010101;
+    const bool fused = a.out32 == nullptr;
+    const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
+    HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
+    bool full_grid = true;
+    int c_lo = INT_MIN, c_hi = INT_MAX;
+    if (fused) {
+        rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
+        full_grid = a.range->qlo == -128 && a.range->qhi == 127;
+        c_hi = hq_clip_threshold(rq.mult, rq.fhi, true);
+        c_lo = hq_clip_threshold(rq.mult, rq.flo, false);
+    }
+    const float zoff = (float)(rq.z + 128);
+
+    // weights of the four channels, unpacked; mirrored for the input gradient
+    int w[9][4];
+#pragma unroll
+    for (int t = 0; t < 9; t++) {
+        const int ts = a.flip ? 8 - t : t;
+        dw_unpack(*reinterpret_cast<const int *>(a.Wt + (size_t)ts * a.C + c), w[t]);
+    }
+    const v4i wsv = *reinterpret_cast<const v4i *>(a.wsum + c);
+    int zw[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) zw[e] = za * wsv[e];
+
+    const bool okl = ox > 0, okr = ox + 1 < a.W;
+    const size_t rowbytes = (size_t)a.W * a.C;
+    const int8_t *pcol = img + (size_t)ox * a.C + c;                 // this thread's column in input row 0
+    auto load_row = [&](const int8_t *p, bool rowok, int *dst) {      // three packed words of one input row
+        dst[0] = (rowok && okl) ? *reinterpret_cast<const int *>(p - a.C) : fill;
+        dst[1] = rowok ? *reinterpret_cast<const int *>(p) : fill;
+        dst[2] = (rowok && okr) ? *reinterpret_cast<const int *>(p + a.C) : fill;
+    };
+    const int8_t *pn = pcol + (size_t)(y0 > 0 ? y0 - 1 : 0) * rowbytes;   // walks down the input rows
+    size_t o = (out_img + (size_t)y0 * a.W + ox) * a.C + c;           // output word of row oy, advanced per row
+
+    int mn = INT_MAX, mx = INT_MIN;
+    unsigned nlo = 0, nhi = 0;
+    int win[3][3][4];                                                // [row slot][column][channel]
+    int ring[3][3];                                                  // packed words of the next three input rows
+    if (live) {
+        int tmp[3];
+        load_row(pn, y0 > 0, tmp);                                   // row y0 - 1
+        if (y0 > 0) pn += rowbytes;
+#pragma unroll
+        for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[0][s]);
+        load_row(pn, true, tmp);                                     // row y0
+        pn += rowbytes;
+#pragma unroll
+        for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[1][s]);
+#pragma unroll
+        for (int k = 0; k < 3; k++) {                                // rows y0 + 1 .. y0 + 3 in flight
+            load_row(pn, y0 + 1 + k < a.H, ring[k]);
+            pn += rowbytes;
+        }
+    }
+    // one output row; TOP / MID / BOT name the register slots of input rows oy-1, oy, oy+1
+#define DW_STEP(TOP, MID, BOT, RING)                                                                        \
+    if (live && oy < y1) {                                                                            \
+        _Pragma("unroll") for (int s = 0; s < 3; s++) dw_unpack(ring[RING][s], win[BOT][s]);            \
+        if (oy + 3 < y1) { load_row(pn, oy + 4 < a.H, ring[RING]); pn += rowbytes; }                   \
+        int cv[4];                                                                                    \
+        _Pragma("unroll") for (int e = 0; e < 4; e++) {                                                 \
+            int acc = 0;                                                                              \
+            _Pragma("unroll") for (int s = 0; s < 3; s++)                                               \
+                acc += __mul24(win[TOP][s][e], w[s][e]) + __mul24(win[MID][s][e], w[3 + s][e]) + __mul24(win[BOT][s][e], w[6 + s][e]); \
+            cv[e] = acc - zw[e];                                                                      \
+        }                                                                                             \
+        const int qmn = min(min(cv[0], cv[1]), min(cv[2], cv[3]));                                    \
+        const int qmx = max(max(cv[0], cv[1]), max(cv[2], cv[3]));                                    \
+        mn = min(mn, qmn); mx = max(mx, qmx);                                                         \
+        if (fused) {                                                                                  \
+            if (__any(qmx > c_hi || qmn < c_lo)) {                                                    \
+                _Pragma("unroll") for (int e = 0; e < 4; e++) {                                         \
+                    nhi += cv[e] > c_hi ? 1u : 0u; nlo += cv[e] < c_lo ? 1u : 0u;                     \
+                }                                                                                     \
+            }                                                                                         \
+            *reinterpret_cast<unsigned *>(a.out8 + o) = hq_requant4_u8(cv, rq, zoff, full_grid) ^ 0x80808080u; \
+        } else {                                                                                      \
+            const v4i v = {cv[0], cv[1], cv[2], cv[3]};                                               \
+            *reinterpret_cast<v4i *>(a.out32 + o) = v;                                                \
+        }                                                                                             \
+    }                                                                                                 \
+    oy++; o += rowbytes;
+    for (int oy = y0; oy < y1;) {
+        DW_STEP(0, 1, 2, 0)
+        DW_STEP(1, 2, 0, 1)
+        DW_STEP(2, 0, 1, 2)
+    }
+#undef DW_STEP
+    hq_block_stats_commit(mn, mx, nlo, nhi, a.st, red);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+        a.st->acc_scale = acc_scale;
+        atomicAdd((unsigned long long *)&a.st->count, (unsigned long long)a.B * a.H * a.W * (unsigned long long)a.C);
+        if (fused) *a.outq = a.range->qp;
+    }
+}
+
 // Weight gradient: acc[tap][c] = sum_m Xg[m][tap][c] * G[m][c], plus the column sums that
 // remove the zero points.  Each workgroup takes a run of pixels; a thread owns four channels
 // and strides over the run; partial sums meet in LDS and leave with one atomic per value.
@@ -197,6 +339,24 @@ int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const h
     a.C = p->C; a.R = p->R; a.S = p->S; a.stride = p->stride; a.pad = p->pad; a.dgrad = dgrad;
     if (!dgrad) { a.M = p->B * OH * OW; a.Hs = p->H; a.Ws = p->W; a.Ho = OH; a.Wo = OW; }
     else        { a.M = p->B * p->H * p->W; a.Hs = OH; a.Ws = OW; a.Ho = p->H; a.Wo = p->W; }
+    if (p->R == 3 && p->S == 3 && p->stride == 1 && p->pad == 1 && p->B <= 65535) {
+        Dw3Args d;
+        d.A = A; d.Wt = Wt; d.wsum = wsum; d.aq = aq; d.bq = bq; d.range = range;
+        d.out8 = out8; d.out32 = out32; d.outq = outq; d.st = st;
+        d.B = p->B; d.H = p->H; d.W = p->W; d.C = p->C; d.flip = dgrad;
+        const int xb = (p->W * (p->C / 4) + HQ_THREADS - 1) / HQ_THREADS;
+        // strips: enough workgroups to fill the chip several times, rows per strip a multiple of 3
+        int strips = (4096 + xb * p->B - 1) / (xb * p->B);
+        if (strips < 1) strips = 1;
+        int rps = (p->H + strips - 1) / strips;
+        rps = (rps + 2) / 3 * 3;
+        if (rps < 6) rps = 6;
+        d.rows_per_strip = rps;
+        strips = (p->H + rps - 1) / rps;
+        hipLaunchKernelGGL(hq_dw3x3_kernel, dim3((unsigned)xb, (unsigned)strips, (unsigned)p->B), dim3(HQ_THREADS), 0,
+                           stream, d);
+        return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+    }
     const size_t total = (size_t)a.M * (a.C / 4);
     size_t blocks = (total + HQ_THREADS - 1) / HQ_THREADS;
     if (blocks > 256u * 64u) blocks = 256u * 64u;

@@ -62,6 +62,41 @@ __device__ inline int hq_requant(int c, const HqRequant &q, unsigned &nlo, unsig
     return (int)r + q.z;
 }
 
+// Largest accumulator value that does not clip high / smallest that does not clip low:
+// bisection on the exact requantization formula (monotone in c; c = 0 never clips because the
+// zero point lies on the grid).  Lets the epilogues count clipped values with integer compares.
+__device__ inline int hq_clip_threshold(float mult, float bound, bool high)
+{
+    auto inside = [&](int c) {
+        const float r = rintf(__fmul_rn((float)c, mult));
+        return high ? r <= bound : r >= bound;
+    };
+    if (inside(high ? INT_MAX : INT_MIN)) return high ? INT_MAX : INT_MIN;
+    int good = 0, bad = high ? INT_MAX : INT_MIN;          // inside(good), !inside(bad)
+    while (true) {
+        const unsigned dist = high ? (unsigned)bad - (unsigned)good : (unsigned)good - (unsigned)bad;
+        if (dist <= 1u) break;
+        const int mid = high ? (int)((unsigned)good + dist / 2) : (int)((unsigned)good - dist / 2);
+        if (inside(mid)) good = mid; else bad = mid;
+    }
+    return good;
+}
+
+// Four accumulators -> four codes packed in one word.  zoff = zero point + 128: the codes are
+// formed as unsigned bytes by v_cvt_pk_u8_f32 (which saturates to 0..255: the clamp of the full
+// 8-bit grid) and flipped to signed storage by the caller with ^ 0x80808080.
+__device__ inline unsigned hq_requant4_u8(const int *c, const HqRequant &q, float zoff, bool full_grid)
+{
+    unsigned w = 0;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        float f = rintf(__fmul_rn((float)c[e], q.mult));
+        if (!full_grid) f = __builtin_amdgcn_fmed3f(f, q.flo, q.fhi);
+        w = __builtin_amdgcn_cvt_pk_u8_f32(f + zoff, e, w);
+    }
+    return w;
+}
+
 __device__ inline unsigned hq_pack4(int a, int b, int c, int d)
 {
     return (unsigned)(a & 0xff) | ((unsigned)(b & 0xff) << 8) | ((unsigned)(c & 0xff) << 16) | ((unsigned)d << 24);
