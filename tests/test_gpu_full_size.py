@@ -80,3 +80,71 @@ def test_c4_full_size_block(H, hq):
                 assert np.array_equal(dWa, ref) and np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
             del Xd, dYd
             torch.cuda.empty_cache()
+
+
+def test_c5_resnet18_stack_small_batch(H, hq):
+    """Every layer of the ResNet-18-shaped stack (7x7/2 stem on 4 input channels, 3x3 stages with
+    stride-2 downsampling and 1x1/2 shortcuts, FC 512->1000) at batch 4: dynamic init + one
+    in-hindsight iteration of fwd and dgrad (no dgrad for the stem), wgrad once; whole tensors
+    against the oracle."""
+    layers = wl.resnet18_layers(B=4)
+    assert len(layers) == 21
+    for idx, L in enumerate(layers):
+        yt, gt = H.TensorTrack(0.9, False), H.TensorTrack(0.9, True)
+        Wdev = None
+        for t in range(2):
+            X, W, dY = wl.layer_inputs(L, 5, t, idx, image_input=(idx == 0))
+            if Wdev is None:
+                W0, Wdev = W, H.DevWeights(L, W)
+            Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+            yt.step(L, "fwd", X, W0, Xd, Wdev)
+            if idx > 0:
+                gt.step(L, "dgrad", dY, W0, dYd, Wdev)
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref), L.name
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale)), L.name
+
+
+@pytest.mark.parametrize("which", ["stem_7x7", "s2_conv0", "s3_short", "s4_conv2", "fc"])
+def test_c5_full_batch_sampled(H, hq, which):
+    """Batch 256 (the size the step is quoted on): forward and dgrad of representative layers with
+    the oracle evaluated on sampled output rows; whole-tensor statistics are checked through
+    properties that hold at any size."""
+    layers = wl.resnet18_layers(B=256)
+    idx = [l.name for l in layers].index(which)
+    L = layers[idx]
+    X, W, dY = wl.layer_inputs(L, 5, 0, idx, image_input=(idx == 0))
+    Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
+    g = np.random.default_rng(7)
+    for op, A, Adev, sym in (("fwd", X, Xd, False), ("dgrad", dY, dYd, True)):
+        if op == "dgrad" and idx == 0:
+            continue
+        r, st = hq.new_range(0.9, sym), hq.new_stats()
+        dyn_codes, q0 = H.gpu_quantized_op(L, op, Adev, Wdev, r, st, "dynamic")
+        s0 = H.read_stats(st)
+        hq.hq_range_update(r, st)
+        codes, q = H.gpu_quantized_op(L, op, Adev, Wdev, r, st, "fused")
+        s1 = H.read_stats(st)
+        nrow = codes.size // codes.shape[-1]
+        rows = np.unique(np.concatenate([g.integers(0, nrow, 2000), [0, nrow - 1]]))
+        po = H.oracle_problem(L)
+        c = oracle.fwd_rows(po, A.codes, A.zero_point, W.codes, rows) if op == "fwd" else \
+            oracle.dgrad_rows(po, A.codes, A.zero_point, W.codes, rows)
+        a_scale = oracle.acc_scale(A.scale, W.scale)
+        # dynamic: the quantizer must be the one the GPU's own min/max imply, codes follow from it
+        gmin, gmax = np.float32(a_scale) * np.float32(s0["acc_min"]), np.float32(a_scale) * np.float32(s0["acc_max"])
+        sc, z = oracle.qparams(gmin, gmax, int(sym), -127 if sym else -128, 127)
+        assert np.float32(q0["scale"]) == sc and int(q0["zero_point"]) == z
+        want, _, _ = oracle.requant(c, a_scale, sc, z, -127 if sym else -128, 127)
+        assert np.array_equal(dyn_codes.reshape(nrow, -1)[rows], want)
+        assert int(s0["acc_min"]) <= c.min() and int(s0["acc_max"]) >= c.max()
+        assert int(s0["count"]) == codes.size and int(s0["clip_lo"]) == 0 and int(s0["clip_hi"]) == 0
+        # fused: range state after the first update, from the oracle's arithmetic
+        ref = oracle.Range.new(0.9, sym)
+        oracle.range_update(ref, int(s0["acc_min"]), int(s0["acc_max"]), a_scale)
+        oracle.range_update(ref, int(s0["acc_min"]), int(s0["acc_max"]), a_scale)
+        assert np.float32(q["scale"]) == np.float32(ref.scale) and int(q["zero_point"]) == ref.zero_point
+        want, _, _ = oracle.requant(c, a_scale, ref.scale, ref.zero_point, ref.qlo, ref.qhi)
+        assert np.array_equal(codes.reshape(nrow, -1)[rows], want)
+        assert (int(s1["acc_min"]), int(s1["acc_max"]), int(s1["count"])) == (int(s0["acc_min"]), int(s0["acc_max"]), codes.size)
