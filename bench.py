@@ -45,7 +45,7 @@ class Layer:
     def __init__(self, hq, torch, wl, L, X, W, dY):
         self.hq, self.torch, self.L = hq, torch, L
         self.p = hq.problem(L.kind, L.B, L.H, L.W, L.C, L.R, L.S, L.stride, L.pad, L.Cout)
-        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        dev = lambda a: a if torch.is_tensor(a) else torch.from_numpy(np.ascontiguousarray(a)).cuda()
         self.X, self.xq = dev(X.codes), hq.new_qparams(X.scale, X.zero_point)
         self.dY, self.gq = dev(dY.codes), hq.new_qparams(dY.scale, dY.zero_point)
         self.W, self.wq = dev(W.codes), hq.new_qparams(W.scale, 0)
@@ -103,6 +103,65 @@ class Layer:
 
     def dynamic_step(self):
         self.dyn_fwd(); self.upd_y(); self.dyn_dgrad(); self.upd_g(); self.wgrad()
+
+
+class DeviceLayer(Layer):
+    """Layer whose synthetic operands are drawn on the device (same recipe as workloads.py:
+    post-ReLU activations on the unsigned grid, He-normal symmetric weights, Laplace gradients),
+    used where host generation of a whole network's tensors would dominate the run."""
+
+    def __init__(self, hq, torch, wl, L, seed):
+        from collections import namedtuple
+        Q = namedtuple("Q", "codes scale zero_point")
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        x = torch.randn(wl.in_shape(L), generator=g, device="cuda").clamp_(min=0)
+        sx = float(x.max()) / 255.0
+        xc = (torch.round(x / sx).clamp_(0, 255) - 128).to(torch.int8)
+        fan_in = L.R * L.S * (1 if L.kind == wl.DEPTHWISE else L.C)
+        w = torch.randn(wl.w_shape(L), generator=g, device="cuda") * (2.0 / fan_in) ** 0.5
+        sw = float(w.abs().max()) / 127.0
+        wc = torch.round(w / sw).clamp_(-127, 127).to(torch.int8)
+        u = torch.rand(wl.out_shape(L), generator=g, device="cuda") - 0.5
+        gr = -1e-3 * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.4999999))
+        sg = float(gr.abs().max()) / 127.0
+        gc = torch.round(gr / sg).clamp_(-127, 127).to(torch.int8)
+        del x, w, u, gr
+        as_q = lambda t, s, z: Q(t, np.float32(s), z)
+        Layer.__init__(self, hq, torch, wl, L, as_q(xc, sx, -128), as_q(wc, sw, 0), as_q(gc, sg, 0))
+
+
+def c5_step(hq, torch, wl, reps=3):
+    """One quantized training step over the ResNet-18-shaped stack at batch 256: 21 forward,
+    20 dgrad (none for the stem) and 21 wgrad launches with in-hindsight ranges, against the same
+    step with the dynamic two-pass path."""
+    specs = wl.resnet18_layers(B=256)
+    layers = [DeviceLayer(hq, torch, wl, L, 1000 + i) for i, L in enumerate(specs)]
+    for ly in layers:
+        ly.init_ranges()
+
+    def fused():
+        for i, ly in enumerate(layers):
+            ly.fwd(); ly.upd_y()
+        for i, ly in reversed(list(enumerate(layers))):
+            if i > 0:
+                ly.dgrad(); ly.upd_g()
+            ly.wgrad()
+
+    def dynamic():
+        for i, ly in enumerate(layers):
+            ly.dyn_fwd(); ly.upd_y()
+        for i, ly in reversed(list(enumerate(layers))):
+            if i > 0:
+                ly.dyn_dgrad(); ly.upd_g()
+            ly.wgrad()
+
+    f_ms, d_ms = time_calls(torch, fused, reps, 1), time_calls(torch, dynamic, reps, 1)
+    ops = sum(2 * wl.macs(L) * (3 if i > 0 else 2) for i, L in enumerate(specs))
+    fb = sum(wl.fused_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
+    db = sum(wl.dynamic_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
+    return {"workload": "ResNet-18-shaped stack, batch 256 @224x224: 21 fwd + 20 dgrad + 21 wgrad", "ops": ops,
+            "fused_ms_per_step": f_ms, "dynamic_ms_per_step": d_ms, "fused_tops": ops / (f_ms * 1e-3) / 1e12,
+            "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb}}
 
 
 def time_calls(torch, fn, reps, warmup=2):
@@ -250,6 +309,8 @@ def main():
             del ly
             torch.cuda.empty_cache()
         out["other_layers"] = extra
+        out["resnet18_step"] = c5_step(hq, torch, wl)
+        torch.cuda.empty_cache()
 
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
