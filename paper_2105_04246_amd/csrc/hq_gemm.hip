@@ -1,25 +1,32 @@
-// Gather-GEMM on int8 MFMA with the fused in-hindsight epilogue (gfx950).
+// Gather-GEMM on int8 MFMA with the fused in-hindsight epilogue (gfx950): the general path of
+// hq_gemm_fwd / hq_gemm_dgrad and of pass 1 of the dynamic baseline, for every supported
+// shape that the weights-resident kernel does not take (large channel counts, linear layers,
+// strided input gradients, channel counts that are not multiples of 16).
 //
-// One kernel serves the forward pass and the input gradient of linear and convolution
-// layers (paper Sec. 3.1).  Both are  out[m][n] = sum_{tap,c} A[pix(m,tap)][c] * Bw[n][tap][c]:
-//   forward:  m = output pixel, A = X,  pix = (oh*stride - pad + r, ow*stride - pad + s)
-//   dgrad:    m = input pixel,  A = dY, pix = ((h + pad - r)/stride, (w + pad - s)/stride)
-//             where that division is exact and lands inside the output image.
-// Taps without a source pixel are filled with A's zero-point code (real zero), so that the
-// zero point leaves the sum as one term per output column: z_a * bsum[n].
+// Both operations are  out[m][n] = sum_{tap,c} A[pix(m,tap)][c] * Bw[n][tap][c]   (paper Sec. 3.1):
+//   forward:            m = output pixel, A = X,  pix = (oh*stride - pad + r, ow*stride - pad + s)
+//   dgrad, stride 1:    the same stencil over dY with padding R-1-pad and mirrored taps
+//   dgrad, stride > 1:  m = input pixel, A = dY, pix = ((h + pad - r)/stride, (w + pad - s)/stride)
+//                       where the division is exact and lands inside the output image
+// Taps without a source pixel are filled with A's zero-point code (real zero), so the zero
+// point leaves the sum as one term per output column, z_a * bsum[n].
+//
+// Tiling: 256 threads (2x2 or 4x1 wavefronts), v_mfma_i32_32x32x32_i8, weights as the first
+// operand.  Weight rows are stored in LDS in a permuted order so that a lane ends up with 16
+// consecutive output channels of one pixel (one 16-byte store).  K is staged through LDS
+// (two buffers, the next stage's global loads in flight during the current stage's MFMAs),
+// rows padded by 16 bytes to keep 16-byte fragment reads free of bank conflicts.  Tiles that
+// share their A rows (same pixels, different channel blocks) get consecutive slots on the
+// same XCD, so the second reader finds the rows in that XCD's L2.
 //
 // The accumulators never leave registers on the fused path (Sec. 3.2, static quantization):
-// the epilogue removes the zero point, folds min / max / clip counts of the tile into the
-// tensor's statistics (Sec. 4, step 2) and stores 8-bit codes quantized with the range that
-// was fixed before the launch (Sec. 4, step 1).  With `out32` set instead, the same kernel is
-// pass 1 of the dynamic baseline: it stores the corrected 32-bit outputs (eq. (5), "save
-// acc output") and gathers min / max only.
+// the epilogue removes the zero point, folds min / max / clip counts into the tensor's
+// statistics (Sec. 4, step 2) and stores codes quantized with the range fixed before the
+// launch (Sec. 4, step 1).  With `out32` set, the kernel is pass 1 of the dynamic baseline:
+// it stores the corrected 32-bit outputs (eq. (5), "save acc output") and gathers min / max.
 #include "hq_device.h"
 
 namespace {
-
-constexpr int BK = 64;            // bytes of reduction staged per step (two MFMA k-steps of 32)
-constexpr int PITCH = BK + 16;    // LDS row pitch: 80 B keeps 16-byte fragment reads conflict-free
 
 struct GemmArgs {
     const int8_t *A, *Bw;
@@ -34,17 +41,19 @@ struct GemmArgs {
     int Cs;                        // reduced channels per tap
     int cpt;                       // 16-byte chunks per tap = ceil(Cs / 16)
     int nchunks;                   // taps * cpt
-    int R, S;
+    int taps, S;
     int Hs, Ws;                    // spatial size of the gathered tensor A
     int Ho, Wo;                    // spatial size the row index m runs over
-    int stride, pad;
-    int dgrad;                     // 0 forward gather, 1 input-gradient gather
-    int aligned16;                 // Cs % 16 == 0: every chunk is one aligned 16-byte load
+    int stride, pad;               // stencil form: effective stride / padding
+    int flip;                      // weight taps mirrored (dgrad written as a stencil)
+    int m_tiles, n_tiles;
 };
 
-__device__ inline v4i load_chunk(const int8_t *p, int nbytes, bool aligned16, int fill)
+__device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
+
+template <bool ALIGNED> __device__ inline v4i load_chunk(const int8_t *p, int nbytes, int fill)
 {
-    if (aligned16) return *reinterpret_cast<const v4i *>(p);
+    if (ALIGNED) return *reinterpret_cast<const v4i *>(p);
     v4i v;
     const int *q = reinterpret_cast<const int *>(p);
     v[0] = nbytes > 0 ? q[0] : fill;
@@ -54,47 +63,68 @@ __device__ inline v4i load_chunk(const int8_t *p, int nbytes, bool aligned16, in
     return v;
 }
 
-template <int BM, int BN, int WGM, int WGN>
+// BKB: bytes of reduction per stage.  STRIDED: input gradient of a strided layer (gather with
+// exact-division test); otherwise the stencil form.  ALIGNED: Cs % 16 == 0.
+template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
 __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
 {
     static_assert(WGM * WGN == HQ_THREADS / 64, "four wavefronts");
-    constexpr int WTM = BM / WGM, WTN = BN / WGN;      // wavefront tile
-    constexpr int MT = WTM / 32, NT = WTN / 32;        // 32x32 MFMA tiles per wavefront
-    constexpr int AROWS = BM / 64;                     // A rows loaded per thread per stage
-    constexpr int BROWS = (BN + 63) / 64;              // B rows loaded per thread per stage
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
+    constexpr int MT = WTM / 32, NT = WTN / 32;         // 32x32 MFMA tiles per wavefront
+    constexpr int CPS = BKB / 16;                       // 16-byte chunks per row and stage
+    constexpr int RPP = HQ_THREADS / CPS;               // rows covered by one pass of the loader
+    constexpr int AROWS = BM / RPP, BROWS = (BN + RPP - 1) / RPP;
+    constexpr int PITCH = BKB + 16;
+    constexpr int KS = BKB / 32;
 
-    __shared__ __attribute__((aligned(16))) int8_t As[2][BM * PITCH];
-    __shared__ __attribute__((aligned(16))) int8_t Bs[2][BN * PITCH];
-    __shared__ int red[4 * (HQ_THREADS / 64)];
+    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+    int8_t *As = smem;                                   // [2][BM][PITCH]
+    int8_t *Bs = smem + 2 * BM * PITCH;                  // [2][BN][PITCH]
+    int *red = reinterpret_cast<int *>(smem + 2 * (BM + BN) * PITCH);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int n_tiles = (a.N + BN - 1) / BN;
-    const int tile_m = blockIdx.x / n_tiles, tile_n = blockIdx.x % n_tiles;
+
+    // tile of this workgroup: ids are dealt round-robin to the 8 XCDs; give each XCD a
+    // contiguous run of tiles (channel blocks of one pixel block next to each other)
+    int tile = blockIdx.x;
+    {
+        const int total = a.m_tiles * a.n_tiles, per = total / 8;
+        if (per > 0 && tile < per * 8) tile = (tile & 7) * per + (tile >> 3);
+    }
+    const int tile_m = tile / a.n_tiles, tile_n = tile - tile_m * a.n_tiles;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int za = a.aq->zero_point;
     const int fill = (za & 0xff) * 0x01010101;
 
-    // ---- per-thread gather state: AROWS rows of the A tile, one 16-byte column of them
-    const int cc = tid & 3;                 // chunk column inside the 64-byte stage
+    // ---- per-thread gather state
+    const int cc = tid % CPS, lrow = tid / CPS;
     const int8_t *abase[AROWS];
     int ay[AROWS], ax[AROWS];
     bool arow_ok[AROWS];
 #pragma unroll
     for (int i = 0; i < AROWS; i++) {
-        int m = m0 + (tid >> 2) + 64 * i;
+        const int m = m0 + lrow + RPP * i;
         arow_ok[i] = m < a.M;
-        int mm = arow_ok[i] ? m : 0;
-        int x = mm % a.Wo, y = (mm / a.Wo) % a.Ho, b = mm / (a.Wo * a.Ho);
+        const int mm = arow_ok[i] ? m : 0;
+        const int x = mm % a.Wo, y = (mm / a.Wo) % a.Ho, b = mm / (a.Wo * a.Ho);
         abase[i] = a.A + (size_t)b * a.Hs * a.Ws * a.Cs;
-        ay[i] = a.dgrad ? y + a.pad : y * a.stride - a.pad;
-        ax[i] = a.dgrad ? x + a.pad : x * a.stride - a.pad;
+        ay[i] = STRIDED ? y + a.pad : y * a.stride - a.pad;
+        ax[i] = STRIDED ? x + a.pad : x * a.stride - a.pad;
     }
-    const size_t brow_len = (size_t)a.R * a.S * a.Cs;      // bytes per weight row
-    // chunk cursor (same for A and B): chunk index -> (r, s, c16)
+    const int8_t *bbase[BROWS];
+    bool brow_ok[BROWS];
+    const size_t brow_len = (size_t)a.taps * a.Cs;
+#pragma unroll
+    for (int i = 0; i < BROWS; i++) {
+        const int row = lrow + RPP * i;                   // LDS row; holds channel sigma-permuted in its 32-block
+        const int n = n0 + (row & ~31) + sigma32(row & 31);
+        brow_ok[i] = row < BN && n < a.N;
+        bbase[i] = a.Bw + (size_t)(brow_ok[i] ? n : 0) * brow_len;
+    }
     int chunk = cc, c16 = cc % a.cpt, tap = cc / a.cpt;
-    int tr = tap / a.S, ts = tap % a.S;
+    int tr = tap / a.S, ts = tap - tr * a.S;
 
     v4i areg[AROWS], breg[BROWS];
     auto load_stage = [&]() {
@@ -102,42 +132,38 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
         const int coff = c16 * 16, nbytes = a.Cs - coff;
 #pragma unroll
         for (int i = 0; i < AROWS; i++) {
-            int iy, ix; bool ok = chunk_ok && arow_ok[i];
-            if (!a.dgrad) {
+            int iy, ix;
+            bool ok = chunk_ok && arow_ok[i];
+            if (!STRIDED) {
                 iy = ay[i] + tr; ix = ax[i] + ts;
             } else {
                 iy = ay[i] - tr; ix = ax[i] - ts;
-                if (a.stride != 1) {
-                    ok = ok && iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
-                    iy /= a.stride; ix /= a.stride;
-                }
+                ok = ok && iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
+                iy /= a.stride; ix /= a.stride;
             }
             ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
             v4i v = {fill, fill, fill, fill};
-            if (ok) v = load_chunk(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff, nbytes, a.aligned16, fill);
+            if (ok) v = load_chunk<ALIGNED>(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff, nbytes, fill);
             areg[i] = v;
         }
+        const int wtap = a.flip ? a.taps - 1 - tap : tap;
 #pragma unroll
         for (int i = 0; i < BROWS; i++) {
-            int row = (tid >> 2) + 64 * i, n = n0 + row;
             v4i v = {0, 0, 0, 0};
-            if (row < BN && n < a.N && chunk_ok)
-                v = load_chunk(a.Bw + (size_t)n * brow_len + (size_t)tap * a.Cs + coff, nbytes, a.aligned16, 0);
+            if (brow_ok[i] && chunk_ok) v = load_chunk<ALIGNED>(bbase[i] + (size_t)wtap * a.Cs + coff, nbytes, 0);
             breg[i] = v;
         }
-        // advance the cursor by one stage (4 chunks)
-        chunk += 4; c16 += 4;
+        chunk += CPS; c16 += CPS;
         while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == a.S) { ts = 0; tr++; } }
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < AROWS; i++)
-            *reinterpret_cast<v4i *>(&As[buf][((tid >> 2) + 64 * i) * PITCH + cc * 16]) = areg[i];
+            *reinterpret_cast<v4i *>(As + (buf * BM + lrow + RPP * i) * PITCH + cc * 16) = areg[i];
 #pragma unroll
-        for (int i = 0; i < BROWS; i++) {
-            int row = (tid >> 2) + 64 * i;
-            if (row < BN) *reinterpret_cast<v4i *>(&Bs[buf][row * PITCH + cc * 16]) = breg[i];
-        }
+        for (int i = 0; i < BROWS; i++)
+            if (lrow + RPP * i < BN)
+                *reinterpret_cast<v4i *>(Bs + (buf * BN + lrow + RPP * i) * PITCH + cc * 16) = breg[i];
     };
 
     v16i acc[MT][NT];
@@ -148,7 +174,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
 
-    const int KT = (a.nchunks + 3) / 4;
+    const int KT = (a.nchunks + CPS - 1) / CPS;
     load_stage();
     store_stage(0);
     __syncthreads();
@@ -157,15 +183,15 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
         const int buf = kt & 1;
         const bool more = kt + 1 < KT;
         if (more) load_stage();
-        const int ksteps = min(4, a.nchunks - 4 * kt) > 2 ? 2 : 1;
-        for (int ks = 0; ks < ksteps; ks++) {
+        const int8_t *Ab = As + (buf * BM + wm * WTM) * PITCH + frag_off;
+        const int8_t *Bb = Bs + (buf * BN + wn * WTN) * PITCH + frag_off;
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {                 // chunks past the end of K hold zero weights
             v4i wf[NT], af[MT];
 #pragma unroll
-            for (int j = 0; j < NT; j++)
-                wf[j] = *reinterpret_cast<const v4i *>(&Bs[buf][(wn * WTN + j * 32) * PITCH + frag_off + ks * 32]);
+            for (int j = 0; j < NT; j++) wf[j] = *reinterpret_cast<const v4i *>(Bb + j * 32 * PITCH + ks * 32);
 #pragma unroll
-            for (int i = 0; i < MT; i++)
-                af[i] = *reinterpret_cast<const v4i *>(&As[buf][(wm * WTM + i * 32) * PITCH + frag_off + ks * 32]);
+            for (int i = 0; i < MT; i++) af[i] = *reinterpret_cast<const v4i *>(Ab + i * 32 * PITCH + ks * 32);
 #pragma unroll
             for (int i = 0; i < MT; i++)
 #pragma unroll
@@ -176,13 +202,19 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
         __syncthreads();
     }
 
-    // ---- epilogue.  With weights as the first MFMA operand, lane l holds output row
-    // (l % 32) of the tile and, for register r, column 8*(r/4) + 4*(l/32) + r%4: four
-    // consecutive output channels per register quad, i.e. one 32-bit store of codes.
-    const bool fused = a.out32 == nullptr;
+    // ---- epilogue: lane = one pixel of a 32-row block, 16 consecutive channels per column block
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
     HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
-    if (fused) rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
+    bool full_grid = true;
+    int c_lo = INT_MIN, c_hi = INT_MAX;
+    if (FUSED) {
+        rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
+        full_grid = a.range->qlo == -128 && a.range->qhi == 127;
+        c_hi = hq_clip_threshold(rq.mult, rq.fhi, true);
+        c_lo = hq_clip_threshold(rq.mult, rq.flo, false);
+    }
+    const float zoff = (float)(rq.z + 128);
+    const bool wide_store = (a.N & 15) == 0;
     int mn = INT_MAX, mx = INT_MIN;
     unsigned nlo = 0, nhi = 0;
 #pragma unroll
@@ -191,48 +223,81 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
         if (m >= a.M) continue;
 #pragma unroll
         for (int j = 0; j < NT; j++) {
+            const int nb = n0 + wn * WTN + j * 32 + 16 * (lane >> 5);
+            if (nb >= a.N) continue;
+            v4i packed = {0, 0, 0, 0};
 #pragma unroll
             for (int g = 0; g < 4; g++) {
-                const int n = n0 + wn * WTN + j * 32 + 8 * g + 4 * (lane >> 5);
-                if (n >= a.N) continue;
+                const int n = nb + 4 * g;
+                if (n >= a.N) continue;                    // N % 4 == 0: a quad is all in or all out
                 const v4i bs = *reinterpret_cast<const v4i *>(a.bsum + n);
                 int c[4];
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    c[e] = acc[i][j][4 * g + e] - za * bs[e];
-                    mn = min(mn, c[e]); mx = max(mx, c[e]);
-                }
-                if (fused) {
-                    int q[4];
+                for (int e = 0; e < 4; e++) c[e] = acc[i][j][4 * g + e] - za * bs[e];
+                const int qmn = min(min(c[0], c[1]), min(c[2], c[3]));
+                const int qmx = max(max(c[0], c[1]), max(c[2], c[3]));
+                mn = min(mn, qmn); mx = max(mx, qmx);
+                if (FUSED) {
+                    if (__any(qmx > c_hi || qmn < c_lo)) {
 #pragma unroll
-                    for (int e = 0; e < 4; e++) q[e] = hq_requant(c[e], rq, nlo, nhi);
-                    *reinterpret_cast<unsigned *>(a.out8 + (size_t)m * a.N + n) = hq_pack4(q[0], q[1], q[2], q[3]);
+                        for (int e = 0; e < 4; e++) { nhi += c[e] > c_hi ? 1u : 0u; nlo += c[e] < c_lo ? 1u : 0u; }
+                    }
+                    packed[g] = (int)(hq_requant4_u8(c, rq, zoff, full_grid) ^ 0x80808080u);
+                    if (!wide_store) *reinterpret_cast<int *>(a.out8 + (size_t)m * a.N + n) = packed[g];
                 } else {
-                    v4i v = {c[0], c[1], c[2], c[3]};
+                    const v4i v = {c[0], c[1], c[2], c[3]};
                     *reinterpret_cast<v4i *>(a.out32 + (size_t)m * a.N + n) = v;
                 }
             }
+            if (FUSED && wide_store) *reinterpret_cast<v4i *>(a.out8 + (size_t)m * a.N + nb) = packed;
         }
     }
+    __syncthreads();                                       // LDS tiles are dead: reuse for the reduction
     hq_block_stats_commit(mn, mx, nlo, nhi, a.st, red);
     if (blockIdx.x == 0 && tid == 0) {
         a.st->acc_scale = acc_scale;
         atomicAdd((unsigned long long *)&a.st->count, (unsigned long long)a.M * (unsigned long long)a.N);
-        if (fused) *a.outq = a.range->qp;
+        if (FUSED) *a.outq = a.range->qp;
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
-int launch(const GemmArgs &a, hipStream_t s)
+template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
+int launch3(GemmArgs &a, hipStream_t s)
 {
-    const long tiles = (long)((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((hq_gemm_kernel<BM, BN, WGM, WGN>), dim3((unsigned)tiles), dim3(HQ_THREADS), 0, s, a);
+    a.m_tiles = (a.M + BM - 1) / BM;
+    a.n_tiles = (a.N + BN - 1) / BN;
+    const size_t lds = 2 * (size_t)(BM + BN) * (BKB + 16) + 64;
+    auto kern = hq_gemm_kernel<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, FUSED>;
+    static bool configured = false;
+    if (!configured) {
+        if (lds > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return HQ_E_HIP;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.m_tiles * a.n_tiles)), dim3(HQ_THREADS), lds, s, a);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+}
+
+template <int BM, int BN, int WGM, int WGN, int BKB>
+int launch2(GemmArgs &a, bool strided, bool aligned, bool fused, hipStream_t s)
+{
+    if (strided) {
+        if (aligned) return fused ? launch3<BM, BN, WGM, WGN, BKB, true, true, true>(a, s)
+                                  : launch3<BM, BN, WGM, WGN, BKB, true, true, false>(a, s);
+        return fused ? launch3<BM, BN, WGM, WGN, BKB, true, false, true>(a, s)
+                     : launch3<BM, BN, WGM, WGN, BKB, true, false, false>(a, s);
+    }
+    if (aligned) return fused ? launch3<BM, BN, WGM, WGN, BKB, false, true, true>(a, s)
+                              : launch3<BM, BN, WGM, WGN, BKB, false, true, false>(a, s);
+    return fused ? launch3<BM, BN, WGM, WGN, BKB, false, false, true>(a, s)
+                 : launch3<BM, BN, WGM, WGN, BKB, false, false, false>(a, s);
 }
 
 } // namespace
 
-// Host-side entry used by hq_api.hip.  `dgrad` selects the gather; `out32` the dynamic pass 1.
+// Host-side entry used by hq_api.hip.  `dgrad` selects the operation; `out32` the dynamic pass 1.
 int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                    const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
                    int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
@@ -241,18 +306,28 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
     GemmArgs a;
     a.A = A; a.Bw = Bw; a.bsum = bsum; a.aq = aq; a.bq = bq; a.range = range;
     a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
-    a.R = p->R; a.S = p->S; a.stride = p->stride; a.pad = p->pad; a.dgrad = dgrad;
+    a.taps = p->R * p->S; a.S = p->S;
+    bool strided = false;
     if (!dgrad) {
         a.M = p->B * OH * OW; a.N = p->Cout; a.Cs = p->C;
         a.Hs = p->H; a.Ws = p->W; a.Ho = OH; a.Wo = OW;
+        a.stride = p->stride; a.pad = p->pad; a.flip = 0;
     } else {
         a.M = p->B * p->H * p->W; a.N = p->C; a.Cs = p->Cout;
         a.Hs = OH; a.Ws = OW; a.Ho = p->H; a.Wo = p->W;
+        if (p->stride == 1 && p->R == p->S) {             // stencil over dY with mirrored taps
+            a.stride = 1; a.pad = p->R - 1 - p->pad; a.flip = 1;
+        } else {
+            strided = true; a.stride = p->stride; a.pad = p->pad; a.flip = 0;
+        }
     }
     a.cpt = (a.Cs + 15) / 16;
-    a.nchunks = p->R * p->S * a.cpt;
-    a.aligned16 = (a.Cs % 16) == 0;
-    if (a.N > 64) return launch<128, 128, 2, 2>(a, stream);
-    if (a.N > 32) return launch<256, 64, 4, 1>(a, stream);
-    return launch<256, 32, 4, 1>(a, stream);
+    a.nchunks = a.taps * a.cpt;
+    const bool aligned = (a.Cs % 16) == 0, fused = out32 == nullptr;
+    if (a.N > 64) {
+        if (a.nchunks >= 16) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, fused, stream);
+        return launch2<128, 128, 2, 2, 64>(a, strided, aligned, fused, stream);
+    }
+    if (a.N > 32) return launch2<256, 64, 4, 1, 64>(a, strided, aligned, fused, stream);
+    return launch2<256, 32, 4, 1, 64>(a, strided, aligned, fused, stream);
 }
