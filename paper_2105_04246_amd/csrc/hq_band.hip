@@ -27,6 +27,7 @@
 //     16-value groups whose own min / max cross integer thresholds found once per kernel by
 //     bisection on the fp32 requantization formula (it is monotone in the accumulator).
 #include "hq_device.h"
+#include <type_traits>
 #include "hq_internal.h"
 
 namespace {
@@ -80,13 +81,8 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
     const v4i fill = {fillw, fillw, fillw, fillw};
 
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
-    HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
-    bool full_grid = true;
-    if (FUSED) {
-        rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
-        full_grid = a.range->qlo == -128 && a.range->qhi == 127;
-    }
-    const float zoff = (float)(rq.z + 128);
+    HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
+    if (FUSED) ep = hq_make_epilogue(acc_scale, a.range);
 
     // ---- this workgroup's band
     const int img = blockIdx.x / a.bands_per_image, band = blockIdx.x % a.bands_per_image;
@@ -137,12 +133,10 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                     *reinterpret_cast<v4i *>(Pg + k * a.PW * PP + col_lds[j]) = pf[k][j];
     };
 
-    // ---- start-up: request the group's first patch and the weights before anything waits;
-    // search the clip thresholds while the loads are in flight.
+    // ---- start-up: request the group's first patch and the weights before anything waits
     if (grp < nitem) prefetch(grp / nchunk);
     constexpr int WB = 6;
     const int wchunks = a.npad * TAPS * NCH;
-    int c_lo = INT_MIN, c_hi = INT_MAX;
     for (int base = 0; base < wchunks; base += BAND_THREADS * WB) {
         v4i wv[WB];
 #pragma unroll
@@ -154,10 +148,6 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
             wv[k] = v4i{0, 0, 0, 0};
             if (idx < wchunks && n < a.N)
                 wv[k] = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
-        }
-        if (FUSED && base == 0) {
-            c_hi = hq_clip_threshold(rq.mult, rq.fhi, true);
-            c_lo = hq_clip_threshold(rq.mult, rq.flo, false);
         }
 #pragma unroll
         for (int k = 0; k < WB; k++) {
@@ -210,12 +200,17 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                     const int oy = (int)__umulhi((unsigned)pix[i], a.magic_Wo), ox = pix[i] - oy * a.Wo;
                     abase[i] = (((oy - oy0) * a.stride) * a.PW + ox * a.stride) * PP + (lane >> 5) * 16;
                 }
+                // accumulators start at -z_a * bsum[n] (lane = 16 consecutive channels per column block)
 #pragma unroll
-                for (int i = 0; i < 2; i++)
+                for (int j = 0; j < NT; j++)
 #pragma unroll
-                    for (int j = 0; j < NT; j++)
+                    for (int g = 0; g < 4; g++) {
+                        const v4i bzv = *reinterpret_cast<const v4i *>(bz + nc * BN + j * 32 + 16 * (lane >> 5) + 4 * g);   // < npad
 #pragma unroll
-                        for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
+                        for (int i = 0; i < 2; i++)
+#pragma unroll
+                            for (int e = 0; e < 4; e++) acc[i][j][4 * g + e] = -bzv[e];
+                    }
                 if (active) {
                     // Fragments of tap t+1 are requested before the MFMAs of tap t are issued, so
                     // LDS latency hides behind the matrix cores (two register buffers).
@@ -257,86 +252,37 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                 }
             } else {
                 // -------------------------------------------------- vector-ALU phase
-                v4i bzv[NT][4];                            // z_a * bsum of this lane's 16 channels per column block
-#pragma unroll
-                for (int j = 0; j < NT; j++)
-#pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        const int nb = nc * BN + j * 32 + 16 * (lane >> 5);   // < npad
-                        bzv[j][g] = *reinterpret_cast<const v4i *>(bz + nb + 4 * g);
-                    }
                 if (have_pf) stash();                      // nobody reads this group's patch now
+                auto epilogue = [&](auto full) {
+                    constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-                for (int i = 0; i < 2; i++) {
-                    if (!ok[i]) continue;
-                    const size_t m = out_img + pix[i];
+                    for (int i = 0; i < 2; i++) {
+                        if (!ok[i]) continue;
+                        const size_t m = out_img + pix[i];
 #pragma unroll
-                    for (int j = 0; j < NT; j++) {
-                        const int nb = nc * BN + j * 32 + 16 * (lane >> 5);
-                        if (nb >= a.N) continue;
-                        int c[16];
+                        for (int j = 0; j < NT; j++) {
+                            const int nb = nc * BN + j * 32 + 16 * (lane >> 5);
+                            if (nb >= a.N) continue;
+                            int c[16];
 #pragma unroll
-                        for (int g = 0; g < 4; g++)
-#pragma unroll
-                            for (int e = 0; e < 4; e++) c[4 * g + e] = acc[i][j][4 * g + e] - bzv[j][g][e];
-                        // min / max per quad, then per group; clipped values are counted exactly but
-                        // only inside quads whose own extremes cross the thresholds
-                        int qmn[4], qmx[4];
-#pragma unroll
-                        for (int g = 0; g < 4; g++) {
-                            qmn[g] = min(min(c[4 * g], c[4 * g + 1]), min(c[4 * g + 2], c[4 * g + 3]));
-                            qmx[g] = max(max(c[4 * g], c[4 * g + 1]), max(c[4 * g + 2], c[4 * g + 3]));
-                        }
-                        const int gmn = min(min(qmn[0], qmn[1]), min(qmn[2], qmn[3]));
-                        const int gmx = max(max(qmx[0], qmx[1]), max(qmx[2], qmx[3]));
-                        mn = min(mn, gmn); mx = max(mx, gmx);
-                        if (FUSED) {
-                            if (__any(gmx > c_hi || gmn < c_lo)) {
-#pragma unroll
-                                for (int g = 0; g < 4; g++)
-                                    if (__any(qmx[g] > c_hi || qmn[g] < c_lo)) {
-#pragma unroll
-                                        for (int e = 0; e < 4; e++) {
-                                            nhi += c[4 * g + e] > c_hi ? 1u : 0u;
-                                            nlo += c[4 * g + e] < c_lo ? 1u : 0u;
-                                        }
-                                    }
-                            }
-                            v4i packed;
-                            if (full_grid) {
-#pragma unroll
-                                for (int g = 0; g < 4; g++) {
-                                    unsigned w = 0;
-#pragma unroll
-                                    for (int e = 0; e < 4; e++) {
-                                        const float f = rintf(__fmul_rn((float)c[4 * g + e], rq.mult)) + zoff;
-                                        w = __builtin_amdgcn_cvt_pk_u8_f32(f, e, w);        // saturates to 0..255
-                                    }
-                                    packed[g] = (int)(w ^ 0x80808080u);
-                                }
+                            for (int r = 0; r < 16; r++) c[r] = acc[i][j][r];
+                            if (FUSED) {
+                                int w[4];
+                                hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
+                                const v4i packed = {w[0], w[1], w[2], w[3]};
+                                *reinterpret_cast<v4i *>(a.out8 + m * a.N + nb) = packed;
                             } else {
+                                hq_minmax_group<16>(c, mn, mx);
 #pragma unroll
                                 for (int g = 0; g < 4; g++) {
-                                    unsigned w = 0;
-#pragma unroll
-                                    for (int e = 0; e < 4; e++) {
-                                        float f = rintf(__fmul_rn((float)c[4 * g + e], rq.mult));
-                                        f = __builtin_amdgcn_fmed3f(f, rq.flo, rq.fhi) + zoff;
-                                        w = __builtin_amdgcn_cvt_pk_u8_f32(f, e, w);
-                                    }
-                                    packed[g] = (int)(w ^ 0x80808080u);
+                                    const v4i v = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
+                                    *reinterpret_cast<v4i *>(a.out32 + m * a.N + nb + 4 * g) = v;
                                 }
-                            }
-                            *reinterpret_cast<v4i *>(a.out8 + m * a.N + nb) = packed;
-                        } else {
-#pragma unroll
-                            for (int g = 0; g < 4; g++) {
-                                const v4i v = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
-                                *reinterpret_cast<v4i *>(a.out32 + m * a.N + nb + 4 * g) = v;
                             }
                         }
                     }
-                }
+                };
+                if (ep.full_grid) epilogue(std::true_type()); else epilogue(std::false_type());
             }
         }
         __syncthreads();

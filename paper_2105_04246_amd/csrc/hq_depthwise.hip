@@ -135,16 +135,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
     const int fill = (za & 0xff) * 0x01010101;
     const bool fused = a.out32 == nullptr;
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
-    HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
-    bool full_grid = true;
-    int c_lo = INT_MIN, c_hi = INT_MAX;
-    if (fused) {
-        rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
-        full_grid = a.range->qlo == -128 && a.range->qhi == 127;
-        c_hi = hq_clip_threshold(rq.mult, rq.fhi, true);
-        c_lo = hq_clip_threshold(rq.mult, rq.flo, false);
-    }
-    const float zoff = (float)(rq.z + 128);
+    HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
+    if (fused) ep = hq_make_epilogue(acc_scale, a.range);
 
     // weights of the four channels, unpacked; mirrored for the input gradient
     int w[9][4];
@@ -196,22 +188,18 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
         if (oy + 3 < y1) { load_row(pn, oy + 4 < a.H, ring[RING]); pn += rowbytes; }                   \
         int cv[4];                                                                                    \
         _Pragma("unroll") for (int e = 0; e < 4; e++) {                                                 \
-            int acc = 0;                                                                              \
+            int acc = -zw[e];                                                                         \
             _Pragma("unroll") for (int s = 0; s < 3; s++)                                               \
                 acc += __mul24(win[TOP][s][e], w[s][e]) + __mul24(win[MID][s][e], w[3 + s][e]) + __mul24(win[BOT][s][e], w[6 + s][e]); \
-            cv[e] = acc - zw[e];                                                                      \
+            cv[e] = acc;                                                                              \
         }                                                                                             \
-        const int qmn = min(min(cv[0], cv[1]), min(cv[2], cv[3]));                                    \
-        const int qmx = max(max(cv[0], cv[1]), max(cv[2], cv[3]));                                    \
-        mn = min(mn, qmn); mx = max(mx, qmx);                                                         \
         if (fused) {                                                                                  \
-            if (__any(qmx > c_hi || qmn < c_lo)) {                                                    \
-                _Pragma("unroll") for (int e = 0; e < 4; e++) {                                         \
-                    nhi += cv[e] > c_hi ? 1u : 0u; nlo += cv[e] < c_lo ? 1u : 0u;                     \
-                }                                                                                     \
-            }                                                                                         \
-            *reinterpret_cast<unsigned *>(a.out8 + o) = hq_requant4_u8(cv, rq, zoff, full_grid) ^ 0x80808080u; \
+            int wd;                                                                                   \
+            if (ep.full_grid) hq_requant_group<4, true>(cv, ep, mn, mx, nlo, nhi, &wd);               \
+            else hq_requant_group<4, false>(cv, ep, mn, mx, nlo, nhi, &wd);                            \
+            *reinterpret_cast<int *>(a.out8 + o) = wd;                                                \
         } else {                                                                                      \
+            hq_minmax_group<4>(cv, mn, mx);                                                           \
             const v4i v = {cv[0], cv[1], cv[2], cv[3]};                                               \
             *reinterpret_cast<v4i *>(a.out32 + o) = v;                                                \
         }                                                                                             \

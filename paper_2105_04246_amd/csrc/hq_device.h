@@ -62,39 +62,78 @@ __device__ inline int hq_requant(int c, const HqRequant &q, unsigned &nlo, unsig
     return (int)r + q.z;
 }
 
-// Largest accumulator value that does not clip high / smallest that does not clip low:
-// bisection on the exact requantization formula (monotone in c; c = 0 never clips because the
-// zero point lies on the grid).  Lets the epilogues count clipped values with integer compares.
-__device__ inline int hq_clip_threshold(float mult, float bound, bool high)
+// ---------------------------------------------------------------------------------------
+// Fused epilogue of the MFMA kernels: a lane's zero-point-corrected accumulators -> codes,
+// with min / max and exact clip counts folded in (Sec. 4, steps 1 and 2).
+// Per value: convert, multiply, round (the requantization of the static quantizer), add the
+// zero point, pack.  Clipped values are counted from the rounded floats with lane-mask
+// compares whose popcounts accumulate on the scalar unit, and only in groups whose extreme
+// accumulators clip: requantization is monotone in the accumulator, so the extremes decide
+// for the whole group.  A wavefront's counts are added to the counters of the first lane that
+// is active in the call, so the sum of a counter over all lanes is the total.
+// ---------------------------------------------------------------------------------------
+struct HqEpilogue {
+    float mult;          // (s_a * s_b) / s_out
+    float flo, fhi;      // grid bounds relative to the zero point
+    float zoff;          // zero point + 128: codes are formed as unsigned bytes, see below
+    bool full_grid;      // grid is -128..127: the saturating pack is the whole clamp
+};
+
+__device__ inline HqEpilogue hq_make_epilogue(float acc_scale, const hq_range *r)
 {
-    auto inside = [&](int c) {
-        const float r = rintf(__fmul_rn((float)c, mult));
-        return high ? r <= bound : r >= bound;
-    };
-    if (inside(high ? INT_MAX : INT_MIN)) return high ? INT_MAX : INT_MIN;
-    int good = 0, bad = high ? INT_MAX : INT_MIN;          // inside(good), !inside(bad)
-    while (true) {
-        const unsigned dist = high ? (unsigned)bad - (unsigned)good : (unsigned)good - (unsigned)bad;
-        if (dist <= 1u) break;
-        const int mid = high ? (int)((unsigned)good + dist / 2) : (int)((unsigned)good - dist / 2);
-        if (inside(mid)) good = mid; else bad = mid;
-    }
-    return good;
+    HqEpilogue e;
+    e.mult = __fdiv_rn(acc_scale, r->qp.scale);
+    e.flo = (float)(r->qlo - r->qp.zero_point);
+    e.fhi = (float)(r->qhi - r->qp.zero_point);
+    e.zoff = (float)(r->qp.zero_point + 128);
+    e.full_grid = r->qlo == -128 && r->qhi == 127;
+    return e;
 }
 
-// Four accumulators -> four codes packed in one word.  zoff = zero point + 128: the codes are
-// formed as unsigned bytes by v_cvt_pk_u8_f32 (which saturates to 0..255: the clamp of the full
-// 8-bit grid) and flipped to signed storage by the caller with ^ 0x80808080.
-__device__ inline unsigned hq_requant4_u8(const int *c, const HqRequant &q, float zoff, bool full_grid)
+__device__ inline float hq_round_scaled(int c, float mult) { return rintf(__fmul_rn((float)c, mult)); }
+
+// N = 4 or 16 accumulators -> N / 4 words of signed codes.  v_cvt_pk_u8_f32 saturates to
+// 0..255, which after the flip of the top bits is the clamp to -128..127.
+template <int N, bool FULL_GRID>
+__device__ inline void hq_requant_group(const int *c, const HqEpilogue &ep, int &mn, int &mx,
+                                        unsigned &w_lo, unsigned &w_hi, int *words)
 {
-    unsigned w = 0;
+    int gmn = c[0], gmx = c[0];
 #pragma unroll
-    for (int e = 0; e < 4; e++) {
-        float f = rintf(__fmul_rn((float)c[e], q.mult));
-        if (!full_grid) f = __builtin_amdgcn_fmed3f(f, q.flo, q.fhi);
-        w = __builtin_amdgcn_cvt_pk_u8_f32(f + zoff, e, w);
+    for (int e = 1; e + 1 < N; e += 2) { gmn = min(gmn, min(c[e], c[e + 1])); gmx = max(gmx, max(c[e], c[e + 1])); }
+    gmn = min(gmn, c[N - 1]); gmx = max(gmx, c[N - 1]);
+    mn = min(mn, gmn); mx = max(mx, gmx);
+    float f[N];
+#pragma unroll
+    for (int e = 0; e < N; e++) f[e] = hq_round_scaled(c[e], ep.mult);
+    if (__any(hq_round_scaled(gmx, ep.mult) > ep.fhi || hq_round_scaled(gmn, ep.mult) < ep.flo)) {
+        unsigned nh = 0, nl = 0;
+#pragma unroll
+        for (int e = 0; e < N; e++) {
+            nh += (unsigned)__popcll(__ballot(f[e] > ep.fhi));
+            nl += (unsigned)__popcll(__ballot(f[e] < ep.flo));
+        }
+        const bool first = (int)__lane_id() == __ffsll((long long)__ballot(true)) - 1;
+        w_hi += first ? nh : 0u; w_lo += first ? nl : 0u;
     }
-    return w;
+#pragma unroll
+    for (int g = 0; g < N / 4; g++) {
+        unsigned w = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            float v = f[4 * g + e];
+            if (!FULL_GRID) v = __builtin_amdgcn_fmed3f(v, ep.flo, ep.fhi);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(v + ep.zoff, e, w);
+        }
+        words[g] = (int)(w ^ 0x80808080u);
+    }
+}
+
+// min / max alone (pass 1 of the dynamic baseline keeps the 32-bit values)
+template <int N> __device__ inline void hq_minmax_group(const int *c, int &mn, int &mx)
+{
+#pragma unroll
+    for (int e = 0; e + 1 < N; e += 2) { mn = min(mn, min(c[e], c[e + 1])); mx = max(mx, max(c[e], c[e + 1])); }
 }
 
 __device__ inline unsigned hq_pack4(int a, int b, int c, int d)

@@ -25,6 +25,7 @@
 // launch (Sec. 4, step 1).  With `out32` set, the kernel is pass 1 of the dynamic baseline:
 // it stores the corrected 32-bit outputs (eq. (5), "save acc output") and gathers min / max.
 #include "hq_device.h"
+#include <type_traits>
 
 namespace {
 
@@ -66,7 +67,7 @@ template <bool ALIGNED> __device__ inline v4i load_chunk(const int8_t *p, int nb
 // BKB: bytes of reduction per stage.  STRIDED: input gradient of a strided layer (gather with
 // exact-division test); otherwise the stencil form.  ALIGNED: Cs % 16 == 0.
 template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
-__global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
+__global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a)
 {
     static_assert(WGM * WGN == HQ_THREADS / 64, "four wavefronts");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
@@ -80,7 +81,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     int8_t *As = smem;                                   // [2][BM][PITCH]
     int8_t *Bs = smem + 2 * BM * PITCH;                  // [2][BN][PITCH]
-    int *red = reinterpret_cast<int *>(smem + 2 * (BM + BN) * PITCH);
+    int *bzs = reinterpret_cast<int *>(smem + 2 * (BM + BN) * PITCH);      // [BN] z_a * bsum[n0 + col]
+    int *red = bzs + BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -97,6 +99,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
 
     const int za = a.aq->zero_point;
     const int fill = (za & 0xff) * 0x01010101;
+
+    if (tid < BN) bzs[tid] = (n0 + tid < a.N) ? za * a.bsum[n0 + tid] : 0;   // visible after the first barrier
 
     // ---- per-thread gather state
     const int cc = tid % CPS, lrow = tid / CPS;
@@ -126,8 +130,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
     int chunk = cc, c16 = cc % a.cpt, tap = cc / a.cpt;
     int tr = tap / a.S, ts = tap - tr * a.S;
 
-    v4i areg[AROWS], breg[BROWS];
-    auto load_stage = [&]() {
+    v4i areg0[AROWS], breg0[BROWS], areg1[AROWS], breg1[BROWS];
+    auto load_stage = [&](v4i (&areg)[AROWS], v4i (&breg)[BROWS]) {
         const bool chunk_ok = chunk < a.nchunks;
         const int coff = c16 * 16, nbytes = a.Cs - coff;
 #pragma unroll
@@ -156,7 +160,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
         chunk += CPS; c16 += CPS;
         while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == a.S) { ts = 0; tr++; } }
     };
-    auto store_stage = [&](int buf) {
+    auto store_stage = [&](int buf, const v4i (&areg)[AROWS], const v4i (&breg)[BROWS]) {
 #pragma unroll
         for (int i = 0; i < AROWS; i++)
             *reinterpret_cast<v4i *>(As + (buf * BM + lrow + RPP * i) * PITCH + cc * 16) = areg[i];
@@ -167,22 +171,13 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
     };
 
     v16i acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; i++)
-#pragma unroll
-        for (int j = 0; j < NT; j++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
 
+    // K loop.  Two LDS buffers and two register sets: while stage kt is multiplied from LDS, the
+    // global loads of stage kt+2 are in flight and stage kt+1 waits in registers, so a load has
+    // two stages of MFMA work to hide behind.
     const int KT = (a.nchunks + CPS - 1) / CPS;
-    load_stage();
-    store_stage(0);
-    __syncthreads();
     const int frag_off = (lane & 31) * PITCH + (lane >> 5) * 16;
-    for (int kt = 0; kt < KT; kt++) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) load_stage();
+    auto compute = [&](int buf) {
         const int8_t *Ab = As + (buf * BM + wm * WTM) * PITCH + frag_off;
         const int8_t *Bb = Bs + (buf * BN + wn * WTN) * PITCH + frag_off;
 #pragma unroll
@@ -198,61 +193,91 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_gemm_kernel(const GemmArgs a)
                 for (int j = 0; j < NT; j++)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
         }
-        if (more) store_stage(buf ^ 1);
+    };
+    load_stage(areg0, breg0);
+    store_stage(0, areg0, breg0);
+    if (KT > 1) load_stage(areg1, breg1);
+    __syncthreads();
+    // the accumulators start at -z_a * bsum[n]: the zero-point term of the sum is gone before
+    // the epilogue looks at them (lane = 16 consecutive channels of column block j)
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+        const int cb = wn * WTN + j * 32 + 16 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            const v4i bz = *reinterpret_cast<const v4i *>(bzs + cb + 4 * g);
+#pragma unroll
+            for (int i = 0; i < MT; i++)
+#pragma unroll
+                for (int e = 0; e < 4; e++) acc[i][j][4 * g + e] = -bz[e];
+        }
+    }
+    for (int kt = 0; kt < KT; kt += 2) {
+        if (kt + 2 < KT) load_stage(areg0, breg0);        // stage kt+2
+        compute(0);
+        if (kt + 1 < KT) store_stage(1, areg1, breg1);    // stage kt+1
         __syncthreads();
+        if (kt + 1 < KT) {
+            if (kt + 3 < KT) load_stage(areg1, breg1);    // stage kt+3
+            compute(1);
+            if (kt + 2 < KT) store_stage(0, areg0, breg0);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: lane = one pixel of a 32-row block, 16 consecutive channels per column block
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
-    HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
-    bool full_grid = true;
-    int c_lo = INT_MIN, c_hi = INT_MAX;
-    if (FUSED) {
-        rq = hq_make_requant(acc_scale, a.range->qp, a.range->qlo, a.range->qhi);
-        full_grid = a.range->qlo == -128 && a.range->qhi == 127;
-        c_hi = hq_clip_threshold(rq.mult, rq.fhi, true);
-        c_lo = hq_clip_threshold(rq.mult, rq.flo, false);
-    }
-    const float zoff = (float)(rq.z + 128);
+    HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
+    if (FUSED) ep = hq_make_epilogue(acc_scale, a.range);
     const bool wide_store = (a.N & 15) == 0;
     int mn = INT_MAX, mx = INT_MIN;
     unsigned nlo = 0, nhi = 0;
+    auto epilogue = [&](auto full) {
+        constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-    for (int i = 0; i < MT; i++) {
-        const int m = m0 + wm * WTM + i * 32 + (lane & 31);
-        if (m >= a.M) continue;
+        for (int i = 0; i < MT; i++) {
+            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+            if (m >= a.M) continue;
 #pragma unroll
-        for (int j = 0; j < NT; j++) {
-            const int nb = n0 + wn * WTN + j * 32 + 16 * (lane >> 5);
-            if (nb >= a.N) continue;
-            v4i packed = {0, 0, 0, 0};
+            for (int j = 0; j < NT; j++) {
+                const int nb = n0 + wn * WTN + j * 32 + 16 * (lane >> 5);
+                if (nb >= a.N) continue;
+                int c[16];
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int n = nb + 4 * g;
-                if (n >= a.N) continue;                    // N % 4 == 0: a quad is all in or all out
-                const v4i bs = *reinterpret_cast<const v4i *>(a.bsum + n);
-                int c[4];
+                for (int r = 0; r < 16; r++) c[r] = acc[i][j][r];
+                const size_t o = (size_t)m * a.N + nb;
+                if (!FUSED) {
 #pragma unroll
-                for (int e = 0; e < 4; e++) c[e] = acc[i][j][4 * g + e] - za * bs[e];
-                const int qmn = min(min(c[0], c[1]), min(c[2], c[3]));
-                const int qmx = max(max(c[0], c[1]), max(c[2], c[3]));
-                mn = min(mn, qmn); mx = max(mx, qmx);
-                if (FUSED) {
-                    if (__any(qmx > c_hi || qmn < c_lo)) {
-#pragma unroll
-                        for (int e = 0; e < 4; e++) { nhi += c[e] > c_hi ? 1u : 0u; nlo += c[e] < c_lo ? 1u : 0u; }
+                    for (int g = 0; g < 4; g++) {
+                        if (nb + 4 * g >= a.N) continue;       // N % 4 == 0: a quad is all in or all out
+                        hq_minmax_group<4>(c + 4 * g, mn, mx);
+                        const v4i v = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
+                        *reinterpret_cast<v4i *>(a.out32 + o + 4 * g) = v;
                     }
-                    packed[g] = (int)(hq_requant4_u8(c, rq, zoff, full_grid) ^ 0x80808080u);
-                    if (!wide_store) *reinterpret_cast<int *>(a.out8 + (size_t)m * a.N + n) = packed[g];
+                } else if (nb + 16 <= a.N) {
+                    int w[4];
+                    hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
+                    if (wide_store) {
+                        const v4i v = {w[0], w[1], w[2], w[3]};
+                        *reinterpret_cast<v4i *>(a.out8 + o) = v;
+                    } else {
+#pragma unroll
+                        for (int g = 0; g < 4; g++) *reinterpret_cast<int *>(a.out8 + o + 4 * g) = w[g];
+                    }
                 } else {
-                    const v4i v = {c[0], c[1], c[2], c[3]};
-                    *reinterpret_cast<v4i *>(a.out32 + (size_t)m * a.N + n) = v;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        if (nb + 4 * g >= a.N) continue;
+                        int w;
+                        hq_requant_group<4, FULL>(c + 4 * g, ep, mn, mx, nlo, nhi, &w);
+                        *reinterpret_cast<int *>(a.out8 + o + 4 * g) = w;
+                    }
                 }
             }
-            if (FUSED && wide_store) *reinterpret_cast<v4i *>(a.out8 + (size_t)m * a.N + nb) = packed;
         }
-    }
-    __syncthreads();                                       // LDS tiles are dead: reuse for the reduction
+    };
+    if (ep.full_grid) epilogue(std::true_type()); else epilogue(std::false_type());
+    __syncthreads();
     hq_block_stats_commit(mn, mx, nlo, nhi, a.st, red);
     if (blockIdx.x == 0 && tid == 0) {
         a.st->acc_scale = acc_scale;
@@ -266,7 +291,7 @@ int launch3(GemmArgs &a, hipStream_t s)
 {
     a.m_tiles = (a.M + BM - 1) / BM;
     a.n_tiles = (a.N + BN - 1) / BN;
-    const size_t lds = 2 * (size_t)(BM + BN) * (BKB + 16) + 64;
+    const size_t lds = 2 * (size_t)(BM + BN) * (BKB + 16) + 4 * BN + 64;
     auto kern = hq_gemm_kernel<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, FUSED>;
     static bool configured = false;
     if (!configured) {
