@@ -67,13 +67,28 @@ typedef struct {
  * accumulator outputs; one accumulator unit is worth acc_scale in real units.
  * clip_lo/clip_hi count the outputs whose rounded code fell below qlo / above qhi
  * (saturation ratio = (clip_lo + clip_hi) / count, Sec. 4 footnote).
- * Kernels only ever merge into this struct; hq_stats_reset / hq_range_update empty it.      */
+ *
+ * A record is sharded: the workgroups of a GEMM merge their minima, maxima and clip counts
+ * into one of HQ_STATS_PARTS partial records, each in a 128-byte line of its own, so that
+ * the atomics of a launch spread over many addresses instead of queueing on one.  The
+ * leading fields are the fold of the partial records: hq_stats_fold, hq_range_update and
+ * hq_gemm_dynamic (between its passes) move what the partial records hold into them and
+ * empty the partial records, so folding twice is harmless.  acc_scale and count are
+ * written by the GEMMs directly.  hq_stats_reset / hq_range_update empty the whole record. */
+#define HQ_STATS_PARTS 64
+typedef struct {
+    int32_t  acc_min, acc_max;
+    uint64_t clip_lo, clip_hi;
+    uint8_t  pad[104];
+} hq_stats_part;                                   /* 128 bytes */
 typedef struct {
     int32_t  acc_min, acc_max;
     float    acc_scale;
     uint32_t reserved;
     uint64_t clip_lo, clip_hi, count;
-} hq_stats;
+    uint8_t  pad[88];
+    hq_stats_part part[HQ_STATS_PARTS];
+} hq_stats;                                        /* 128 + 64 * 128 bytes, 128-byte aligned */
 
 /* Layer shape (host struct).  Linear: kind=HQ_LINEAR, B=M, C=K, Cout=N, H=W=R=S=stride=1,
  * pad=0.  Output spatial size: OH = (H + 2*pad - R)/stride + 1, same for OW.
@@ -111,8 +126,8 @@ size_t hq_workspace_bytes(int32_t entry, const hq_problem *p /* host */);
  *   Y        output codes [B][OH][OW][Cout], written once
  *   yq       out: the quantizer actually used for Y (a copy of yr->qp), so that consumers
  *            never race with a later hq_range_update
- *   st       statistics of this output, merged in place (min, max, clips, count) and
- *            st->acc_scale set to xq->scale * wq->scale                                      */
+ *   st       statistics of this output, merged in place (min, max, clips into the partial
+ *            records, count) and st->acc_scale set to xq->scale * wq->scale                  */
 int hq_gemm_fwd(const hq_problem *p /* host */,
                 const int8_t *X, const hq_qparams *xq,
                 const int8_t *W, const hq_qparams *wq, const int32_t *wsum,
@@ -142,14 +157,14 @@ int hq_gemm_wgrad(const hq_problem *p /* host */,
 
 /* In-hindsight min-max update, eq. (2)-(3): folds the statistics of the tensor just
  * produced into the range for the next iteration and re-derives r->qp.  If r is not
- * initialized the statistics become q^0 (Sec. 4.1).  Empties *st afterwards.  With
- * st->count == 0 the range is left as it is.  One thread; run it on the stream that
- * produced the tensor, any time after the producing kernel.                                  */
+ * initialized the statistics become q^0 (Sec. 4.1).  Folds the partial records first and
+ * empties *st afterwards.  With st->count == 0 the range is left as it is.  One wavefront;
+ * run it on the stream that produced the tensor, any time after the producing kernel.        */
 int hq_range_update(hq_range *r, hq_stats *st, void *stream);
 
 /* Dynamic-quantization baseline (Sec. 3.2; eq. (1); traffic of eq. (5)): pass 1 runs the
  * same GEMM and writes every zero-point-corrected 32-bit output to `ws` while gathering
- * min/max; a one-thread kernel derives the quantizer; pass 2 reads the 32-bit tensor back,
+ * min/max; a one-wavefront kernel folds the statistics and derives the quantizer; pass 2 reads the 32-bit tensor back,
  * quantizes and writes the codes.
  *   op        HQ_ENTRY_DYNAMIC_FWD (A=X, Bw=W, bsum=wsum) or HQ_ENTRY_DYNAMIC_DGRAD
  *             (A=dY, Bw=Wd, bsum=wdsum)
@@ -170,6 +185,11 @@ int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p /* host */,
 
 /* Empties n statistics records (min = INT32_MAX, max = INT32_MIN, counters 0). */
 int hq_stats_reset(hq_stats *st, int32_t n, void *stream);
+
+/* Folds the partial records of n statistics records into their leading fields (and empties
+ * the partial records), so that a reader of acc_min / acc_max / clip_lo / clip_hi sees
+ * everything the kernels before it on the stream have merged.                               */
+int hq_stats_fold(hq_stats *st, int32_t n, void *stream);
 
 /* Weight-side preparation, once per weight update (the weight quantizer's output does not
  * depend on the batch, Sec. 3.1): from W [Cout][R][S][C] writes the dgrad layout

@@ -21,9 +21,14 @@ HQ_DYN_CURRENT, HQ_DYN_RUNNING = 0, 1
 QPARAMS = np.dtype([("scale", "<f4"), ("zero_point", "<i4")])
 RANGE = np.dtype([("qmin", "<f4"), ("qmax", "<f4"), ("eta", "<f4"), ("qlo", "<i4"), ("qhi", "<i4"),
                   ("symmetric", "<i4"), ("initialized", "<i4"), ("scale", "<f4"), ("zero_point", "<i4")])
+STATS_PARTS = 64
+STATS_PART = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("clip_lo", "<u8"), ("clip_hi", "<u8"),
+                       ("pad", "u1", (104,))])
 STATS = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("acc_scale", "<f4"), ("reserved", "<u4"),
-                  ("clip_lo", "<u8"), ("clip_hi", "<u8"), ("count", "<u8")])
-assert QPARAMS.itemsize == 8 and RANGE.itemsize == 36 and STATS.itemsize == 40
+                  ("clip_lo", "<u8"), ("clip_hi", "<u8"), ("count", "<u8"), ("pad", "u1", (88,)),
+                  ("part", STATS_PART, (STATS_PARTS,))])
+assert QPARAMS.itemsize == 8 and RANGE.itemsize == 36 and STATS_PART.itemsize == 128
+assert STATS.itemsize == 128 * (1 + STATS_PARTS)
 
 
 class hq_problem(C.Structure):
@@ -42,7 +47,7 @@ class HqError(RuntimeError):
 
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_wgrad", "hq_range_update",
-           "hq_gemm_dynamic", "hq_stats_reset", "hq_weight_prepare", "hq_error_string")
+           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_error_string")
 
 
 def lib():
@@ -64,6 +69,7 @@ def lib():
         L.hq_range_update.argtypes = [vp, vp, vp]
         L.hq_gemm_dynamic.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 10 + [C.c_size_t, vp]
         L.hq_stats_reset.argtypes = [vp, C.c_int32, vp]
+        L.hq_stats_fold.argtypes = [vp, C.c_int32, vp]
         L.hq_weight_prepare.argtypes = [PP, vp, vp, vp, vp, vp]
         for f in EXPORTS[1:-1]:
             getattr(L, f).restype = C.c_int
@@ -123,6 +129,10 @@ def hq_gemm_dynamic(op, mode, p, A, aq, Bw, bq, bsum, r, out, outq, st, ws, ws_b
 
 def hq_stats_reset(st, n=1, stream=None):
     _check("hq_stats_reset", lib().hq_stats_reset(_ptr(st), n, _stream(stream)))
+
+
+def hq_stats_fold(st, n=1, stream=None):
+    _check("hq_stats_fold", lib().hq_stats_fold(_ptr(st), n, _stream(stream)))
 
 
 def hq_weight_prepare(p, W, Wd, wsum, wdsum, stream=None):

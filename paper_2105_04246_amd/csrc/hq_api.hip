@@ -25,33 +25,45 @@ __device__ inline void ema_update(hq_range *r, float gmin, float gmax)
     r->qp = hq_qparams_from_range(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi);
 }
 
-__device__ inline void stats_clear(hq_stats *st)
+// Empties a record; called by the 64 lanes of one wavefront (lane = partial record).
+__device__ inline void stats_clear_wave(hq_stats *st)
 {
-    st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
-    st->clip_lo = 0; st->clip_hi = 0; st->count = 0;
+    const int lane = threadIdx.x & 63;
+    hq_stats_part *p = &st->part[lane];
+    p->acc_min = INT_MAX; p->acc_max = INT_MIN; p->clip_lo = 0; p->clip_hi = 0;
+    if (lane == 0) {
+        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
+        st->clip_lo = 0; st->clip_hi = 0; st->count = 0;
+    }
 }
 
-__global__ void range_update_kernel(hq_range *r, hq_stats *st)
+__global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats *st)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    if (st->count != 0) {
+    __shared__ unsigned long long sh[128];
+    hq_stats_fold_wave(st, sh);
+    if (threadIdx.x == 0 && st->count != 0) {
         const float gmin = __fmul_rn(st->acc_scale, (float)st->acc_min);
         const float gmax = __fmul_rn(st->acc_scale, (float)st->acc_max);
         ema_update(r, gmin, gmax);
     }
-    stats_clear(st);
+    __syncthreads();
+    stats_clear_wave(st);
 }
 
-__global__ void stats_reset_kernel(hq_stats *st, int n)
+__global__ __launch_bounds__(64) void stats_reset_kernel(hq_stats *st) { stats_clear_wave(st + blockIdx.x); }
+
+__global__ __launch_bounds__(64) void stats_fold_kernel(hq_stats *st)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) stats_clear(st + i);
+    __shared__ unsigned long long sh[128];
+    hq_stats_fold_wave(st + blockIdx.x, sh);
 }
 
 // Dynamic baseline, between the passes: the quantizer of the tensor just written.
-__global__ void dynamic_mid_kernel(int mode, hq_range *r, const hq_stats *st, hq_qparams *outq)
+__global__ __launch_bounds__(64) void dynamic_mid_kernel(int mode, hq_range *r, hq_stats *st, hq_qparams *outq)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    __shared__ unsigned long long sh[128];
+    hq_stats_fold_wave(st, sh);
+    if (threadIdx.x != 0) return;
     const float gmin = __fmul_rn(st->acc_scale, (float)st->acc_min);
     const float gmax = __fmul_rn(st->acc_scale, (float)st->acc_max);
     if (mode == HQ_DYN_RUNNING) {
@@ -234,7 +246,14 @@ int hq_range_update(hq_range *r, hq_stats *st, void *stream)
 int hq_stats_reset(hq_stats *st, int32_t n, void *stream)
 {
     if (!st || n <= 0 || misaligned(st, 8)) return HQ_E_BADARG;
-    hipLaunchKernelGGL(stats_reset_kernel, dim3((n + 63) / 64), dim3(64), 0, as_stream(stream), st, n);
+    hipLaunchKernelGGL(stats_reset_kernel, dim3(n), dim3(64), 0, as_stream(stream), st);
+    return launch_status();
+}
+
+int hq_stats_fold(hq_stats *st, int32_t n, void *stream)
+{
+    if (!st || n <= 0 || misaligned(st, 8)) return HQ_E_BADARG;
+    hipLaunchKernelGGL(stats_fold_kernel, dim3(n), dim3(64), 0, as_stream(stream), st);
     return launch_status();
 }
 

@@ -169,8 +169,10 @@ struct HqMax { __device__ int operator()(int a, int b) const { return a > b ? a 
 struct HqAdd { __device__ int operator()(int a, int b) const { return a + b; } };
 
 // Merges one workgroup's statistics into the tensor's record: wavefront reduction, a
-// second level through LDS, then one atomic per field from one lane.  `red` is LDS space
-// for 4 * (NTHREADS / 64) ints.  Must be called by all NTHREADS threads of the workgroup.
+// second level through LDS, then one atomic per field from one lane, into the partial record
+// chosen by the workgroup's index: consecutive workgroups land on different 128-byte lines, so
+// a launch's atomics do not queue on one address.  `red` is LDS space for 4 * (NTHREADS / 64)
+// ints.  Must be called by all NTHREADS threads of the workgroup.
 template <int NTHREADS>
 __device__ inline void hq_block_stats_commit_n(int mn, int mx, unsigned nlo, unsigned nhi,
                                                hq_stats *st, int *red)
@@ -189,13 +191,37 @@ __device__ inline void hq_block_stats_commit_n(int mn, int mx, unsigned nlo, uns
             mn = min(mn, red[w]); mx = max(mx, red[NW + w]);
             lo += (unsigned)red[2 * NW + w]; hi += (unsigned)red[3 * NW + w];
         }
-        if (mn <= mx) { atomicMin(&st->acc_min, mn); atomicMax(&st->acc_max, mx); }
-        if (lo) atomicAdd((unsigned long long *)&st->clip_lo, lo);
-        if (hi) atomicAdd((unsigned long long *)&st->clip_hi, hi);
+        const unsigned block = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+        hq_stats_part *part = &st->part[block % HQ_STATS_PARTS];
+        if (mn <= mx) { atomicMin(&part->acc_min, mn); atomicMax(&part->acc_max, mx); }
+        if (lo) atomicAdd((unsigned long long *)&part->clip_lo, lo);
+        if (hi) atomicAdd((unsigned long long *)&part->clip_hi, hi);
     }
 }
 
 __device__ inline void hq_block_stats_commit(int mn, int mx, unsigned nlo, unsigned nhi, hq_stats *st, int *red)
 {
     hq_block_stats_commit_n<HQ_THREADS>(mn, mx, nlo, nhi, st, red);
+}
+
+// Moves what the partial records hold into the record's leading fields and empties them.
+// One wavefront (HQ_STATS_PARTS == 64 lanes, lane = partial record); `sh` is LDS space for
+// 2 * 64 64-bit words.  The leading fields are complete for every lane after the call.
+__device__ inline void hq_stats_fold_wave(hq_stats *st, unsigned long long *sh)
+{
+    static_assert(HQ_STATS_PARTS == 64, "one lane per partial record");
+    const int lane = threadIdx.x & 63;
+    hq_stats_part *p = &st->part[lane];
+    const int mn = hq_wave_reduce(p->acc_min, HqMin()), mx = hq_wave_reduce(p->acc_max, HqMax());
+    sh[lane] = p->clip_lo; sh[64 + lane] = p->clip_hi;
+    p->acc_min = INT_MAX; p->acc_max = INT_MIN; p->clip_lo = 0; p->clip_hi = 0;
+    __syncthreads();
+    if (lane == 0) {
+        unsigned long long lo = 0, hi = 0;
+        for (int i = 0; i < 64; i++) { lo += sh[i]; hi += sh[64 + i]; }
+        st->acc_min = min(st->acc_min, mn); st->acc_max = max(st->acc_max, mx);
+        st->clip_lo += lo; st->clip_hi += hi;
+    }
+    __threadfence_block();
+    __syncthreads();
 }

@@ -48,7 +48,11 @@ def read_range(r):
 
 
 def read_stats(st):
-    return hq.from_device(st, hq.STATS)[0]
+    """The statistics record with its partial records folded into the leading fields."""
+    hq.hq_stats_fold(st)
+    rec = hq.from_device(st, hq.STATS)[0]
+    assert (rec["part"]["clip_lo"] == 0).all() and (rec["part"]["acc_min"] == np.iinfo(np.int32).max).all()
+    return rec
 
 
 def read_qparams(q):

@@ -53,14 +53,19 @@ def test_struct_views_match_header_sizes():
                     ("qlo", ctypes.c_int32), ("qhi", ctypes.c_int32), ("symmetric", ctypes.c_int32),
                     ("initialized", ctypes.c_int32), ("qp", QP)]
 
+    class PT(ctypes.Structure):
+        _fields_ = [("acc_min", ctypes.c_int32), ("acc_max", ctypes.c_int32), ("clip_lo", ctypes.c_uint64),
+                    ("clip_hi", ctypes.c_uint64), ("pad", ctypes.c_uint8 * 104)]
+
     class ST(ctypes.Structure):
         _fields_ = [("acc_min", ctypes.c_int32), ("acc_max", ctypes.c_int32), ("acc_scale", ctypes.c_float),
                     ("reserved", ctypes.c_uint32), ("clip_lo", ctypes.c_uint64), ("clip_hi", ctypes.c_uint64),
-                    ("count", ctypes.c_uint64)]
+                    ("count", ctypes.c_uint64), ("pad", ctypes.c_uint8 * 88), ("part", PT * 64)]
 
     assert ctypes.sizeof(QP) == hq.QPARAMS.itemsize
     assert ctypes.sizeof(RG) == hq.RANGE.itemsize and RG.qp.offset == hq.RANGE.fields["scale"][1]
     assert ctypes.sizeof(ST) == hq.STATS.itemsize and ST.clip_lo.offset == hq.STATS.fields["clip_lo"][1]
+    assert ctypes.sizeof(PT) == 128 and ST.part.offset == hq.STATS.fields["part"][1] == 128
     assert ctypes.sizeof(hq.hq_problem) == 40
 
 
