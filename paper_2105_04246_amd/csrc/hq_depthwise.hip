@@ -294,6 +294,127 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_wgrad_kernel(const Dw
     }
 }
 
+// 3x3, stride 1, pad 1 weight gradient: the thread layout of hq_dw3x3_kernel (four channels of
+// one column, sliding down a strip of rows with the 3x3 input window unpacked in registers), so
+// an output row costs three new input words and one gradient word instead of ten loads with
+// their address arithmetic.  A workgroup walks over several images and keeps its 36 products
+// per thread in registers; threads that share channels meet in LDS, and the workgroup leaves
+// with one atomic per value.  The column sums of the input that remove the gradient's zero
+// point are only gathered when that zero point is not 0.
+struct Dw3WgradArgs {
+    const int8_t *X, *G;
+    const hq_qparams *xq, *gq;
+    int32_t *acc, *gsum, *xsum;
+    int B, H, W, C;
+    int rows_per_strip;
+};
+
+__global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_wgrad_kernel(const Dw3WgradArgs a)
+{
+    extern __shared__ int lds[];                 // [9][C] acc, [C] gsum, [9][C] xsum
+    const int words = 19 * a.C;
+    for (int i = threadIdx.x; i < words; i += HQ_THREADS) lds[i] = 0;
+    __syncthreads();
+    const int c4n = a.C >> 2, rowwords = a.W * c4n;
+    const int q = blockIdx.x * HQ_THREADS + threadIdx.x;
+    const bool live = q < rowwords;
+    const int qq = live ? q : 0;
+    const int ox = qq / c4n, c = (qq - ox * c4n) * 4;
+    const int y0 = blockIdx.y * a.rows_per_strip, y1 = min(a.H, y0 + a.rows_per_strip);
+    const int zx = a.xq->zero_point;
+    const bool want_xsum = a.gq->zero_point != 0;
+    const int fill = (zx & 0xff) * 0x01010101;
+    const bool okl = ox > 0, okr = ox + 1 < a.W;
+    const size_t rowbytes = (size_t)a.W * a.C;
+
+    int acc[9][4], xs[9][4], gs[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < 9; t++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) { acc[t][e] = 0; xs[t][e] = 0; }
+
+    if (live && y0 < y1) {
+        for (int b = blockIdx.z; b < a.B; b += gridDim.z) {
+            const int8_t *pcol = a.X + (size_t)b * a.H * rowbytes + (size_t)ox * a.C + c;
+            const int8_t *pg = a.G + (size_t)b * a.H * rowbytes + (size_t)y0 * rowbytes + (size_t)ox * a.C + c;
+            auto load_row = [&](const int8_t *p, bool rowok, int *dst) {
+                dst[0] = (rowok && okl) ? *reinterpret_cast<const int *>(p - a.C) : fill;
+                dst[1] = rowok ? *reinterpret_cast<const int *>(p) : fill;
+                dst[2] = (rowok && okr) ? *reinterpret_cast<const int *>(p + a.C) : fill;
+            };
+            const int8_t *pn = pcol + (size_t)(y0 > 0 ? y0 - 1 : 0) * rowbytes;
+            int win[3][3][4], ring[3][3], gring[3];
+            {
+                int tmp[3];
+                load_row(pn, y0 > 0, tmp);
+                if (y0 > 0) pn += rowbytes;
+#pragma unroll
+                for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[0][s]);
+                load_row(pn, true, tmp);
+                pn += rowbytes;
+#pragma unroll
+                for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[1][s]);
+#pragma unroll
+                for (int k = 0; k < 3; k++) {
+                    load_row(pn, y0 + 1 + k < a.H, ring[k]);
+                    pn += rowbytes;
+                    gring[k] = y0 + k < y1 ? *reinterpret_cast<const int *>(pg) : 0;
+                    pg += rowbytes;
+                }
+            }
+#define DWW_STEP(TOP, MID, BOT, RING)                                                                      \
+            if (oy < y1) {                                                                                \
+                _Pragma("unroll") for (int s = 0; s < 3; s++) dw_unpack(ring[RING][s], win[BOT][s]);        \
+                int g[4];                                                                                 \
+                dw_unpack(gring[RING], g);                                                                \
+                if (oy + 3 < y1) {                                                                        \
+                    load_row(pn, oy + 4 < a.H, ring[RING]); pn += rowbytes;                               \
+                    gring[RING] = *reinterpret_cast<const int *>(pg); pg += rowbytes;                      \
+                }                                                                                         \
+                _Pragma("unroll") for (int e = 0; e < 4; e++) {                                             \
+                    gs[e] += g[e];                                                                        \
+                    _Pragma("unroll") for (int s = 0; s < 3; s++) {                                         \
+                        acc[s][e] += __mul24(win[TOP][s][e], g[e]);                                       \
+                        acc[3 + s][e] += __mul24(win[MID][s][e], g[e]);                                   \
+                        acc[6 + s][e] += __mul24(win[BOT][s][e], g[e]);                                   \
+                    }                                                                                     \
+                }                                                                                         \
+                if (want_xsum) {                                                                          \
+                    _Pragma("unroll") for (int e = 0; e < 4; e++)                                           \
+                        _Pragma("unroll") for (int s = 0; s < 3; s++) {                                     \
+                            xs[s][e] += win[TOP][s][e]; xs[3 + s][e] += win[MID][s][e]; xs[6 + s][e] += win[BOT][s][e]; \
+                        }                                                                                 \
+                }                                                                                         \
+            }                                                                                             \
+            oy++;
+            for (int oy = y0; oy < y1;) {
+                DWW_STEP(0, 1, 2, 0)
+                DWW_STEP(1, 2, 0, 1)
+                DWW_STEP(2, 0, 1, 2)
+            }
+#undef DWW_STEP
+        }
+#pragma unroll
+        for (int t = 0; t < 9; t++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                atomicAdd(&lds[t * a.C + c + e], acc[t][e]);
+                if (want_xsum) atomicAdd(&lds[(10 + t) * a.C + c + e], xs[t][e]);
+            }
+#pragma unroll
+        for (int e = 0; e < 4; e++) atomicAdd(&lds[9 * a.C + c + e], gs[e]);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < words; i += HQ_THREADS) {
+        const int v = lds[i];
+        if (v == 0) continue;
+        const int row = i / a.C, col = i - row * a.C;
+        if (row < 9) atomicAdd(a.acc + row * a.C + col, v);
+        else if (row == 9) atomicAdd(a.gsum + col, v);
+        else atomicAdd(a.xsum + (row - 10) * a.C + col, v);
+    }
+}
+
 __global__ void dw_zero_kernel(int32_t *p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
@@ -369,6 +490,27 @@ int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qpa
     a.stride = p->stride; a.pad = p->pad;
     const size_t ws_words = hq_wgrad_workspace_bytes(p) / 4;
     hipLaunchKernelGGL(dw_zero_kernel, dim3(16), dim3(256), 0, stream, a.acc, ws_words);
+    if (p->R == 3 && p->S == 3 && p->stride == 1 && p->pad == 1 && 19 * (size_t)p->C * 4 <= 64 * 1024) {
+        Dw3WgradArgs d;
+        d.X = X; d.G = dY; d.xq = xq; d.gq = gq; d.acc = a.acc; d.gsum = a.gsum; d.xsum = a.xsum;
+        d.B = p->B; d.H = p->H; d.W = p->W; d.C = p->C;
+        const int xb = (p->W * (p->C / 4) + HQ_THREADS - 1) / HQ_THREADS;
+        // about four workgroups per compute unit: strips of at least 6 rows, then images in turn
+        int strips = p->H / 6 > 0 ? p->H / 6 : 1;
+        while (strips > 1 && xb * strips > 1024) strips--;
+        int rps = (p->H + strips - 1) / strips;
+        rps = (rps + 2) / 3 * 3;
+        d.rows_per_strip = rps;
+        strips = (p->H + rps - 1) / rps;
+        int gz = 1024 / (xb * strips);
+        if (gz < 1) gz = 1;
+        if (gz > p->B) gz = p->B;
+        hipLaunchKernelGGL(hq_dw3x3_wgrad_kernel, dim3((unsigned)xb, (unsigned)strips, (unsigned)gz), dim3(HQ_THREADS),
+                           19 * (size_t)p->C * 4, stream, d);
+        hipLaunchKernelGGL(dw_wgrad_finalize_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream,
+                           a.acc, a.gsum, a.xsum, xq, gq, (unsigned)a.M, (int)K, p->C, dW, dW_acc);
+        return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+    }
     a.CT = p->C < 256 ? p->C : 256;
     const int ctiles = (p->C + a.CT - 1) / a.CT;
     int blocks = (2048 + ctiles - 1) / ctiles;

@@ -235,6 +235,282 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// 3x3, stride 1, pad 1, C % 64 == 0 and Cout % 64 == 0: the shape of most layers of the paper's
+// networks (Table 5; ResNet-18 basic blocks).  One workgroup owns a 64 (Cout) x 64 (C) block of
+// G_W for all nine taps (36 MFMA tiles, in registers for the whole launch) and walks a run of
+// pixel bands.  A band (a few output rows of one image, or a few whole small images) is
+// staged once: the dY rows as they lie in memory and the input rows with their one-pixel
+// border; the nine taps are nine shifted views of that input patch, so an input byte is
+// fetched once per band instead of once per tap.
+// The reduction index of an MFMA k-step is the output pixel; the transposing LDS read takes
+// a row address per lane, so each lane looks up the patch row of its pixels in a small
+// table (pixel -> row of tap (0,0)) and adds the tap's offset.
+// 512 threads: two groups of four wavefronts take alternate k-steps of a band (both groups
+// accumulate the same 36 tiles and are added through LDS at the end); inside a group a
+// wavefront owns one 32-channel block of C and taps 0..4 or 5..8 for both 32-blocks of Cout:
+// 7 fragments feed 10 MFMAs.
+// ---------------------------------------------------------------------------------------
+constexpr int WB_THREADS = 512;
+constexpr int WB_P = 96;               // LDS pitch of a 64-channel pixel row (32 mod 64: transposing reads)
+constexpr int WB_XLD = 3, WB_GLD = 2;  // 16-byte chunks a thread stages per band (input patch / dY rows)
+
+struct WbandArgs {
+    const int8_t *X, *G;
+    const hq_qparams *xq;
+    int32_t *acc, *gsum, *xsum;
+    int B, H, W, C, N;
+    int rows, nimg;                // band: `rows` output rows of one image, or `nimg` whole images (rows == H)
+    int bands_per_img;
+    int nstages, stages_per_block, splits;
+    int copies;                    // 8: one copy of acc per XCD (acc + xcd * N * 9 * C), 1: a single copy
+    int cparts, nparts;            // C / 64, N / 64
+    int npix, npix_pad;            // output pixels of a band, rounded up to a k-step
+    int prows, PW;                 // patch rows (nimg * (rows + 2)) and patch row length (W + 2)
+    int xchunks, gchunks;          // 16-byte chunks of a patch / of a band of dY
+    unsigned buf_bytes;            // one LDS buffer: patch + dY band
+};
+
+__global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+    unsigned *tbl = reinterpret_cast<unsigned *>(smem);                 // [npix_pad] patch byte offset of pixel k
+    int8_t *bufs = smem + ((a.npix_pad * 4 + 15) & ~15);
+    const unsigned xbytes = (unsigned)a.prows * a.PW * WB_P;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = wave >> 2, cblk = wave & 1, th = (wave >> 1) & 1;
+    const int t0 = th ? 5 : 0, nt = th ? 4 : 5;
+
+    // workgroup -> (output block, run of bands); the blocks of one run sit on one XCD
+    int part, split;
+    {
+        const int per = a.cparts * a.nparts, total = per * a.splits;
+        const int full = (total / (8 * per)) * (8 * per);
+        if ((int)blockIdx.x < full) {
+            const int g8 = blockIdx.x / (8 * per), r = blockIdx.x % (8 * per);
+            split = g8 * 8 + (r & 7); part = r >> 3;
+        } else {
+            const int r = blockIdx.x - full;
+            split = full / per + r / per; part = r % per;
+        }
+    }
+    const int cp = part % a.cparts, np = part / a.cparts;
+    const int c0 = cp * 64, n0 = np * 64;
+    const int s_begin = split * a.stages_per_block, s_end = min(a.nstages, s_begin + a.stages_per_block);
+    const int zx = a.xq->zero_point;
+    const int fillw = (zx & 0xff) * 0x01010101;
+    const bool do_gsum = cp == 0 && cblk == 0 && th == 0;
+    const bool do_xsum = np == 0;
+
+    // ---- per-thread staging plan (the same for every band)
+    int x_lds[WB_XLD], x_rel[WB_XLD], x_pr[WB_XLD], x_il[WB_XLD];
+    bool x_on[WB_XLD], x_col[WB_XLD];
+#pragma unroll
+    for (int i = 0; i < WB_XLD; i++) {
+        const int idx = tid + WB_THREADS * i, c16 = idx & 3, ppix = idx >> 2;
+        const int prow = ppix / a.PW, pcol = ppix - prow * a.PW;
+        x_on[i] = idx < a.xchunks;
+        x_il[i] = prow / (a.rows + 2); x_pr[i] = prow - x_il[i] * (a.rows + 2);
+        x_col[i] = pcol >= 1 && pcol <= a.W;
+        x_lds[i] = ppix * WB_P + c16 * 16;
+        x_rel[i] = ((x_il[i] * a.H + x_pr[i] - 1) * a.W + (pcol - 1)) * a.C + c16 * 16;
+    }
+    int g_lds[WB_GLD], g_rel[WB_GLD], g_il[WB_GLD];
+    bool g_on[WB_GLD];
+#pragma unroll
+    for (int i = 0; i < WB_GLD; i++) {
+        const int idx = tid + WB_THREADS * i, c16 = idx & 3, p = idx >> 2;
+        g_on[i] = idx < a.gchunks;
+        g_il[i] = p / (a.rows * a.W);
+        g_lds[i] = p * WB_P + c16 * 16;
+        g_rel[i] = p * a.N + c16 * 16;
+    }
+    v4i xreg[WB_XLD], greg[WB_GLD];
+    auto load_stage = [&](int s) {
+        int b0, y0;
+        if (a.nimg == 1) { b0 = s / a.bands_per_img; y0 = (s - b0 * a.bands_per_img) * a.rows; }
+        else { b0 = s * a.nimg; y0 = 0; }
+        const size_t pix0 = ((size_t)b0 * a.H + y0) * a.W;
+        const int8_t *xs = a.X + pix0 * a.C + c0;
+        const int8_t *gs = a.G + pix0 * a.N + n0;
+#pragma unroll
+        for (int i = 0; i < WB_XLD; i++) {
+            const bool img = b0 + x_il[i] < a.B;                    // images past the end of the batch count as zeros
+            const bool inside = img && x_col[i] && (unsigned)(y0 + x_pr[i] - 1) < (unsigned)a.H;
+            const int f = img ? fillw : 0;                          // border of a real image: real zero
+            v4i v = {f, f, f, f};
+            if (x_on[i] && inside) v = *reinterpret_cast<const v4i *>(xs + x_rel[i]);
+            xreg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < WB_GLD; i++) {
+            v4i v = {0, 0, 0, 0};
+            if (g_on[i] && b0 + g_il[i] < a.B) v = *reinterpret_cast<const v4i *>(gs + g_rel[i]);
+            greg[i] = v;
+        }
+    };
+    auto store_stage = [&](int buf) {
+        int8_t *xb = bufs + buf * a.buf_bytes, *gb = xb + xbytes;
+#pragma unroll
+        for (int i = 0; i < WB_XLD; i++)
+            if (x_on[i]) *reinterpret_cast<v4i *>(xb + x_lds[i]) = xreg[i];
+#pragma unroll
+        for (int i = 0; i < WB_GLD; i++)
+            if (g_on[i]) *reinterpret_cast<v4i *>(gb + g_lds[i]) = greg[i];
+    };
+
+    // ---- start-up: first band on its way, pixel table, zero rows behind the last pixel of a band
+    if (s_begin < s_end) load_stage(s_begin);
+    for (int k = tid; k < a.npix_pad; k += WB_THREADS) {
+        unsigned off = 0;                                  // pixels past the band read patch row 0 (their dY is zero)
+        if (k < a.npix) {
+            const int il = k / (a.rows * a.W), rem = k - il * a.rows * a.W;
+            const int oy = rem / a.W, ox = rem - oy * a.W;
+            off = (unsigned)(((il * (a.rows + 2) + oy) * a.PW + ox) * WB_P);
+        }
+        tbl[k] = off;
+    }
+    for (int i = tid; i < (a.npix_pad - a.npix) * (WB_P / 4) * 2; i += WB_THREADS) {
+        const int buf = i / ((a.npix_pad - a.npix) * (WB_P / 4)), w = i % ((a.npix_pad - a.npix) * (WB_P / 4));
+        reinterpret_cast<int *>(bufs + buf * a.buf_bytes + xbytes + a.npix * WB_P)[w] = 0;
+    }
+    if (s_begin < s_end) store_stage(0);
+    __syncthreads();
+
+    v16i acc[2][5];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int u = 0; u < 5; u++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][u][r] = 0;
+    int gsv[2] = {0, 0}, xsv[5] = {0, 0, 0, 0, 0};
+
+    // lane's place in a fragment: rows klo and klo + 8 of the k-step, 8 bytes at column `fcol`
+    const int j16 = lane & 15;
+    const int klo = (lane >> 5) * 16 + (j16 >> 1);
+    const int fcol = 16 * ((lane >> 4) & 1) + 8 * (j16 & 1);
+    unsigned tapoff[5];
+#pragma unroll
+    for (int u = 0; u < 5; u++) {
+        const int t = min(t0 + u, 8);
+        tapoff[u] = (unsigned)(((t / 3) * a.PW + (t % 3)) * WB_P) + cblk * 32 + fcol;
+    }
+    const int nks = a.npix_pad / 32, ninv = a.npix_pad - a.npix;
+
+    for (int s = s_begin; s < s_end; s++) {
+        const int it = s - s_begin, buf = it & 1;
+        const bool more = s + 1 < s_end;
+        if (more) load_stage(s + 1);
+        const int8_t *xb = bufs + buf * a.buf_bytes, *gb = xb + xbytes;
+        for (int ks = (grp + it) & 1; ks < nks; ks += 2) {
+            const int kb = ks * 32;
+            const unsigned rlo = tbl[kb + klo], rhi = tbl[kb + klo + 8];
+            v4i gf[2], xf[5];
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const int8_t *p = gb + (kb + klo) * WB_P + i * 32 + fcol;
+                const tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(p));
+                const tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(p + 8 * WB_P));
+                gf[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int u = 0; u < 5; u++) {
+                if (u < nt) {
+                    const tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(xb + rlo + tapoff[u]));
+                    const tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(xb + rhi + tapoff[u]));
+                    xf[u] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 5; u++) {
+                if (u < nt) {
+#pragma unroll
+                    for (int i = 0; i < 2; i++)
+                        acc[i][u] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gf[i], xf[u], acc[i][u], 0, 0, 0);
+                }
+            }
+            if (do_gsum) {
+#pragma unroll
+                for (int i = 0; i < 2; i++)
+#pragma unroll
+                    for (int d = 0; d < 4; d++) gsv[i] = __builtin_amdgcn_sdot4(gf[i][d], 0x01010101, gsv[i], false);
+            }
+            if (do_xsum) {
+#pragma unroll
+                for (int u = 0; u < 5; u++) {
+                    if (u < nt) {
+#pragma unroll
+                        for (int d = 0; d < 4; d++) xsv[u] = __builtin_amdgcn_sdot4(xf[u][d], 0x01010101, xsv[u], false);
+                        // the last k-step read patch row 0 for its `ninv` pixels past the band: take that back
+                        if (ninv > 0 && ks == nks - 1 && lane < 32)
+                            xsv[u] -= ninv * (int)xb[tapoff[u] - fcol + (lane & 31)];
+                    }
+                }
+            }
+        }
+        if (more) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- add the two groups through LDS (one 32-block of Cout at a time), then merge into the
+    // launch-wide sums.  G fragments were the first MFMA operand: lane l holds input channel
+    // l % 32 and output channels 8*(r/4) + 4*(l/32) + r%4 of the block.
+    int *xch = reinterpret_cast<int *>(smem);
+    const int t256 = tid & 255;
+    const size_t krow = (size_t)9 * a.C;
+    // Small outputs are summed into one copy per XCD, picked by the id of the XCD this workgroup
+    // runs on: a line of a copy is then only ever touched through one L2.  Any id is correct.
+    int32_t *accp = a.acc;
+    if (a.copies == 8) {
+        int xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
+        accp += (size_t)(xcc & 7) * a.N * krow;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+        if (grp == 1) {
+#pragma unroll
+            for (int u = 0; u < 5; u++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) xch[(u * 16 + r) * 256 + t256] = acc[i][u][r];
+        }
+        __syncthreads();
+        if (grp == 0) {
+            const int c = c0 + cblk * 32 + (lane & 31);
+#pragma unroll
+            for (int u = 0; u < 5; u++) {
+                if (u < nt) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int v = acc[i][u][r] + xch[(u * 16 + r) * 256 + t256];
+                        const int n = n0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                        if (v != 0) atomicAdd(accp + (size_t)n * krow + (size_t)(t0 + u) * a.C + c, v);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (do_gsum) {
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            const int sm = gsv[i] + __shfl_xor(gsv[i], 32);
+            if (lane < 32 && sm != 0) atomicAdd(a.gsum + n0 + i * 32 + (lane & 31), sm);
+        }
+    }
+    if (do_xsum) {
+#pragma unroll
+        for (int u = 0; u < 5; u++) {
+            if (u < nt) {
+                const int sm = xsv[u] + __shfl_xor(xsv[u], 32);
+                if (lane < 32 && sm != 0) atomicAdd(a.xsum + (size_t)(t0 + u) * a.C + c0 + cblk * 32 + (lane & 31), sm);
+            }
+        }
+    }
+}
+
 __global__ void zero_kernel(int32_t *p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
@@ -244,7 +520,7 @@ __global__ void zero_kernel(int32_t *p, size_t n)
 // result fits 32 bits) and applies the one FP32 scale.
 __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, const int32_t *xsum,
                                       const hq_qparams *xq, const hq_qparams *gq, unsigned M, int N, int K,
-                                      int gsum_per_k, float *dW, int32_t *dW_acc)
+                                      int gsum_per_k, int copies, float *dW, int32_t *dW_acc)
 {
     const unsigned zx = (unsigned)xq->zero_point, zg = (unsigned)gq->zero_point;
     const float s = __fmul_rn(xq->scale, gq->scale);
@@ -252,7 +528,9 @@ __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, c
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int n = (int)(i / K), k = (int)(i % K);
         const unsigned g = (unsigned)gsum[gsum_per_k ? k % gsum_per_k : n];
-        unsigned c = (unsigned)acc[i] - zx * g - zg * (unsigned)xsum[k] + M * zx * zg;
+        unsigned sum = 0;
+        for (int q = 0; q < copies; q++) sum += (unsigned)acc[(size_t)q * total + i];
+        unsigned c = sum - zx * g - zg * (unsigned)xsum[k] + M * zx * zg;
         if (dW_acc) dW_acc[i] = (int)c;
         dW[i] = __fmul_rn(s, (float)(int)c);
     }
@@ -260,13 +538,80 @@ __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, c
 
 size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
+bool wgrad_band_shape(const hq_problem *p)
+{
+    return p->kind == HQ_CONV2D && p->R == 3 && p->S == 3 && p->stride == 1 && p->pad == 1 &&
+           p->C % 64 == 0 && p->Cout % 64 == 0;
+}
+
+// Copies of the integer sum in the workspace: small weight tensors of band-kernel layers get one
+// per XCD (32 MB of copies at most).
+int wgrad_copies(const hq_problem *p)
+{
+    return wgrad_band_shape(p) && (size_t)p->Cout * 9 * p->C <= ((size_t)1 << 20) ? 8 : 1;
+}
+
+// Band kernel geometry; false when the layer is not covered (the tile kernel takes it).
+bool launch_wgrad_band(const hq_problem *p, const WgradArgs &w, hipStream_t stream)
+{
+    if (!wgrad_band_shape(p)) return false;
+    const int H = p->H, W = p->W;
+    // candidates: `rows` output rows of one image (rows | H), or `nimg` whole images; a band holds at
+    // most 256 pixels and what 512 threads stage in WB_XLD / WB_GLD chunks each.  Prefer the band
+    // that wastes the fewest k-steps (the two groups take ceil(nks / 2) k-steps per band).
+    int best_rows = 0, best_nimg = 0;
+    double best_eff = 0.0;
+    auto consider = [&](int rows, int nimg) {
+        const int npix = nimg * rows * W, prows = nimg * (rows + 2);
+        if (npix > 256 || npix * 4 > WB_GLD * WB_THREADS || prows * (W + 2) * 4 > WB_XLD * WB_THREADS) return;
+        const int nks = (npix + 31) / 32;
+        const double eff = (double)npix / (64.0 * ((nks + 1) / 2));
+        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && npix > best_nimg * best_rows * W)) {
+            best_eff = eff; best_rows = rows; best_nimg = nimg;
+        }
+    };
+    for (int rows = 1; rows <= H; rows++) if (H % rows == 0) consider(rows, 1);
+    for (int nimg = 2; nimg * H * W <= 256; nimg++) consider(H, nimg);
+    if (best_rows == 0) return false;
+
+    WbandArgs a;
+    a.X = w.X; a.G = w.G; a.xq = w.xq; a.acc = w.acc; a.gsum = w.gsum; a.xsum = w.xsum;
+    a.B = p->B; a.H = H; a.W = W; a.C = p->C; a.N = p->Cout;
+    a.rows = best_rows; a.nimg = best_nimg;
+    a.bands_per_img = H / best_rows;
+    a.nstages = best_nimg == 1 ? p->B * a.bands_per_img : (p->B + best_nimg - 1) / best_nimg;
+    a.cparts = p->C / 64; a.nparts = p->Cout / 64;
+    a.copies = wgrad_copies(p);
+    a.npix = best_nimg * best_rows * W; a.npix_pad = (a.npix + 31) & ~31;
+    a.prows = best_nimg * (best_rows + 2); a.PW = W + 2;
+    a.xchunks = a.prows * a.PW * 4; a.gchunks = a.npix * 4;
+    a.buf_bytes = (unsigned)(a.prows * a.PW * WB_P + a.npix_pad * WB_P);
+    size_t lds = (size_t)((a.npix_pad * 4 + 15) & ~15) + 2 * (size_t)a.buf_bytes;
+    const size_t reduce_bytes = 5 * 16 * 256 * 4;           // the two groups meet in LDS at the end
+    if (lds < reduce_bytes) lds = reduce_bytes;
+    if (lds > 160 * 1024) return false;
+    const int parts = a.cparts * a.nparts;
+    int splits = parts >= 256 ? 1 : (256 + parts - 1) / parts;     // one workgroup per compute unit
+    if (splits > a.nstages) splits = a.nstages;
+    a.stages_per_block = (a.nstages + splits - 1) / splits;
+    a.splits = (a.nstages + a.stages_per_block - 1) / a.stages_per_block;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_wgrad_band_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return false;
+        configured = true;
+    }
+    hipLaunchKernelGGL(hq_wgrad_band_kernel, dim3((unsigned)(parts * a.splits)), dim3(WB_THREADS), lds, stream, a);
+    return true;
+}
+
 } // namespace
 
 size_t hq_wgrad_workspace_bytes(const hq_problem *p)
 {
     const size_t K = (size_t)p->R * p->S * p->C;
     if (p->kind == HQ_DEPTHWISE) return align16(4 * K) + align16(4 * (size_t)p->C) + align16(4 * K);
-    return align16(4 * (size_t)p->Cout * K) + align16(4 * (size_t)p->Cout) + align16(4 * K);
+    return align16(4 * (size_t)p->Cout * K * wgrad_copies(p)) + align16(4 * (size_t)p->Cout) + align16(4 * K);
 }
 
 int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
@@ -278,15 +623,27 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     a.X = X; a.G = dY; a.xq = xq; a.gq = gq;
     char *w = static_cast<char *>(ws);
     a.acc = reinterpret_cast<int32_t *>(w);
-    a.gsum = reinterpret_cast<int32_t *>(w + align16(4 * (size_t)p->Cout * K));
-    a.xsum = reinterpret_cast<int32_t *>(w + align16(4 * (size_t)p->Cout * K) + align16(4 * (size_t)p->Cout));
+    const size_t acc_bytes = align16(4 * (size_t)p->Cout * K * wgrad_copies(p));
+    a.gsum = reinterpret_cast<int32_t *>(w + acc_bytes);
+    a.xsum = reinterpret_cast<int32_t *>(w + acc_bytes + align16(4 * (size_t)p->Cout));
     a.M = p->B * OH * OW; a.N = p->Cout; a.C = p->C;
     a.R = p->R; a.S = p->S; a.H = p->H; a.W = p->W; a.OH = OH; a.OW = OW; a.stride = p->stride; a.pad = p->pad;
     a.g16 = (a.N % 16) == 0; a.x16 = (a.C % 16) == 0;
 
+    auto finalize = [&](int copies) {
+        const size_t total = (size_t)a.N * K;
+        unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
+        hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb), dim3(256), 0, stream, a.acc, a.gsum, a.xsum, xq, gq,
+                           (unsigned)a.M, a.N, (int)K, 0, copies, dW, dW_acc);
+    };
     const size_t ws_words = hq_wgrad_workspace_bytes(p) / 4;
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
                        dim3(256), 0, stream, a.acc, ws_words);
+
+    if (launch_wgrad_band(p, a, stream)) {
+        finalize(wgrad_copies(p));
+        return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+    }
 
     const bool big = a.N > 64 && a.C > 64;
     const int TN = big ? 128 : 64, TK = big ? 128 : 64;
@@ -304,9 +661,6 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128>), grid, dim3(HQ_THREADS), 0, stream, a);
     else     hipLaunchKernelGGL((hq_wgrad_kernel<64, 64>), grid, dim3(HQ_THREADS), 0, stream, a);
 
-    const size_t total = (size_t)a.N * K;
-    unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
-    hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb), dim3(256), 0, stream, a.acc, a.gsum, a.xsum, xq, gq,
-                       (unsigned)a.M, a.N, (int)K, 0, dW, dW_acc);
+    finalize(1);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }
