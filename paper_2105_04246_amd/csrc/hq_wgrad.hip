@@ -254,16 +254,18 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 constexpr int WB_THREADS = 512;
 constexpr int WB_P = 96;               // LDS pitch of a 64-channel pixel row (32 mod 64: transposing reads)
 constexpr int WB_XLD = 3, WB_GLD = 2;  // 16-byte chunks a thread stages per band (input patch / dY rows)
+constexpr int WB_SLOT_V4 = 2 * 5 * 4 * 256;   // 16-byte words of one workgroup's partial sums
+constexpr int WB_SUMS = 64 + 9 * 64;          // column sums a group of a workgroup leaves: dY [64], input [9][64]
 
 struct WbandArgs {
     const int8_t *X, *G;
     const hq_qparams *xq;
-    int32_t *acc, *gsum, *xsum;
+    int32_t *partial;              // [slot][WB_SLOT_V4] 16-byte words: this workgroup's 64 x 9 x 64 sums
+    int32_t *sums;                 // [slot][2 groups][64 + 9 * 64]: column sums of dY and of the input taps
     int B, H, W, C, N;
     int rows, nimg;                // band: `rows` output rows of one image, or `nimg` whole images (rows == H)
     int bands_per_img;
     int nstages, stages_per_block, splits;
-    int copies;                    // 8: one copy of acc per XCD (acc + xcd * N * 9 * C), 1: a single copy
     int cparts, nparts;            // C / 64, N / 64
     int npix, npix_pad;            // output pixels of a band, rounded up to a k-step
     int prows, PW;                 // patch rows (nimg * (rows + 2)) and patch row length (W + 2)
@@ -454,50 +456,45 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
         __syncthreads();
     }
 
-    // ---- add the two groups through LDS (one 32-block of Cout at a time), then merge into the
-    // launch-wide sums.  G fragments were the first MFMA operand: lane l holds input channel
-    // l % 32 and output channels 8*(r/4) + 4*(l/32) + r%4 of the block.
+    // ---- add the two groups through LDS, one 32-block of Cout per round (the group that
+    // receives alternates), and store this workgroup's partial sums with plain 16-byte stores:
+    // partial[slot][i][u][r / 4][thread][r % 4].  The finalize kernel adds the slots; merging
+    // with atomics instead would queue every workgroup of the launch on the same lines.
     int *xch = reinterpret_cast<int *>(smem);
     const int t256 = tid & 255;
-    const size_t krow = (size_t)9 * a.C;
-    // Small outputs are summed into one copy per XCD, picked by the id of the XCD this workgroup
-    // runs on: a line of a copy is then only ever touched through one L2.  Any id is correct.
-    int32_t *accp = a.acc;
-    if (a.copies == 8) {
-        int xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
-        accp += (size_t)(xcc & 7) * a.N * krow;
-    }
+    v4i *pout = reinterpret_cast<v4i *>(a.partial) + (size_t)(split * (a.cparts * a.nparts) + part) * WB_SLOT_V4;
 #pragma unroll
     for (int i = 0; i < 2; i++) {
-        if (grp == 1) {
+        if (grp != i) {
 #pragma unroll
             for (int u = 0; u < 5; u++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) xch[(u * 16 + r) * 256 + t256] = acc[i][u][r];
         }
         __syncthreads();
-        if (grp == 0) {
-            const int c = c0 + cblk * 32 + (lane & 31);
+        if (grp == i) {
 #pragma unroll
             for (int u = 0; u < 5; u++) {
                 if (u < nt) {
 #pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int v = acc[i][u][r] + xch[(u * 16 + r) * 256 + t256];
-                        const int n = n0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                        if (v != 0) atomicAdd(accp + (size_t)n * krow + (size_t)(t0 + u) * a.C + c, v);
+                    for (int rq = 0; rq < 4; rq++) {
+                        v4i v;
+#pragma unroll
+                        for (int e = 0; e < 4; e++) v[e] = acc[i][u][4 * rq + e] + xch[(u * 16 + 4 * rq + e) * 256 + t256];
+                        pout[((i * 5 + u) * 4 + rq) * 256 + t256] = v;
                     }
                 }
             }
         }
         __syncthreads();
     }
+    // column sums: plain stores as well, one record per workgroup and group
+    int *sp = a.sums + ((size_t)(split * (a.cparts * a.nparts) + part) * 2 + grp) * WB_SUMS;
     if (do_gsum) {
 #pragma unroll
         for (int i = 0; i < 2; i++) {
             const int sm = gsv[i] + __shfl_xor(gsv[i], 32);
-            if (lane < 32 && sm != 0) atomicAdd(a.gsum + n0 + i * 32 + (lane & 31), sm);
+            if (lane < 32) sp[i * 32 + lane] = sm;
         }
     }
     if (do_xsum) {
@@ -505,7 +502,7 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
         for (int u = 0; u < 5; u++) {
             if (u < nt) {
                 const int sm = xsv[u] + __shfl_xor(xsv[u], 32);
-                if (lane < 32 && sm != 0) atomicAdd(a.xsum + (size_t)(t0 + u) * a.C + c0 + cblk * 32 + (lane & 31), sm);
+                if (lane < 32) sp[64 + (t0 + u) * 64 + cblk * 32 + lane] = sm;
             }
         }
     }
@@ -520,7 +517,7 @@ __global__ void zero_kernel(int32_t *p, size_t n)
 // result fits 32 bits) and applies the one FP32 scale.
 __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, const int32_t *xsum,
                                       const hq_qparams *xq, const hq_qparams *gq, unsigned M, int N, int K,
-                                      int gsum_per_k, int copies, float *dW, int32_t *dW_acc)
+                                      int gsum_per_k, float *dW, int32_t *dW_acc)
 {
     const unsigned zx = (unsigned)xq->zero_point, zg = (unsigned)gq->zero_point;
     const float s = __fmul_rn(xq->scale, gq->scale);
@@ -528,33 +525,81 @@ __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, c
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int n = (int)(i / K), k = (int)(i % K);
         const unsigned g = (unsigned)gsum[gsum_per_k ? k % gsum_per_k : n];
-        unsigned sum = 0;
-        for (int q = 0; q < copies; q++) sum += (unsigned)acc[(size_t)q * total + i];
-        unsigned c = sum - zx * g - zg * (unsigned)xsum[k] + M * zx * zg;
+        unsigned c = (unsigned)acc[i] - zx * g - zg * (unsigned)xsum[k] + M * zx * zg;
         if (dW_acc) dW_acc[i] = (int)c;
         dW[i] = __fmul_rn(s, (float)(int)c);
     }
 }
 
+
+// Band kernel's finalize: adds the workgroups' partial sums (64 threads along C, TY taking every
+// TY-th slot), removes the zero points and scales.  One thread owns 4 consecutive output
+// channels of one (tap, c): the 16 bytes a lane of the band kernel stored.
+template <int TY>
+__global__ __launch_bounds__(64 * TY) void wband_finalize_kernel(const int32_t *partial, const int32_t *sums,
+                                                              const hq_qparams *xq, const hq_qparams *gq, unsigned M,
+                                                              int N, int C, int splits, float *dW, int32_t *dW_acc)
+{
+    __shared__ v4i sh[TY][64];
+    __shared__ int shx[TY][64], shg[TY][4];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int cparts = C / 64, parts = cparts * (N / 64);
+    const size_t o = (size_t)blockIdx.x * 64 + tx;                 // (n / 4, tap, c), c fastest
+    const int c = (int)(o % C), tap = (int)((o / C) % 9), n0 = (int)(o / ((size_t)9 * C)) * 4;
+    const int cp = c / 64, cblk = (c >> 5) & 1, np = n0 / 64, i = (n0 >> 5) & 1, rq = (n0 >> 3) & 3, lh = (n0 >> 2) & 1;
+    const int th = tap >= 5, u = tap - 5 * th;
+    const int t256 = (th * 2 + cblk) * 64 + lh * 32 + (c & 31);
+    const v4i *src = reinterpret_cast<const v4i *>(partial) + (size_t)(np * cparts + cp) * WB_SLOT_V4 +
+                     ((i * 5 + u) * 4 + rq) * 256 + t256;
+    const int *xsrc = sums + (size_t)cp * 2 * WB_SUMS + 64 + tap * 64 + (c & 63);            // workgroups with np == 0
+    const int *gsrc = sums + (size_t)(np * cparts) * 2 * WB_SUMS + (n0 & 63) + (tx & 3);    // workgroups with cp == 0
+    v4i sum = {0, 0, 0, 0};
+    int xs = 0, gs = 0;
+    for (int s = ty; s < splits; s += TY) {
+        sum += src[(size_t)s * parts * WB_SLOT_V4];
+        const size_t so = (size_t)s * parts * 2 * WB_SUMS;
+        xs += xsrc[so] + xsrc[so + WB_SUMS];
+        if (tx < 4) gs += gsrc[so] + gsrc[so + WB_SUMS];
+    }
+    sh[ty][tx] = sum; shx[ty][tx] = xs;
+    if (tx < 4) shg[ty][tx] = gs;
+    __syncthreads();
+    if (ty != 0) return;
+    int g4[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int y = 1; y < TY; y++) { sum += sh[y][tx]; xs += shx[y][tx]; }
+#pragma unroll
+    for (int y = 0; y < TY; y++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) g4[e] += shg[y][e];
+    const unsigned zx = (unsigned)xq->zero_point, zg = (unsigned)gq->zero_point;
+    const float sc = __fmul_rn(xq->scale, gq->scale);
+    const size_t K = (size_t)9 * C, k = (size_t)tap * C + c;
+    const unsigned xterm = zg * (unsigned)xs, both = M * zx * zg;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        const unsigned v = (unsigned)sum[e] - zx * (unsigned)g4[e] - xterm + both;
+        const size_t idx = (size_t)(n0 + e) * K + k;
+        if (dW_acc) dW_acc[idx] = (int)v;
+        dW[idx] = __fmul_rn(sc, (float)(int)v);
+    }
+}
+
 size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
-bool wgrad_band_shape(const hq_problem *p)
-{
-    return p->kind == HQ_CONV2D && p->R == 3 && p->S == 3 && p->stride == 1 && p->pad == 1 &&
-           p->C % 64 == 0 && p->Cout % 64 == 0;
-}
+// Geometry of the band kernel for one layer (host, pure); covered == false: the tile kernel takes it.
+struct WbandPlan {
+    bool covered;
+    int rows, nimg, nstages, stages_per_block, splits, parts;
+    int npix, npix_pad, prows;
+    size_t lds, buf_bytes;
+};
 
-// Copies of the integer sum in the workspace: small weight tensors of band-kernel layers get one
-// per XCD (32 MB of copies at most).
-int wgrad_copies(const hq_problem *p)
+WbandPlan wband_plan(const hq_problem *p)
 {
-    return wgrad_band_shape(p) && (size_t)p->Cout * 9 * p->C <= ((size_t)1 << 20) ? 8 : 1;
-}
-
-// Band kernel geometry; false when the layer is not covered (the tile kernel takes it).
-bool launch_wgrad_band(const hq_problem *p, const WgradArgs &w, hipStream_t stream)
-{
-    if (!wgrad_band_shape(p)) return false;
+    WbandPlan pl = {};
+    if (p->kind != HQ_CONV2D || p->R != 3 || p->S != 3 || p->stride != 1 || p->pad != 1) return pl;
+    if (p->C % 64 != 0 || p->Cout % 64 != 0) return pl;
     const int H = p->H, W = p->W;
     // candidates: `rows` output rows of one image (rows | H), or `nimg` whole images; a band holds at
     // most 256 pixels and what 512 threads stage in WB_XLD / WB_GLD chunks each.  Prefer the band
@@ -572,46 +617,61 @@ bool launch_wgrad_band(const hq_problem *p, const WgradArgs &w, hipStream_t stre
     };
     for (int rows = 1; rows <= H; rows++) if (H % rows == 0) consider(rows, 1);
     for (int nimg = 2; nimg * H * W <= 256; nimg++) consider(H, nimg);
-    if (best_rows == 0) return false;
-
-    WbandArgs a;
-    a.X = w.X; a.G = w.G; a.xq = w.xq; a.acc = w.acc; a.gsum = w.gsum; a.xsum = w.xsum;
-    a.B = p->B; a.H = H; a.W = W; a.C = p->C; a.N = p->Cout;
-    a.rows = best_rows; a.nimg = best_nimg;
-    a.bands_per_img = H / best_rows;
-    a.nstages = best_nimg == 1 ? p->B * a.bands_per_img : (p->B + best_nimg - 1) / best_nimg;
-    a.cparts = p->C / 64; a.nparts = p->Cout / 64;
-    a.copies = wgrad_copies(p);
-    a.npix = best_nimg * best_rows * W; a.npix_pad = (a.npix + 31) & ~31;
-    a.prows = best_nimg * (best_rows + 2); a.PW = W + 2;
-    a.xchunks = a.prows * a.PW * 4; a.gchunks = a.npix * 4;
-    a.buf_bytes = (unsigned)(a.prows * a.PW * WB_P + a.npix_pad * WB_P);
-    size_t lds = (size_t)((a.npix_pad * 4 + 15) & ~15) + 2 * (size_t)a.buf_bytes;
+    if (best_rows == 0) return pl;
+    pl.rows = best_rows; pl.nimg = best_nimg;
+    pl.nstages = best_nimg == 1 ? p->B * (H / best_rows) : (p->B + best_nimg - 1) / best_nimg;
+    pl.parts = (p->C / 64) * (p->Cout / 64);
+    pl.npix = best_nimg * best_rows * W; pl.npix_pad = (pl.npix + 31) & ~31;
+    pl.prows = best_nimg * (best_rows + 2);
+    pl.buf_bytes = (size_t)pl.prows * (W + 2) * WB_P + (size_t)pl.npix_pad * WB_P;
+    pl.lds = (size_t)((pl.npix_pad * 4 + 15) & ~15) + 2 * pl.buf_bytes;
     const size_t reduce_bytes = 5 * 16 * 256 * 4;           // the two groups meet in LDS at the end
-    if (lds < reduce_bytes) lds = reduce_bytes;
-    if (lds > 160 * 1024) return false;
-    const int parts = a.cparts * a.nparts;
-    int splits = parts >= 256 ? 1 : (256 + parts - 1) / parts;     // one workgroup per compute unit
-    if (splits > a.nstages) splits = a.nstages;
-    a.stages_per_block = (a.nstages + splits - 1) / splits;
-    a.splits = (a.nstages + a.stages_per_block - 1) / a.stages_per_block;
+    if (pl.lds < reduce_bytes) pl.lds = reduce_bytes;
+    if (pl.lds > 160 * 1024) return pl;
+    int splits = pl.parts >= 256 ? 1 : (256 + pl.parts - 1) / pl.parts;     // one workgroup per compute unit
+    if (splits > pl.nstages) splits = pl.nstages;
+    pl.stages_per_block = (pl.nstages + splits - 1) / splits;
+    pl.splits = (pl.nstages + pl.stages_per_block - 1) / pl.stages_per_block;
+    pl.covered = true;
+    return pl;
+}
+
+size_t wband_partial_bytes(const WbandPlan &pl) { return pl.covered ? (size_t)pl.parts * pl.splits * WB_SLOT_V4 * 16 : 0; }
+size_t wband_sums_bytes(const WbandPlan &pl) { return pl.covered ? (size_t)pl.parts * pl.splits * 2 * WB_SUMS * 4 : 0; }
+
+bool launch_wgrad_band(const hq_problem *p, const WbandPlan &pl, const WgradArgs &w, int32_t *partial, int32_t *sums,
+                       hipStream_t stream)
+{
+    WbandArgs a;
+    a.X = w.X; a.G = w.G; a.xq = w.xq; a.partial = partial; a.sums = sums;
+    a.B = p->B; a.H = p->H; a.W = p->W; a.C = p->C; a.N = p->Cout;
+    a.rows = pl.rows; a.nimg = pl.nimg;
+    a.bands_per_img = p->H / pl.rows;
+    a.nstages = pl.nstages; a.stages_per_block = pl.stages_per_block; a.splits = pl.splits;
+    a.cparts = p->C / 64; a.nparts = p->Cout / 64;
+    a.npix = pl.npix; a.npix_pad = pl.npix_pad;
+    a.prows = pl.prows; a.PW = p->W + 2;
+    a.xchunks = a.prows * a.PW * 4; a.gchunks = a.npix * 4;
+    a.buf_bytes = (unsigned)pl.buf_bytes;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_wgrad_band_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return false;
         configured = true;
     }
-    hipLaunchKernelGGL(hq_wgrad_band_kernel, dim3((unsigned)(parts * a.splits)), dim3(WB_THREADS), lds, stream, a);
+    hipLaunchKernelGGL(hq_wgrad_band_kernel, dim3((unsigned)(pl.parts * pl.splits)), dim3(WB_THREADS), pl.lds, stream, a);
     return true;
 }
 
 } // namespace
 
+// Workspace: [Cout][K] integer sums, [Cout] and [K] column sums, then the band kernel's partial sums.
 size_t hq_wgrad_workspace_bytes(const hq_problem *p)
 {
     const size_t K = (size_t)p->R * p->S * p->C;
     if (p->kind == HQ_DEPTHWISE) return align16(4 * K) + align16(4 * (size_t)p->C) + align16(4 * K);
-    return align16(4 * (size_t)p->Cout * K * wgrad_copies(p)) + align16(4 * (size_t)p->Cout) + align16(4 * K);
+    return align16(4 * (size_t)p->Cout * K) + align16(4 * (size_t)p->Cout) + align16(4 * K) +
+           wband_partial_bytes(wband_plan(p)) + wband_sums_bytes(wband_plan(p));
 }
 
 int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
@@ -623,27 +683,37 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     a.X = X; a.G = dY; a.xq = xq; a.gq = gq;
     char *w = static_cast<char *>(ws);
     a.acc = reinterpret_cast<int32_t *>(w);
-    const size_t acc_bytes = align16(4 * (size_t)p->Cout * K * wgrad_copies(p));
+    const size_t acc_bytes = align16(4 * (size_t)p->Cout * K);
     a.gsum = reinterpret_cast<int32_t *>(w + acc_bytes);
     a.xsum = reinterpret_cast<int32_t *>(w + acc_bytes + align16(4 * (size_t)p->Cout));
+    const size_t sums_bytes = acc_bytes + align16(4 * (size_t)p->Cout) + align16(4 * K);
     a.M = p->B * OH * OW; a.N = p->Cout; a.C = p->C;
     a.R = p->R; a.S = p->S; a.H = p->H; a.W = p->W; a.OH = OH; a.OW = OW; a.stride = p->stride; a.pad = p->pad;
     a.g16 = (a.N % 16) == 0; a.x16 = (a.C % 16) == 0;
 
-    auto finalize = [&](int copies) {
-        const size_t total = (size_t)a.N * K;
-        unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
-        hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb), dim3(256), 0, stream, a.acc, a.gsum, a.xsum, xq, gq,
-                           (unsigned)a.M, a.N, (int)K, 0, copies, dW, dW_acc);
-    };
-    const size_t ws_words = hq_wgrad_workspace_bytes(p) / 4;
-    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
-                       dim3(256), 0, stream, a.acc, ws_words);
-
-    if (launch_wgrad_band(p, a, stream)) {
-        finalize(wgrad_copies(p));
+    const WbandPlan pl = wband_plan(p);
+    if (pl.covered) {
+        // every workgroup stores its sums to a slot of its own: nothing to zero, no atomics
+        int32_t *partial = reinterpret_cast<int32_t *>(w + sums_bytes);
+        int32_t *sums = reinterpret_cast<int32_t *>(w + sums_bytes + wband_partial_bytes(pl));
+        if (!launch_wgrad_band(p, pl, a, partial, sums, stream)) return HQ_E_HIP;
+        const size_t quads = (size_t)a.N / 4 * K;              // multiple of 64 (C % 64 == 0)
+        const dim3 fgrid((unsigned)(quads / 64));
+        if (pl.splits >= 48)
+            hipLaunchKernelGGL(wband_finalize_kernel<16>, fgrid, dim3(1024), 0, stream, partial, sums, xq, gq,
+                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc);
+        else if (pl.splits >= 12)
+            hipLaunchKernelGGL(wband_finalize_kernel<4>, fgrid, dim3(256), 0, stream, partial, sums, xq, gq,
+                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc);
+        else
+            hipLaunchKernelGGL(wband_finalize_kernel<1>, fgrid, dim3(64), 0, stream, partial, sums, xq, gq,
+                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc);
         return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
     }
+
+    const size_t ws_words = sums_bytes / 4;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
+                       dim3(256), 0, stream, a.acc, ws_words);
 
     const bool big = a.N > 64 && a.C > 64;
     const int TN = big ? 128 : 64, TK = big ? 128 : 64;
@@ -661,6 +731,9 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128>), grid, dim3(HQ_THREADS), 0, stream, a);
     else     hipLaunchKernelGGL((hq_wgrad_kernel<64, 64>), grid, dim3(HQ_THREADS), 0, stream, a);
 
-    finalize(1);
+    const size_t total = (size_t)a.N * K;
+    unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
+    hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb), dim3(256), 0, stream, a.acc, a.gsum, a.xsum, xq, gq,
+                       (unsigned)a.M, a.N, (int)K, 0, dW, dW_acc);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }

@@ -70,6 +70,8 @@ SMALL = [
     wl.conv("band_1x1_c32", 2, 20, 32, 192, 1),      # three column chunks per tile
     wl.conv("band_1x1_c192", 2, 20, 192, 32, 1),
     wl.conv("band_multi_tile", 128, 36, 64, 64, 3),  # 4 bands per image of 9 rows: two tiles per band, second ragged
+    wl.conv("wband_14", 3, 14, 64, 64, 3),           # weight-gradient band = one whole image, 28 pixels of padding
+    wl.depthwise("dw_strips", 3, 40, 48),            # depthwise strips with a ragged last strip
 ]
 
 
@@ -105,7 +107,9 @@ def test_asymmetric_gradients_and_symmetric_inputs(H, hq):
     """Zero points on the gradient side (the paper quantizes gradients asymmetrically in its
     ablations, Sec. 5.1) and none on the input side."""
     for L in (wl.conv("asym_g", 2, 8, 16, 32, 3), wl.conv("asym_g_s2", 1, 9, 32, 16, 3, stride=2),
-              wl.depthwise("asym_dw", 2, 9, 24)):
+              wl.depthwise("asym_dw", 2, 9, 24),
+              wl.conv("asym_wband_img", 5, 7, 64, 128, 3),     # weight-gradient bands of 4 images, last one short
+              wl.conv("asym_wband_rows", 2, 20, 128, 64, 3)):  # bands of rows with pixels past the band's end
         X, W, dY = rand_layer_inputs(L, 77, x_asym=False, g_asym=True)
         assert dY.zero_point != 0 and X.zero_point == 0
         Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
