@@ -39,33 +39,27 @@ __device__ inline void stats_clear_wave(hq_stats *st)
 
 __global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats *st)
 {
-    __shared__ unsigned long long sh[128];
-    hq_stats_fold_wave(st, sh);
-    if (threadIdx.x == 0 && st->count != 0) {
-        const float gmin = __fmul_rn(st->acc_scale, (float)st->acc_min);
-        const float gmax = __fmul_rn(st->acc_scale, (float)st->acc_max);
-        ema_update(r, gmin, gmax);
+    const float acc_scale = st->acc_scale;
+    const unsigned long long count = st->count;
+    const HqStatsFolded f = hq_stats_fold_wave(st);
+    if (threadIdx.x == 0) {
+        if (count != 0) ema_update(r, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
+        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
+        st->clip_lo = 0; st->clip_hi = 0; st->count = 0;           // the partial records are already empty
     }
-    __syncthreads();
-    stats_clear_wave(st);
 }
 
 __global__ __launch_bounds__(64) void stats_reset_kernel(hq_stats *st) { stats_clear_wave(st + blockIdx.x); }
 
-__global__ __launch_bounds__(64) void stats_fold_kernel(hq_stats *st)
-{
-    __shared__ unsigned long long sh[128];
-    hq_stats_fold_wave(st + blockIdx.x, sh);
-}
+__global__ __launch_bounds__(64) void stats_fold_kernel(hq_stats *st) { hq_stats_fold_wave(st + blockIdx.x); }
 
 // Dynamic baseline, between the passes: the quantizer of the tensor just written.
 __global__ __launch_bounds__(64) void dynamic_mid_kernel(int mode, hq_range *r, hq_stats *st, hq_qparams *outq)
 {
-    __shared__ unsigned long long sh[128];
-    hq_stats_fold_wave(st, sh);
+    const HqStatsFolded f = hq_stats_fold_wave(st);
     if (threadIdx.x != 0) return;
-    const float gmin = __fmul_rn(st->acc_scale, (float)st->acc_min);
-    const float gmax = __fmul_rn(st->acc_scale, (float)st->acc_max);
+    const float gmin = __fmul_rn(st->acc_scale, (float)f.acc_min);
+    const float gmax = __fmul_rn(st->acc_scale, (float)f.acc_max);
     if (mode == HQ_DYN_RUNNING) {
         ema_update(r, gmin, gmax);                 // running min-max: this tensor moves the range first
         *outq = r->qp;

@@ -205,23 +205,34 @@ __device__ inline void hq_block_stats_commit(int mn, int mx, unsigned nlo, unsig
 }
 
 // Moves what the partial records hold into the record's leading fields and empties them.
-// One wavefront (HQ_STATS_PARTS == 64 lanes, lane = partial record); `sh` is LDS space for
-// 2 * 64 64-bit words.  The leading fields are complete for every lane after the call.
-__device__ inline void hq_stats_fold_wave(hq_stats *st, unsigned long long *sh)
+// One wavefront (HQ_STATS_PARTS == 64 lanes, lane = partial record), registers only.  Lane 0
+// writes the leading fields; every lane returns their new values.
+struct HqStatsFolded { int acc_min, acc_max; unsigned long long clip_lo, clip_hi; };
+
+__device__ inline unsigned long long hq_wave_sum64(unsigned long long v)
+{
+#pragma unroll
+    for (int k = 1; k < 64; k <<= 1) {
+        const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, k), hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), k);
+        v += ((unsigned long long)hi << 32) | lo;
+    }
+    return v;
+}
+
+__device__ inline HqStatsFolded hq_stats_fold_wave(hq_stats *st)
 {
     static_assert(HQ_STATS_PARTS == 64, "one lane per partial record");
     const int lane = threadIdx.x & 63;
     hq_stats_part *p = &st->part[lane];
-    const int mn = hq_wave_reduce(p->acc_min, HqMin()), mx = hq_wave_reduce(p->acc_max, HqMax());
-    sh[lane] = p->clip_lo; sh[64 + lane] = p->clip_hi;
+    const int pmn = p->acc_min, pmx = p->acc_max;
+    const unsigned long long plo = p->clip_lo, phi = p->clip_hi;
+    HqStatsFolded f;
+    f.acc_min = st->acc_min; f.acc_max = st->acc_max; f.clip_lo = st->clip_lo; f.clip_hi = st->clip_hi;
     p->acc_min = INT_MAX; p->acc_max = INT_MIN; p->clip_lo = 0; p->clip_hi = 0;
-    __syncthreads();
-    if (lane == 0) {
-        unsigned long long lo = 0, hi = 0;
-        for (int i = 0; i < 64; i++) { lo += sh[i]; hi += sh[64 + i]; }
-        st->acc_min = min(st->acc_min, mn); st->acc_max = max(st->acc_max, mx);
-        st->clip_lo += lo; st->clip_hi += hi;
-    }
-    __threadfence_block();
-    __syncthreads();
+    f.acc_min = min(f.acc_min, hq_wave_reduce(pmn, HqMin()));
+    f.acc_max = max(f.acc_max, hq_wave_reduce(pmx, HqMax()));
+    f.clip_lo += hq_wave_sum64(plo);
+    f.clip_hi += hq_wave_sum64(phi);
+    if (lane == 0) { st->acc_min = f.acc_min; st->acc_max = f.acc_max; st->clip_lo = f.clip_lo; st->clip_hi = f.clip_hi; }
+    return f;
 }

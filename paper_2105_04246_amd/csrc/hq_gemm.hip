@@ -40,8 +40,10 @@ struct GemmArgs {
     hq_stats *st;
     int M, N;                      // output rows (pixels) and columns (channels)
     int Cs;                        // reduced channels per tap
-    int cpt;                       // 16-byte chunks per tap = ceil(Cs / 16)
-    int nchunks;                   // taps * cpt
+    int cpt;                       // aligned: 16-byte chunks per tap = Cs / 16
+    int nchunks;                   // 16-byte chunks of the reduction: taps * cpt, or ceil(taps * Cs / 16)
+    int kcols;                     // taps * Cs
+    unsigned magic_Cs, magic_S;    // ceil(2^32 / d): x / d == umulhi(x, magic) for the small x used here
     int taps, S;
     int Hs, Ws;                    // spatial size of the gathered tensor A
     int Ho, Wo;                    // spatial size the row index m runs over
@@ -52,20 +54,8 @@ struct GemmArgs {
 
 __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
-template <bool ALIGNED> __device__ inline v4i load_chunk(const int8_t *p, int nbytes, int fill)
-{
-    if (ALIGNED) return *reinterpret_cast<const v4i *>(p);
-    v4i v;
-    const int *q = reinterpret_cast<const int *>(p);
-    v[0] = nbytes > 0 ? q[0] : fill;
-    v[1] = nbytes > 4 ? q[1] : fill;
-    v[2] = nbytes > 8 ? q[2] : fill;
-    v[3] = nbytes > 12 ? q[3] : fill;
-    return v;
-}
-
 // BKB: bytes of reduction per stage.  STRIDED: input gradient of a strided layer (gather with
-// exact-division test); otherwise the stencil form.  ALIGNED: Cs % 16 == 0.
+// exact-division test); otherwise the stencil form.  ALIGNED: Cs % 16 == 0 (16-byte loads, one tap per chunk).
 template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
 __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a)
 {
@@ -133,32 +123,77 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
     v4i areg0[AROWS], breg0[BROWS], areg1[AROWS], breg1[BROWS];
     auto load_stage = [&](v4i (&areg)[AROWS], v4i (&breg)[BROWS]) {
         const bool chunk_ok = chunk < a.nchunks;
-        const int coff = c16 * 16, nbytes = a.Cs - coff;
+        if (ALIGNED) {
+            const int coff = c16 * 16;
 #pragma unroll
-        for (int i = 0; i < AROWS; i++) {
-            int iy, ix;
-            bool ok = chunk_ok && arow_ok[i];
-            if (!STRIDED) {
-                iy = ay[i] + tr; ix = ax[i] + ts;
-            } else {
-                iy = ay[i] - tr; ix = ax[i] - ts;
-                ok = ok && iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
-                iy /= a.stride; ix /= a.stride;
+            for (int i = 0; i < AROWS; i++) {
+                int iy, ix;
+                bool ok = chunk_ok && arow_ok[i];
+                if (!STRIDED) {
+                    iy = ay[i] + tr; ix = ax[i] + ts;
+                } else {
+                    iy = ay[i] - tr; ix = ax[i] - ts;
+                    ok = ok && iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
+                    iy /= a.stride; ix /= a.stride;
+                }
+                ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
+                v4i v = {fill, fill, fill, fill};
+                if (ok) v = *reinterpret_cast<const v4i *>(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff);
+                areg[i] = v;
             }
-            ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
-            v4i v = {fill, fill, fill, fill};
-            if (ok) v = load_chunk<ALIGNED>(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff, nbytes, fill);
-            areg[i] = v;
-        }
-        const int wtap = a.flip ? a.taps - 1 - tap : tap;
+            const int wtap = a.flip ? a.taps - 1 - tap : tap;
 #pragma unroll
-        for (int i = 0; i < BROWS; i++) {
-            v4i v = {0, 0, 0, 0};
-            if (brow_ok[i] && chunk_ok) v = load_chunk<ALIGNED>(bbase[i] + (size_t)wtap * a.Cs + coff, nbytes, 0);
-            breg[i] = v;
+            for (int i = 0; i < BROWS; i++) {
+                v4i v = {0, 0, 0, 0};
+                if (brow_ok[i] && chunk_ok) v = *reinterpret_cast<const v4i *>(bbase[i] + (size_t)wtap * a.Cs + coff);
+                breg[i] = v;
+            }
+            chunk += CPS; c16 += CPS;
+            while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == a.S) { ts = 0; tr++; } }
+        } else {
+            // Channel counts that are not multiples of 16: the reduction runs over the (tap, channel)
+            // pairs as they lie in a weight row, 4 bytes at a time (a 4-byte word never straddles two
+            // taps because Cs % 4 == 0), so a tap costs Cs bytes of the reduction, not a padded 16.
+            int dr[4], ds[4], doff[4], dw[4];
+            bool dok[4];
+#pragma unroll
+            for (int d = 0; d < 4; d++) {
+                const int kc = chunk * 16 + 4 * d;
+                dok[d] = kc < a.kcols;
+                const int t = (int)__umulhi((unsigned)kc, a.magic_Cs), cx = kc - t * a.Cs;
+                dr[d] = (int)__umulhi((unsigned)t, a.magic_S); ds[d] = t - dr[d] * a.S;
+                doff[d] = cx;
+                dw[d] = (a.flip ? a.taps - 1 - t : t) * a.Cs + cx;
+            }
+#pragma unroll
+            for (int i = 0; i < AROWS; i++) {
+                v4i v = {fill, fill, fill, fill};
+#pragma unroll
+                for (int d = 0; d < 4; d++) {
+                    int iy, ix;
+                    bool ok = dok[d] && arow_ok[i];
+                    if (!STRIDED) {
+                        iy = ay[i] + dr[d]; ix = ax[i] + ds[d];
+                    } else {
+                        iy = ay[i] - dr[d]; ix = ax[i] - ds[d];
+                        ok = ok && iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
+                        iy /= a.stride; ix /= a.stride;
+                    }
+                    ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
+                    if (ok) v[d] = *reinterpret_cast<const int *>(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + doff[d]);
+                }
+                areg[i] = v;
+            }
+#pragma unroll
+            for (int i = 0; i < BROWS; i++) {
+                v4i v = {0, 0, 0, 0};
+#pragma unroll
+                for (int d = 0; d < 4; d++)
+                    if (brow_ok[i] && dok[d]) v[d] = *reinterpret_cast<const int *>(bbase[i] + dw[d]);
+                breg[i] = v;
+            }
+            chunk += CPS;
         }
-        chunk += CPS; c16 += CPS;
-        while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == a.S) { ts = 0; tr++; } }
     };
     auto store_stage = [&](int buf, const v4i (&areg)[AROWS], const v4i (&breg)[BROWS]) {
 #pragma unroll
@@ -346,9 +381,12 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
             strided = true; a.stride = p->stride; a.pad = p->pad; a.flip = 0;
         }
     }
-    a.cpt = (a.Cs + 15) / 16;
-    a.nchunks = a.taps * a.cpt;
     const bool aligned = (a.Cs % 16) == 0, fused = out32 == nullptr;
+    a.kcols = a.taps * a.Cs;
+    a.cpt = aligned ? a.Cs / 16 : 1;
+    a.nchunks = aligned ? a.taps * a.cpt : (a.kcols + 15) / 16;
+    a.magic_Cs = (unsigned)(((1ull << 32) + a.Cs - 1) / a.Cs);
+    a.magic_S = (unsigned)(((1ull << 32) + a.S - 1) / a.S);
     if (a.N > 64) {
         if (a.nchunks >= 16) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, fused, stream);
         return launch2<128, 128, 2, 2, 64>(a, strided, aligned, fused, stream);

@@ -63,7 +63,10 @@ template <int P> __device__ inline v4i read_frag_tr(const int8_t *tile, int lane
     return f;
 }
 
-template <int TN, int TK>
+// PACKED: layers with fewer than 16 input channels (a network's first layer).  The tile's columns
+// then run over (tap, channel) pairs as they lie in a row of G_W, so a 16-byte chunk of the staged
+// tile holds 16 / C taps (one 4-byte load each) instead of one tap padded with zeros.
+template <int TN, int TK, bool PACKED>
 __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 {
     constexpr int PG = TN + 32, PX = TK + 32;           // LDS pitches (32 mod 64: best for the transposing reads)
@@ -96,8 +99,9 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
         }
         bx = tile % a.xt; by = tile / a.xt; bz = split;
     }
-    const int tap = bx / a.ctiles, c0 = (bx % a.ctiles) * TK;
+    const int tap = PACKED ? 0 : bx / a.ctiles, c0 = PACKED ? bx * TK : (bx % a.ctiles) * TK;
     const int tr = tap / a.S, ts = tap % a.S;
+    const int kcols = a.R * a.S * a.C;            // PACKED: columns of the whole weight row
     const int n0 = by * TN;
     const int m_begin = bz * a.m_per_split;
     const int m_end = min(a.M, m_begin + a.m_per_split);
@@ -106,6 +110,22 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     const bool do_gsum = bx == 0 && wk == 0;     // column sums of G: first tile column
     const bool do_xsum = by == 0 && wn == 0;     // column sums of Xg: first tile row
 
+    int pk_r[4], pk_s[4], pk_off[4], pk_ow[XLD], pk_oh[XLD], pk_b[XLD];
+    if (PACKED) {
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            const int kc = c0 + (tid % XCH) * 16 + 4 * d;
+            const int t = kc / a.C, cc = kc - t * a.C;
+            pk_r[d] = kc < kcols ? t / a.S : -1;
+            pk_s[d] = t % a.S;
+            pk_off[d] = (pk_r[d] * a.W + pk_s[d]) * a.C + cc;
+        }
+#pragma unroll
+        for (int i = 0; i < XLD; i++) {
+            const int m = m_begin + (tid + i * HQ_THREADS) / XCH;
+            pk_ow[i] = m % a.OW; pk_oh[i] = (m / a.OW) % a.OH; pk_b[i] = m / (a.OW * a.OH);
+        }
+    }
     v4i greg[GLD], xreg[XLD];
     auto load_stage = [&](int mb) {
 #pragma unroll
@@ -121,7 +141,24 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
             const int idx = tid + i * HQ_THREADS, row = idx / XCH, col = (idx % XCH) * 16;
             const int m = mb + row, c = c0 + col;
             v4i v = {0, 0, 0, 0};
-            if (m < m_end && c < a.C) {
+            if (PACKED) {
+                // the thread's four (tap, channel) columns never change; its pixels advance by MB per stage
+                if (m < m_end) {
+                    const int iy0 = pk_oh[i] * a.stride - a.pad, ix0 = pk_ow[i] * a.stride - a.pad;
+                    const int8_t *base = a.X + (((size_t)pk_b[i] * a.H + iy0) * a.W + ix0) * a.C;
+#pragma unroll
+                    for (int d = 0; d < 4; d++) {
+                        if (pk_r[d] >= 0) {
+                            const int iy = iy0 + pk_r[d], ix = ix0 + pk_s[d];
+                            v[d] = (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W)
+                                       ? *reinterpret_cast<const int *>(base + pk_off[d]) : fill;
+                        }
+                    }
+                }
+                pk_ow[i] += MB;
+                while (pk_ow[i] >= a.OW) { pk_ow[i] -= a.OW; pk_oh[i]++; }
+                while (pk_oh[i] >= a.OH) { pk_oh[i] -= a.OH; pk_b[i]++; }
+            } else if (m < m_end && c < a.C) {
                 const int ow = m % a.OW, oh = (m / a.OW) % a.OH, b = m / (a.OW * a.OH);
                 const int iy = oh * a.stride - a.pad + tr, ix = ow * a.stride - a.pad + ts;
                 if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) {
@@ -210,7 +247,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 #pragma unroll
         for (int j = 0; j < KT; j++) {
             const int c = c0 + wk * WTK + j * 32 + (lane & 31);
-            if (c >= a.C) continue;
+            if (c >= (PACKED ? kcols : a.C)) continue;
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const int n = n0 + wn * WTN + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -230,7 +267,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
         for (int j = 0; j < KT; j++) {
             int s = xs[j] + __shfl_xor(xs[j], 32);
             const int c = c0 + wk * WTK + j * 32 + (lane & 31);
-            if (lane < 32 && c < a.C && s != 0) atomicAdd(a.xsum + (size_t)tap * a.C + c, s);
+            if (lane < 32 && c < (PACKED ? kcols : a.C) && s != 0) atomicAdd(a.xsum + (size_t)tap * a.C + c, s);
         }
     }
 }
@@ -715,10 +752,10 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
                        dim3(256), 0, stream, a.acc, ws_words);
 
-    const bool big = a.N > 64 && a.C > 64;
-    const int TN = big ? 128 : 64, TK = big ? 128 : 64;
+    const bool big = a.N > 64 && a.C > 64, packed = a.C < 16;
+    const int TN = big ? 128 : 64, TK = packed ? 256 : big ? 128 : 64;
     a.ctiles = (a.C + TK - 1) / TK;
-    const int xt = p->R * p->S * a.ctiles, yt = (a.N + TN - 1) / TN;
+    const int xt = packed ? (int)((K + TK - 1) / TK) : p->R * p->S * a.ctiles, yt = (a.N + TN - 1) / TN;
     const int stages_total = (a.M + MB - 1) / MB;
     int splits = (2048 + xt * yt - 1) / (xt * yt);          // aim at ~8 workgroups per CU
     if (splits > stages_total) splits = stages_total;
@@ -728,8 +765,9 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     splits = (stages_total + stages_per - 1) / stages_per;
     a.xt = xt; a.yt = yt; a.splits = splits;
     dim3 grid((unsigned)(xt * yt * splits));
-    if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128>), grid, dim3(HQ_THREADS), 0, stream, a);
-    else     hipLaunchKernelGGL((hq_wgrad_kernel<64, 64>), grid, dim3(HQ_THREADS), 0, stream, a);
+    if (packed)   hipLaunchKernelGGL((hq_wgrad_kernel<64, 256, true>), grid, dim3(HQ_THREADS), 0, stream, a);
+    else if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128, false>), grid, dim3(HQ_THREADS), 0, stream, a);
+    else          hipLaunchKernelGGL((hq_wgrad_kernel<64, 64, false>), grid, dim3(HQ_THREADS), 0, stream, a);
 
     const size_t total = (size_t)a.N * K;
     unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
