@@ -7,7 +7,12 @@
 //   forward:            m = output pixel, A = X,  pix = (oh*stride - pad + r, ow*stride - pad + s)
 //   dgrad, stride 1:    the same stencil over dY with padding R-1-pad and mirrored taps
 //   dgrad, stride > 1:  m = input pixel, A = dY, pix = ((h + pad - r)/stride, (w + pad - s)/stride)
-//                       where the division is exact and lands inside the output image
+//                       where the division is exact and lands inside the output image.  With
+//                       16-byte-aligned channel counts the input pixels are split into the
+//                       stride^2 classes (h % stride, w % stride): inside a class only the taps
+//                       r = r0 + stride*jr, s = s0 + stride*js ever divide exactly, and the class
+//                       is a stride-1 stencil over dY with those taps.  A tile holds pixels of one
+//                       class and reduces over that class's taps only.
 // Taps without a source pixel are filled with A's zero-point code (real zero), so the zero
 // point leaves the sum as one term per output column, z_a * bsum[n].
 //
@@ -50,6 +55,9 @@ struct GemmArgs {
     int stride, pad;               // stencil form: effective stride / padding
     int flip;                      // weight taps mirrored (dgrad written as a stencil)
     int m_tiles, n_tiles;
+    int Bn;                        // images (class form)
+    int ncls;                      // class form: stride * stride classes, 0 otherwise
+    int cls_tile0[17];             // first row tile of each class (prefix sums), [ncls] = m_tiles
 };
 
 __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
@@ -84,13 +92,57 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
         const int total = a.m_tiles * a.n_tiles, per = total / 8;
         if (per > 0 && tile < per * 8) tile = (tile & 7) * per + (tile >> 3);
     }
-    const int tile_m = tile / a.n_tiles, tile_n = tile - tile_m * a.n_tiles;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    int tile_m = tile / a.n_tiles;
+    const int tile_n = tile - tile_m * a.n_tiles;
+    const int n0 = tile_n * BN;
+
+    // class form (strided input gradient): the tile's class and that class's stencil
+    constexpr bool CLASSED = STRIDED && ALIGNED;
+    int Hc = a.Ho, Wc = a.Wo, Mrows = a.M, ph = 0, pw = 0, r0 = 0, s0 = 0, nr = 0, ns = 1, dh = 0, dw = 0;
+    int nchunks = a.nchunks;
+    if (CLASSED) {
+        int cls = 0;
+        while (cls + 1 < a.ncls && tile_m >= a.cls_tile0[cls + 1]) cls++;
+        tile_m -= a.cls_tile0[cls];
+        ph = cls / a.stride; pw = cls - ph * a.stride;
+        Hc = (a.Ho - ph + a.stride - 1) / a.stride; Wc = (a.Wo - pw + a.stride - 1) / a.stride;
+        Mrows = a.Bn * Hc * Wc;
+        r0 = (ph + a.pad) % a.stride; s0 = (pw + a.pad) % a.stride;
+        const int R = a.taps / a.S;
+        nr = r0 < R ? (R - r0 + a.stride - 1) / a.stride : 0;
+        ns = s0 < a.S ? (a.S - s0 + a.stride - 1) / a.stride : 0;
+        dh = (ph + a.pad - r0) / a.stride; dw = (pw + a.pad - s0) / a.stride;
+        nchunks = nr * ns * a.cpt;
+        if (ns == 0) ns = 1;                       // no taps at all: nchunks == 0, nothing is decoded
+    }
+    const int m0 = tile_m * BM;
 
     const int za = a.aq->zero_point;
     const int fill = (za & 0xff) * 0x01010101;
 
-    if (tid < BN) bzs[tid] = (n0 + tid < a.N) ? za * a.bsum[n0 + tid] : 0;   // visible after the first barrier
+    // z_a * (sum of the weights the reduction runs over), visible after the first barrier
+    if (tid < BN) {
+        int bz = 0;
+        const int n = n0 + tid;
+        if (n < a.N) {
+            if (!CLASSED) {
+                bz = za * a.bsum[n];
+            } else if (za != 0) {
+                int sum = 0;
+                for (int jr = 0; jr < nr; jr++)
+                    for (int js = 0; js * a.stride + s0 < a.S; js++) {
+                        const int8_t *w = a.Bw + ((size_t)n * a.taps + (r0 + a.stride * jr) * a.S + s0 + a.stride * js) * a.Cs;
+                        for (int k = 0; k < a.Cs; k += 16) {
+                            const v4i v = *reinterpret_cast<const v4i *>(w + k);
+#pragma unroll
+                            for (int d = 0; d < 4; d++) sum = __builtin_amdgcn_sdot4(v[d], 0x01010101, sum, false);
+                        }
+                    }
+                bz = za * sum;
+            }
+        }
+        bzs[tid] = bz;
+    }
 
     // ---- per-thread gather state
     const int cc = tid % CPS, lrow = tid / CPS;
@@ -100,12 +152,12 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
 #pragma unroll
     for (int i = 0; i < AROWS; i++) {
         const int m = m0 + lrow + RPP * i;
-        arow_ok[i] = m < a.M;
+        arow_ok[i] = m < Mrows;
         const int mm = arow_ok[i] ? m : 0;
-        const int x = mm % a.Wo, y = (mm / a.Wo) % a.Ho, b = mm / (a.Wo * a.Ho);
+        const int x = mm % Wc, y = (mm / Wc) % Hc, b = mm / (Wc * Hc);
         abase[i] = a.A + (size_t)b * a.Hs * a.Ws * a.Cs;
-        ay[i] = STRIDED ? y + a.pad : y * a.stride - a.pad;
-        ax[i] = STRIDED ? x + a.pad : x * a.stride - a.pad;
+        ay[i] = CLASSED ? y + dh : STRIDED ? y + a.pad : y * a.stride - a.pad;
+        ax[i] = CLASSED ? x + dw : STRIDED ? x + a.pad : x * a.stride - a.pad;
     }
     const int8_t *bbase[BROWS];
     bool brow_ok[BROWS];
@@ -118,18 +170,21 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
         bbase[i] = a.Bw + (size_t)(brow_ok[i] ? n : 0) * brow_len;
     }
     int chunk = cc, c16 = cc % a.cpt, tap = cc / a.cpt;
-    int tr = tap / a.S, ts = tap - tr * a.S;
+    const int tapw = CLASSED ? ns : a.S;             // taps per row of the tap grid the chunks run over
+    int tr = tap / tapw, ts = tap - tr * tapw;
 
     v4i areg0[AROWS], breg0[BROWS], areg1[AROWS], breg1[BROWS];
     auto load_stage = [&](v4i (&areg)[AROWS], v4i (&breg)[BROWS]) {
-        const bool chunk_ok = chunk < a.nchunks;
+        const bool chunk_ok = chunk < nchunks;
         if (ALIGNED) {
             const int coff = c16 * 16;
 #pragma unroll
             for (int i = 0; i < AROWS; i++) {
                 int iy, ix;
                 bool ok = chunk_ok && arow_ok[i];
-                if (!STRIDED) {
+                if (CLASSED) {
+                    iy = ay[i] - tr; ix = ax[i] - ts;
+                } else if (!STRIDED) {
                     iy = ay[i] + tr; ix = ax[i] + ts;
                 } else {
                     iy = ay[i] - tr; ix = ax[i] - ts;
@@ -141,7 +196,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
                 if (ok) v = *reinterpret_cast<const v4i *>(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff);
                 areg[i] = v;
             }
-            const int wtap = a.flip ? a.taps - 1 - tap : tap;
+            const int wtap = CLASSED ? (r0 + a.stride * tr) * a.S + s0 + a.stride * ts : a.flip ? a.taps - 1 - tap : tap;
 #pragma unroll
             for (int i = 0; i < BROWS; i++) {
                 v4i v = {0, 0, 0, 0};
@@ -149,7 +204,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
                 breg[i] = v;
             }
             chunk += CPS; c16 += CPS;
-            while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == a.S) { ts = 0; tr++; } }
+            while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == tapw) { ts = 0; tr++; } }
         } else {
             // Channel counts that are not multiples of 16: the reduction runs over the (tap, channel)
             // pairs as they lie in a weight row, 4 bytes at a time (a 4-byte word never straddles two
@@ -210,7 +265,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
     // K loop.  Two LDS buffers and two register sets: while stage kt is multiplied from LDS, the
     // global loads of stage kt+2 are in flight and stage kt+1 waits in registers, so a load has
     // two stages of MFMA work to hide behind.
-    const int KT = (a.nchunks + CPS - 1) / CPS;
+    const int KT = (nchunks + CPS - 1) / CPS;
     const int frag_off = (lane & 31) * PITCH + (lane >> 5) * 16;
     auto compute = [&](int buf) {
         const int8_t *Ab = As + (buf * BM + wm * WTM) * PITCH + frag_off;
@@ -271,8 +326,12 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
         constexpr bool FULL = decltype(full)::value;
 #pragma unroll
         for (int i = 0; i < MT; i++) {
-            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
-            if (m >= a.M) continue;
+            int m = m0 + wm * WTM + i * 32 + (lane & 31);
+            if (m >= Mrows) continue;
+            if (CLASSED) {                                  // row inside the class -> input pixel
+                const int x = m % Wc, y = (m / Wc) % Hc, b = m / (Wc * Hc);
+                m = (b * a.Ho + ph + a.stride * y) * a.Wo + pw + a.stride * x;
+            }
 #pragma unroll
             for (int j = 0; j < NT; j++) {
                 const int nb = n0 + wn * WTN + j * 32 + 16 * (lane >> 5);
@@ -326,6 +385,19 @@ int launch3(GemmArgs &a, hipStream_t s)
 {
     a.m_tiles = (a.M + BM - 1) / BM;
     a.n_tiles = (a.N + BN - 1) / BN;
+    a.ncls = 0;
+    if (STRIDED && ALIGNED) {
+        a.ncls = a.stride * a.stride;
+        int t = 0;
+        for (int c = 0; c < a.ncls; c++) {
+            const int ph = c / a.stride, pw = c % a.stride;
+            const int Hc = (a.Ho - ph + a.stride - 1) / a.stride, Wc = (a.Wo - pw + a.stride - 1) / a.stride;
+            a.cls_tile0[c] = t;
+            t += (a.Bn * Hc * Wc + BM - 1) / BM;
+        }
+        a.cls_tile0[a.ncls] = t;
+        a.m_tiles = t;
+    }
     const size_t lds = 2 * (size_t)(BM + BN) * (BKB + 16) + 4 * BN + 64;
     auto kern = hq_gemm_kernel<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, FUSED>;
     static bool configured = false;
@@ -366,7 +438,7 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
     GemmArgs a;
     a.A = A; a.Bw = Bw; a.bsum = bsum; a.aq = aq; a.bq = bq; a.range = range;
     a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
-    a.taps = p->R * p->S; a.S = p->S;
+    a.taps = p->R * p->S; a.S = p->S; a.Bn = p->B;
     bool strided = false;
     if (!dgrad) {
         a.M = p->B * OH * OW; a.N = p->Cout; a.Cs = p->C;
@@ -381,7 +453,8 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
             strided = true; a.stride = p->stride; a.pad = p->pad; a.flip = 0;
         }
     }
-    const bool aligned = (a.Cs % 16) == 0, fused = out32 == nullptr;
+    // (the class form of the strided input gradient keeps at most 16 classes: larger strides take the 4-byte path)
+    const bool aligned = (a.Cs % 16) == 0 && !(strided && a.stride > 4), fused = out32 == nullptr;
     a.kcols = a.taps * a.Cs;
     a.cpt = aligned ? a.Cs / 16 : 1;
     a.nchunks = aligned ? a.taps * a.cpt : (a.kcols + 15) / 16;
