@@ -65,7 +65,7 @@ __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4
 // BKB: bytes of reduction per stage.  STRIDED: input gradient of a strided layer (gather with
 // exact-division test); otherwise the stencil form.  ALIGNED: Cs % 16 == 0 (16-byte loads, one tap per chunk).
 template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
-__global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a)
+__global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 : 2)) void hq_gemm_kernel(const GemmArgs a)
 {
     static_assert(WGM * WGN == HQ_THREADS / 64, "four wavefronts");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
     constexpr int CPS = BKB / 16;                       // 16-byte chunks per row and stage
     constexpr int RPP = HQ_THREADS / CPS;               // rows covered by one pass of the loader
     constexpr int AROWS = BM / RPP, BROWS = (BN + RPP - 1) / RPP;
-    constexpr int PITCH = BKB + 16;
+    constexpr int PITCH = ALIGNED ? BKB : BKB + 16;     // aligned: dense rows, 16-byte chunks XOR-swizzled
     constexpr int KS = BKB / 32;
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
@@ -169,43 +169,61 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
         brow_ok[i] = row < BN && n < a.N;
         bbase[i] = a.Bw + (size_t)(brow_ok[i] ? n : 0) * brow_len;
     }
-    int chunk = cc, c16 = cc % a.cpt, tap = cc / a.cpt;
+    // Aligned form: rows are dense in LDS and the 16-byte chunks of a row are XOR-swizzled by the row
+    // index, which keeps the fragment reads free of bank conflicts without padding.  The LDS slot of
+    // a thread is fixed (slot = thread: that is where a direct-to-LDS load of lane l lands), so the
+    // swizzle is applied to the chunk the thread fetches instead.
+    auto swz = [](int row) { return CPS == 8 ? (row & 7) : ((row >> 1) & (CPS - 1)); };
+    const int csrc = ALIGNED ? (cc ^ swz(lrow)) : cc;
+    int chunk = csrc, c16 = csrc % a.cpt, tap = csrc / a.cpt;
     const int tapw = CLASSED ? ns : a.S;             // taps per row of the tap grid the chunks run over
     int tr = tap / tapw, ts = tap - tr * tapw;
 
+
+    // Aligned form: global -> LDS without passing through registers (global_load_lds_dwordx4: lane l
+    // of a wavefront writes 16 bytes at base + 16 * l).  Lanes without a source (padding taps, rows
+    // past the end, chunks past the end of K) store the fill value themselves.
+    auto issue_stage = [&](int buf) {
+        const bool chunk_ok = chunk < nchunks;
+        const int coff = c16 * 16;
+        const v4i fillv = {fill, fill, fill, fill}, zerov = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < AROWS; i++) {
+            int iy, ix;
+            bool ok = chunk_ok && arow_ok[i];
+            if (CLASSED) { iy = ay[i] - tr; ix = ax[i] - ts; }
+            else { iy = ay[i] + tr; ix = ax[i] + ts; }
+            ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
+            int8_t *dst = As + (size_t)buf * BM * BKB + 4096 * i + (tid & ~63) * 16;      // this wavefront's 1 KiB
+            if (ok) {
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff),
+                    (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+            } else {
+                *reinterpret_cast<v4i *>(dst + lane * 16) = fillv;
+            }
+        }
+        const int wtap = CLASSED ? (r0 + a.stride * tr) * a.S + s0 + a.stride * ts : a.flip ? a.taps - 1 - tap : tap;
+#pragma unroll
+        for (int i = 0; i < BROWS; i++) {
+            if (lrow + RPP * i < BN) {
+                int8_t *dst = Bs + (size_t)buf * BN * BKB + 4096 * i + (tid & ~63) * 16;
+                if (brow_ok[i] && chunk_ok) {
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(bbase[i] + (size_t)wtap * a.Cs + coff),
+                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+                } else {
+                    *reinterpret_cast<v4i *>(dst + lane * 16) = zerov;
+                }
+            }
+        }
+        chunk += CPS; c16 += CPS;
+        while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == tapw) { ts = 0; tr++; } }
+    };
+
     v4i areg0[AROWS], breg0[BROWS], areg1[AROWS], breg1[BROWS];
     auto load_stage = [&](v4i (&areg)[AROWS], v4i (&breg)[BROWS]) {
-        const bool chunk_ok = chunk < nchunks;
-        if (ALIGNED) {
-            const int coff = c16 * 16;
-#pragma unroll
-            for (int i = 0; i < AROWS; i++) {
-                int iy, ix;
-                bool ok = chunk_ok && arow_ok[i];
-                if (CLASSED) {
-                    iy = ay[i] - tr; ix = ax[i] - ts;
-                } else if (!STRIDED) {
-                    iy = ay[i] + tr; ix = ax[i] + ts;
-                } else {
-                    iy = ay[i] - tr; ix = ax[i] - ts;
-                    ok = ok && iy >= 0 && ix >= 0 && (iy % a.stride == 0) && (ix % a.stride == 0);
-                    iy /= a.stride; ix /= a.stride;
-                }
-                ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
-                v4i v = {fill, fill, fill, fill};
-                if (ok) v = *reinterpret_cast<const v4i *>(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff);
-                areg[i] = v;
-            }
-            const int wtap = CLASSED ? (r0 + a.stride * tr) * a.S + s0 + a.stride * ts : a.flip ? a.taps - 1 - tap : tap;
-#pragma unroll
-            for (int i = 0; i < BROWS; i++) {
-                v4i v = {0, 0, 0, 0};
-                if (brow_ok[i] && chunk_ok) v = *reinterpret_cast<const v4i *>(bbase[i] + (size_t)wtap * a.Cs + coff);
-                breg[i] = v;
-            }
-            chunk += CPS; c16 += CPS;
-            while (c16 >= a.cpt) { c16 -= a.cpt; tap++; ts++; if (ts == tapw) { ts = 0; tr++; } }
-        } else {
+        {
             // Channel counts that are not multiples of 16: the reduction runs over the (tap, channel)
             // pairs as they lie in a weight row, 4 bytes at a time (a 4-byte word never straddles two
             // taps because Cs % 4 == 0), so a tap costs Cs bytes of the reduction, not a padded 16.
@@ -266,17 +284,20 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
     // global loads of stage kt+2 are in flight and stage kt+1 waits in registers, so a load has
     // two stages of MFMA work to hide behind.
     const int KT = (nchunks + CPS - 1) / CPS;
-    const int frag_off = (lane & 31) * PITCH + (lane >> 5) * 16;
+    int frag_off[KS];                                     // lane's 16 bytes of k-step ks inside its row block
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+        frag_off[ks] = (lane & 31) * PITCH + 16 * (ALIGNED ? ((2 * ks + (lane >> 5)) ^ swz(lane & 31)) : 2 * ks + (lane >> 5));
     auto compute = [&](int buf) {
-        const int8_t *Ab = As + (buf * BM + wm * WTM) * PITCH + frag_off;
-        const int8_t *Bb = Bs + (buf * BN + wn * WTN) * PITCH + frag_off;
+        const int8_t *Ab = As + (buf * BM + wm * WTM) * PITCH;
+        const int8_t *Bb = Bs + (buf * BN + wn * WTN) * PITCH;
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {                 // chunks past the end of K hold zero weights
             v4i wf[NT], af[MT];
 #pragma unroll
-            for (int j = 0; j < NT; j++) wf[j] = *reinterpret_cast<const v4i *>(Bb + j * 32 * PITCH + ks * 32);
+            for (int j = 0; j < NT; j++) wf[j] = *reinterpret_cast<const v4i *>(Bb + j * 32 * PITCH + frag_off[ks]);
 #pragma unroll
-            for (int i = 0; i < MT; i++) af[i] = *reinterpret_cast<const v4i *>(Ab + i * 32 * PITCH + ks * 32);
+            for (int i = 0; i < MT; i++) af[i] = *reinterpret_cast<const v4i *>(Ab + i * 32 * PITCH + frag_off[ks]);
 #pragma unroll
             for (int i = 0; i < MT; i++)
 #pragma unroll
@@ -284,9 +305,14 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
         }
     };
-    load_stage(areg0, breg0);
-    store_stage(0, areg0, breg0);
-    if (KT > 1) load_stage(areg1, breg1);
+    if constexpr (ALIGNED) {
+        issue_stage(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        load_stage(areg0, breg0);
+        store_stage(0, areg0, breg0);
+        if (KT > 1) load_stage(areg1, breg1);
+    }
     __syncthreads();
     // the accumulators start at -z_a * bsum[n]: the zero-point term of the sum is gone before
     // the epilogue looks at them (lane = 16 consecutive channels of column block j)
@@ -302,16 +328,26 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_gemm_kernel(const GemmArgs a
                 for (int e = 0; e < 4; e++) acc[i][j][4 * g + e] = -bz[e];
         }
     }
-    for (int kt = 0; kt < KT; kt += 2) {
-        if (kt + 2 < KT) load_stage(areg0, breg0);        // stage kt+2
-        compute(0);
-        if (kt + 1 < KT) store_stage(1, areg1, breg1);    // stage kt+1
-        __syncthreads();
-        if (kt + 1 < KT) {
-            if (kt + 3 < KT) load_stage(areg1, breg1);    // stage kt+3
-            compute(1);
-            if (kt + 2 < KT) store_stage(0, areg0, breg0);
+    if constexpr (ALIGNED) {
+        // stage kt+1 lands in the other buffer while stage kt is multiplied
+        for (int kt = 0; kt < KT; kt++) {
+            if (kt + 1 < KT) issue_stage((kt + 1) & 1);
+            compute(kt & 1);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
+        }
+    } else {
+        for (int kt = 0; kt < KT; kt += 2) {
+            if (kt + 2 < KT) load_stage(areg0, breg0);        // stage kt+2
+            compute(0);
+            if (kt + 1 < KT) store_stage(1, areg1, breg1);    // stage kt+1
+            __syncthreads();
+            if (kt + 1 < KT) {
+                if (kt + 3 < KT) load_stage(areg1, breg1);    // stage kt+3
+                compute(1);
+                if (kt + 2 < KT) store_stage(0, areg0, breg0);
+                __syncthreads();
+            }
         }
     }
 
@@ -398,7 +434,7 @@ int launch3(GemmArgs &a, hipStream_t s)
         a.cls_tile0[a.ncls] = t;
         a.m_tiles = t;
     }
-    const size_t lds = 2 * (size_t)(BM + BN) * (BKB + 16) + 4 * BN + 64;
+    const size_t lds = 2 * (size_t)(BM + BN) * (ALIGNED ? BKB : BKB + 16) + 4 * BN + 64;
     auto kern = hq_gemm_kernel<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, FUSED>;
     static bool configured = false;
     if (!configured) {
@@ -461,7 +497,11 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
     a.magic_Cs = (unsigned)(((1ull << 32) + a.Cs - 1) / a.Cs);
     a.magic_S = (unsigned)(((1ull << 32) + a.S - 1) / a.S);
     if (a.N > 64) {
-        if (a.nchunks >= 16) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, fused, stream);
+        // 128-byte stages halve the barriers per tile; with enough tiles to keep three or more
+        // workgroups on every compute unit, 64-byte stages (half the LDS, four resident workgroups)
+        // hide more latency instead
+        const long tiles = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+        if (a.nchunks >= 16 && !(aligned && tiles >= 3 * 256)) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, fused, stream);
         return launch2<128, 128, 2, 2, 64>(a, strided, aligned, fused, stream);
     }
     if (a.N > 32) return launch2<256, 64, 4, 1, 64>(a, strided, aligned, fused, stream);
