@@ -252,8 +252,8 @@ def main():
     value = step_ops / (wall_ms * 1e-3) / 1e12
 
     # ---- roofline of the dominant kernel: the slowest of the three GEMM launches ------------
-    names = {"fwd": "hq_gemm_kernel<256,64,4,1> (forward)", "dgrad": "hq_gemm_kernel<256,64,4,1> (dgrad)",
-             "wgrad": "hq_wgrad_kernel (+zero, finalize)"}
+    names = {"fwd": "hq_band_kernel<64,3,2,8,1,fused> (forward)", "dgrad": "hq_band_kernel<64,3,2,8,1,fused> (dgrad)",
+             "wgrad": "hq_wgrad_band_kernel + wband_finalize_kernel (one hq_gemm_wgrad call)"}
     dom = max(("fwd", "dgrad", "wgrad"), key=lambda n: per_call[n])
     achieved = ops_gemm / (per_call[dom] * 1e-3) / 1e12
     roofline = {"kernel": names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",

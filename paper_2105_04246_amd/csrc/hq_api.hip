@@ -39,11 +39,16 @@ __device__ inline void stats_clear_wave(hq_stats *st)
 
 __global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats *st)
 {
+    // every load of the kernel is issued before anything waits: one memory round trip
+    hq_range rr = *r;
     const float acc_scale = st->acc_scale;
     const unsigned long long count = st->count;
     const HqStatsFolded f = hq_stats_fold_wave(st);
     if (threadIdx.x == 0) {
-        if (count != 0) ema_update(r, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
+        if (count != 0) {
+            ema_update(&rr, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
+            *r = rr;
+        }
         st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
         st->clip_lo = 0; st->clip_hi = 0; st->count = 0;           // the partial records are already empty
     }
@@ -112,12 +117,21 @@ __global__ void weight_rowsum_kernel(const int8_t *W, int rows, int len, int32_t
 
 __global__ void weight_colsum_kernel(const int8_t *W, int rows, int taps, int C, int32_t *sum)
 {
-    // sum over (row, tap) for each channel c of W[rows][taps][C]
-    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    // sum over (row, tap) for each channel c of W[rows][taps][C]: a workgroup takes a slab of 64
+    // (row, tap) lines, a thread one channel of it; the slabs meet with one atomic per channel
+    // (sum is zeroed before the launch)
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
+    const int lines = rows * taps, l0 = blockIdx.y * 64, l1 = min(lines, l0 + 64);
     int s = 0;
-    for (int i = 0; i < rows * taps; i++) s += W[(size_t)i * C + c];
-    sum[c] = s;
+    for (int i = l0; i < l1; i++) s += W[(size_t)i * C + c];
+    if (s != 0) atomicAdd(sum + c, s);
+}
+
+__global__ void zero_words_kernel(int32_t *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 __global__ void weight_relayout_kernel(const int8_t *W, int Cout, int taps, int C, int8_t *Wd)
@@ -285,13 +299,18 @@ int hq_weight_prepare(const hq_problem *p, const int8_t *W, int8_t *Wd, int32_t 
     if (!W) return HQ_E_BADARG;
     hipStream_t s = as_stream(stream);
     const int taps = p->R * p->S;
+    auto colsum = [&](int rows, int32_t *sum) {
+        hipLaunchKernelGGL(zero_words_kernel, dim3((p->C + 255) / 256), dim3(256), 0, s, sum, p->C);
+        hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64, (rows * taps + 63) / 64), dim3(64), 0, s,
+                           W, rows, taps, p->C, sum);
+    };
     if (p->kind == HQ_DEPTHWISE) {
-        if (wsum) hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64), dim3(64), 0, s, W, 1, taps, p->C, wsum);
-        if (wdsum) hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64), dim3(64), 0, s, W, 1, taps, p->C, wdsum);
+        if (wsum) colsum(1, wsum);
+        if (wdsum) colsum(1, wdsum);
         return launch_status();
     }
     if (wsum) hipLaunchKernelGGL(weight_rowsum_kernel, dim3((p->Cout + 3) / 4), dim3(256), 0, s, W, p->Cout, taps * p->C, wsum);
-    if (wdsum) hipLaunchKernelGGL(weight_colsum_kernel, dim3((p->C + 63) / 64), dim3(64), 0, s, W, p->Cout, taps, p->C, wdsum);
+    if (wdsum) colsum(p->Cout, wdsum);
     if (Wd) hipLaunchKernelGGL(weight_relayout_kernel, dim3(1024), dim3(256), 0, s, W, p->Cout, taps, p->C, Wd);
     return launch_status();
 }

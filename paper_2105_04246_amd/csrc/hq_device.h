@@ -66,11 +66,9 @@ __device__ inline int hq_requant(int c, const HqRequant &q, unsigned &nlo, unsig
 // Fused epilogue of the MFMA kernels: a lane's zero-point-corrected accumulators -> codes,
 // with min / max and exact clip counts folded in (Sec. 4, steps 1 and 2).
 // Per value: convert, multiply, round (the requantization of the static quantizer), add the
-// zero point, pack.  Clipped values are counted from the rounded floats with lane-mask
-// compares whose popcounts accumulate on the scalar unit, and only in groups whose extreme
-// accumulators clip: requantization is monotone in the accumulator, so the extremes decide
-// for the whole group.  A wavefront's counts are added to the counters of the first lane that
-// is active in the call, so the sum of a counter over all lanes is the total.
+// zero point, pack.  Clipped values are counted per lane from the rounded floats, and only in
+// groups whose extreme accumulators clip: requantization is monotone in the accumulator, so
+// the extremes decide for the whole group.
 // ---------------------------------------------------------------------------------------
 struct HqEpilogue {
     float mult;          // (s_a * s_b) / s_out
@@ -107,14 +105,15 @@ __device__ inline void hq_requant_group(const int *c, const HqEpilogue &ep, int 
 #pragma unroll
     for (int e = 0; e < N; e++) f[e] = hq_round_scaled(c[e], ep.mult);
     if (__any(hq_round_scaled(gmx, ep.mult) > ep.fhi || hq_round_scaled(gmn, ep.mult) < ep.flo)) {
-        unsigned nh = 0, nl = 0;
+        // rounded values and bounds are whole numbers: clamping the difference to [0, 1] is the
+        // indicator of a clipped value (a subtraction with the clamp modifier, no compare)
+        float nh = 0.0f, nl = 0.0f;
 #pragma unroll
         for (int e = 0; e < N; e++) {
-            nh += (unsigned)__popcll(__ballot(f[e] > ep.fhi));
-            nl += (unsigned)__popcll(__ballot(f[e] < ep.flo));
+            nh += __builtin_amdgcn_fmed3f(f[e] - ep.fhi, 0.0f, 1.0f);
+            nl += __builtin_amdgcn_fmed3f(ep.flo - f[e], 0.0f, 1.0f);
         }
-        const bool first = (int)__lane_id() == __ffsll((long long)__ballot(true)) - 1;
-        w_hi += first ? nh : 0u; w_lo += first ? nl : 0u;
+        w_hi += (unsigned)nh; w_lo += (unsigned)nl;
     }
 #pragma unroll
     for (int g = 0; g < N / 4; g++) {
