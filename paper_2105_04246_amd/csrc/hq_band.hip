@@ -106,23 +106,28 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
         col_lds[j] = ixp * PP + q * 16;
     }
     v4i pf[PR][PJ];
-    auto prefetch = [&](int tile) {
+    int pf_nrows = 0, pf_iy = 0;                           // rows of the patch being prefetched, its first input row
+    auto prefetch_setup = [&](int tile) {
         const int ps = p0 + tile * BM;
         const int oy0 = ps / a.Wo, oy1 = (min(ps + BM, p1) - 1) / a.Wo;
-        const int nrows = (oy1 - oy0) * a.stride + KSZ;
-        const int iy_base = oy0 * a.stride - a.pad;
+        pf_nrows = (oy1 - oy0) * a.stride + KSZ;
+        pf_iy = oy0 * a.stride - a.pad;
+    };
+    auto prefetch_row = [&](int k) {                       // k < PR, compile-time at every call site
+        const int iy = pf_iy + k;
+        const bool row_ok = k < pf_nrows && iy >= 0 && iy < a.Hs;        // uniform
+        const int8_t *rowp = Aimg + (size_t)(row_ok ? iy : 0) * a.Ws * C;
 #pragma unroll
-        for (int k = 0; k < PR; k++) {
-            const int iy = iy_base + k;
-            const bool row_ok = k < nrows && iy >= 0 && iy < a.Hs;       // uniform
-            const int8_t *rowp = Aimg + (size_t)(row_ok ? iy : 0) * a.Ws * C;
-#pragma unroll
-            for (int j = 0; j < PJ; j++) {
-                v4i v = fill;
-                if (row_ok && col_ok[j]) v = *reinterpret_cast<const v4i *>(rowp + col_src[j]);
-                pf[k][j] = v;
-            }
+        for (int j = 0; j < PJ; j++) {
+            v4i v = fill;
+            if (row_ok && col_ok[j]) v = *reinterpret_cast<const v4i *>(rowp + col_src[j]);
+            pf[k][j] = v;
         }
+    };
+    auto prefetch = [&](int tile) {
+        prefetch_setup(tile);
+#pragma unroll
+        for (int k = 0; k < PR; k++) prefetch_row(k);
     };
     auto stash = [&]() {
 #pragma unroll
@@ -188,8 +193,17 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                 // -------------------------------------------------- matrix-core phase
                 const int nxt = item + 2;
                 have_pf = nxt < nitem && nxt / nchunk != tile;
-                if (have_pf) prefetch(nxt / nchunk);
                 const bool active = ps + gwave * 64 < p1;
+                // the next tile's patch rows are requested between the taps (a few per tap), where the
+                // wait for a slot in the memory pipeline overlaps the MFMAs already issued
+                constexpr int RPT = (PR + TAPS - 1) / TAPS;
+                if (have_pf) {
+                    prefetch_setup(nxt / nchunk);
+                    if (!active) {
+#pragma unroll
+                        for (int k = 0; k < PR; k++) prefetch_row(k);
+                    }
+                }
                 const int oy0 = ps / a.Wo;
                 int abase[2];
 #pragma unroll
@@ -244,9 +258,20 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
                         __builtin_amdgcn_sched_barrier(0);
                         mfma_tap(wfA, afA);
                         __builtin_amdgcn_sched_barrier(0);
+                        if (have_pf) {
+#pragma unroll
+                            for (int k = t * RPT; k < (t + 1) * RPT && k < PR; k++) prefetch_row(k);
+                        }
                         if (t + 2 < TAPS) load_tap(t + 2, wfA, afA);
                         __builtin_amdgcn_sched_barrier(0);
-                        if (t + 1 < TAPS) mfma_tap(wfB, afB);
+                        if (t + 1 < TAPS) {
+                            mfma_tap(wfB, afB);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (have_pf) {
+#pragma unroll
+                                for (int k = (t + 1) * RPT; k < (t + 2) * RPT && k < PR; k++) prefetch_row(k);
+                            }
+                        }
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
