@@ -12,6 +12,11 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
                        const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
 
+// Fast path for forward layers with 4 input channels (a network's first layer); HQ_E_BADSHAPE: not covered.
+int hq_try_launch_direct(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
+                         const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
+                         int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+
 int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
                         const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
                         int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);

@@ -148,11 +148,11 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
                     const int8_t *base = a.X + (((size_t)pk_b[i] * a.H + iy0) * a.W + ix0) * a.C;
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
-                        if (pk_r[d] >= 0) {
-                            const int iy = iy0 + pk_r[d], ix = ix0 + pk_s[d];
-                            v[d] = (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W)
-                                       ? *reinterpret_cast<const int *>(base + pk_off[d]) : fill;
-                        }
+                        // branch-free: lanes without a source read the tensor's first word and drop it
+                        const int iy = iy0 + pk_r[d], ix = ix0 + pk_s[d];
+                        const bool in = pk_r[d] >= 0 && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+                        const int x = *reinterpret_cast<const int *>(in ? base + pk_off[d] : a.X);
+                        v[d] = in ? x : pk_r[d] >= 0 ? fill : 0;
                     }
                 }
                 pk_ow[i] += MB;
@@ -757,7 +757,11 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     a.ctiles = (a.C + TK - 1) / TK;
     const int xt = packed ? (int)((K + TK - 1) / TK) : p->R * p->S * a.ctiles, yt = (a.N + TN - 1) / TN;
     const int stages_total = (a.M + MB - 1) / MB;
-    int splits = (2048 + xt * yt - 1) / (xt * yt);          // aim at ~8 workgroups per CU
+    // Workgroups to aim at.  Small tiles need many resident workgroups to hide their stage latency;
+    // 128x128 tiles carry 64 KB of atomics each, and those queue on the same lines when every split
+    // finishes at once, so they get longer runs of pixels and fewer splits.
+    const int target = !big ? 2048 : p->R * p->S == 1 ? 256 : 512;
+    int splits = (target + xt * yt - 1) / (xt * yt);
     if (splits > stages_total) splits = stages_total;
     if (splits < 1) splits = 1;
     const int stages_per = (stages_total + splits - 1) / splits;
