@@ -162,6 +162,12 @@ int hq_gemm_wgrad(const hq_problem *p /* host */,
  * run it on the stream that produced the tensor, any time after the producing kernel.        */
 int hq_range_update(hq_range *r, hq_stats *st, void *stream);
 
+/* The same update for n quantizers in one launch: r[i] is updated from st[i], i < n (arrays of
+ * records).  A tensor's range is read next by its own layer's launch of the following iteration,
+ * so a training step can keep the range states of all its tensors in one array and update them
+ * together after the sweep instead of paying one small launch per tensor.                     */
+int hq_range_update_batch(hq_range *r, hq_stats *st, int32_t n, void *stream);
+
 /* Dynamic-quantization baseline (Sec. 3.2; eq. (1); traffic of eq. (5)): pass 1 runs the
  * same GEMM and writes every zero-point-corrected 32-bit output to `ws` while gathering
  * min/max; a one-wavefront kernel folds the statistics and derives the quantizer; pass 2 reads the 32-bit tensor back,

@@ -47,6 +47,7 @@ class HqError(RuntimeError):
 
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_wgrad", "hq_range_update",
+           "hq_range_update_batch",
            "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_error_string")
 
 
@@ -67,6 +68,7 @@ def lib():
         L.hq_gemm_dgrad.argtypes = [PP] + [vp] * 10
         L.hq_gemm_wgrad.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.hq_range_update.argtypes = [vp, vp, vp]
+        L.hq_range_update_batch.argtypes = [vp, vp, C.c_int32, vp]
         L.hq_gemm_dynamic.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 10 + [C.c_size_t, vp]
         L.hq_stats_reset.argtypes = [vp, C.c_int32, vp]
         L.hq_stats_fold.argtypes = [vp, C.c_int32, vp]
@@ -121,6 +123,10 @@ def hq_range_update(r, st, stream=None):
     _check("hq_range_update", lib().hq_range_update(_ptr(r), _ptr(st), _stream(stream)))
 
 
+def hq_range_update_batch(r, st, n, stream=None):
+    _check("hq_range_update_batch", lib().hq_range_update_batch(_ptr(r), _ptr(st), n, _stream(stream)))
+
+
 def hq_gemm_dynamic(op, mode, p, A, aq, Bw, bq, bsum, r, out, outq, st, ws, ws_bytes, stream=None):
     _check("hq_gemm_dynamic", lib().hq_gemm_dynamic(op, mode, C.byref(p), _ptr(A), _ptr(aq), _ptr(Bw), _ptr(bq),
                                                     _ptr(bsum), _ptr(r), _ptr(out), _ptr(outq), _ptr(st),
@@ -172,6 +178,17 @@ def new_range(eta=0.9, symmetric=False, device="cuda"):
     rec["eta"], rec["symmetric"] = eta, int(symmetric)
     rec["qlo"], rec["qhi"] = (-127, 127) if symmetric else (-128, 127)
     rec["scale"] = 1.0
+    return to_device(rec, device)
+
+
+def new_ranges(symmetric_flags, eta=0.9, device="cuda"):
+    """An array of uninitialised range states (one per flag) in one device buffer, for
+    hq_range_update_batch; record i starts at byte i * RANGE.itemsize."""
+    rec = np.zeros(len(symmetric_flags), RANGE)
+    for i, sym in enumerate(symmetric_flags):
+        rec[i]["eta"], rec[i]["symmetric"] = eta, int(sym)
+        rec[i]["qlo"], rec[i]["qhi"] = (-127, 127) if sym else (-128, 127)
+        rec[i]["scale"] = 1.0
     return to_device(rec, device)
 
 

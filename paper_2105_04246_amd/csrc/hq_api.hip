@@ -39,6 +39,7 @@ __device__ inline void stats_clear_wave(hq_stats *st)
 
 __global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats *st)
 {
+    r += blockIdx.x; st += blockIdx.x;
     // every load of the kernel is issued before anything waits: one memory round trip
     hq_range rr = *r;
     const float acc_scale = st->acc_scale;
@@ -250,6 +251,13 @@ int hq_range_update(hq_range *r, hq_stats *st, void *stream)
 {
     if (!r || !st || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
     hipLaunchKernelGGL(range_update_kernel, dim3(1), dim3(64), 0, as_stream(stream), r, st);
+    return launch_status();
+}
+
+int hq_range_update_batch(hq_range *r, hq_stats *st, int32_t n, void *stream)
+{
+    if (!r || !st || n <= 0 || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
+    hipLaunchKernelGGL(range_update_kernel, dim3(n), dim3(64), 0, as_stream(stream), r, st);
     return launch_status();
 }
 

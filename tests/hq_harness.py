@@ -120,12 +120,12 @@ def assert_range_close(gpu_r, ref_r, rel=1e-6):
 class TensorTrack:
     """One quantized output tensor followed over iterations on both sides: device range
     state + stats, and the oracle's Range."""
-    def __init__(self, eta=0.9, symmetric=False):
-        self.r = hq.new_range(eta, symmetric)
-        self.st = hq.new_stats(1)
+    def __init__(self, eta=0.9, symmetric=False, state=None):
+        """state: (range record, statistics record) views into caller-owned arrays, for the batched update."""
+        self.r, self.st = state if state is not None else (hq.new_range(eta, symmetric), hq.new_stats(1))
         self.ref = oracle.Range.new(eta, symmetric)
 
-    def step(self, L, op, A_q, W_q, A_dev, W_dev, check=True):
+    def step(self, L, op, A_q, W_q, A_dev, W_dev, check=True, update=True):
         """Runs iteration t on both sides (dynamic init at t=0, fused afterwards), compares
         codes, quantizer, statistics and the updated range.  Returns (gpu codes, oracle dict)."""
         a_scale = oracle.acc_scale(A_q.scale, W_q.scale)
@@ -134,12 +134,14 @@ class TensorTrack:
         ref = oracle.in_hindsight_step(c, a_scale, self.ref)
         codes, qp = gpu_quantized_op(L, op, A_dev, W_dev, self.r, self.st, "dynamic" if first else "fused")
         st = read_stats(self.st)
-        hq.hq_range_update(self.r, self.st)
+        if update:
+            hq.hq_range_update(self.r, self.st)
         torch.cuda.synchronize()
         if check:
             assert_stats_equal(st, ref, a_scale)
             assert np.float32(qp["scale"]) == ref["scale"] and int(qp["zero_point"]) == ref["zero_point"], (qp, ref["scale"], ref["zero_point"])
             assert np.array_equal(codes, ref["codes"]), "int8 outputs differ in %d places" % int((codes != ref["codes"]).sum())
+        if check and update:
             assert_range_close(read_range(self.r), self.ref)
             st2 = read_stats(self.st)
             assert int(st2["count"]) == 0 and int(st2["acc_min"]) == 2**31 - 1 and int(st2["acc_max"]) == -2**31

@@ -264,3 +264,29 @@ def test_error_codes(H, hq):
     torch.cuda.synchronize()
     s = H.read_stats(st)
     assert int(s["count"]) == 0                                             # nothing ran
+
+
+def test_batched_range_update(H, hq):
+    """eq. (2)-(3) for several quantizers in one launch: three range states in one array (two fed by
+    layers of different shapes, one that sees no data), updated together after each iteration."""
+    La, Lb = wl.conv("batch_a", 2, 9, 16, 32, 3), wl.linear("batch_b", 70, 48, 64)
+    ranges, stats = hq.new_ranges([False, True, False]), hq.new_stats(3)
+    rs, ss = hq.RANGE.itemsize, hq.STATS.itemsize
+    tracks = [H.TensorTrack(0.9, sym, state=(ranges[i * rs:(i + 1) * rs], stats[i * ss:(i + 1) * ss]))
+              for i, sym in enumerate((False, True, False))]
+    Xa, Wa, dYa = rand_layer_inputs(La, 5)
+    Xb, Wb, dYb = rand_layer_inputs(Lb, 6)
+    Wda, Wdb = H.DevWeights(La, Wa), H.DevWeights(Lb, Wb)
+    for t in range(3):
+        Xa_t = wl.relu_activation(np.random.default_rng(100 + t), wl.in_shape(La))
+        dYb_t = wl.laplace_gradient(np.random.default_rng(200 + t), wl.out_shape(Lb), 1e-2 * 0.7 ** t)
+        tracks[0].step(La, "fwd", Xa_t, Wa, H.DevTensor(Xa_t), Wda, update=False)
+        tracks[1].step(Lb, "dgrad", dYb_t, Wb, H.DevTensor(dYb_t), Wdb, update=False)
+        hq.hq_range_update_batch(ranges, stats, 3)
+        torch.cuda.synchronize()
+        for tr in tracks[:2]:
+            H.assert_range_close(H.read_range(tr.r), tr.ref)
+            st = H.read_stats(tr.st)
+            assert int(st["count"]) == 0 and int(st["acc_min"]) == 2**31 - 1
+        idle = H.read_range(tracks[2].r)
+        assert int(idle["initialized"]) == 0 and float(idle["qmin"]) == 0.0 and float(idle["qmax"]) == 0.0
