@@ -51,7 +51,6 @@ struct BandArgs {
 };
 
 constexpr int BM = 256;            // output pixels per tile: 4 wavefronts x 2 MFMA row blocks
-constexpr int BAND_THREADS = 512;  // two groups of four wavefronts
 
 __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
@@ -61,20 +60,26 @@ template <int C> __device__ inline int wswz(int i)
 }
 
 // PR: patch rows prefetched per tile (>= PRmax), PJ: 16-byte column chunks per thread and row.
-template <int C, int KSZ, int NT, int PR, int PJ, bool FUSED>
-__global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
+// NG: groups of four wavefronts in a workgroup.  NG == 2: the two groups alternate matrix-core
+// phase and epilogue phase in lockstep, half a step apart.  NG == 1 (when the LDS holds two
+// workgroups with their own copy of the weights): a workgroup runs its phases one after the other
+// and the two workgroups of a compute unit overlap freely, without a common barrier and without the
+// idle half steps at both ends.
+template <int C, int KSZ, int NT, int PR, int PJ, int NG, bool FUSED>
+__global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(const BandArgs a)
 {
+    constexpr int BAND_THREADS = 256 * NG;
     constexpr int NCH = C / 16, KS = C / 32, PP = C + 16, BN = 32 * NT, TAPS = KSZ * KSZ;
     constexpr int WROW = TAPS * C;                        // bytes per weight row in LDS
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     const int patch_bytes = a.PRmax * a.PW * PP;
     int8_t *Wl = smem;                                     // [npad][TAPS][C], chunks swizzled
     int *bz = reinterpret_cast<int *>(smem + (size_t)a.npad * WROW);     // [npad]  z_a * bsum[n]
-    int8_t *Pl = reinterpret_cast<int8_t *>(bz + a.npad);  // two patches [PRmax * PW][PP]
-    int *red = reinterpret_cast<int *>(Pl + 2 * (size_t)patch_bytes);
+    int8_t *Pl = reinterpret_cast<int8_t *>(bz + a.npad);  // one patch per group [PRmax * PW][PP]
+    int *red = reinterpret_cast<int *>(Pl + NG * (size_t)patch_bytes);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int grp = wave >> 2, gwave = wave & 3, gtid = tid & 255;
+    const int grp = NG == 2 ? wave >> 2 : 0, gwave = wave & 3, gtid = tid & 255;
     int8_t *Pg = Pl + grp * patch_bytes;                   // this group's patch
     const int za = a.aq->zero_point;
     const int fillw = (za & 0xff) * 0x01010101;
@@ -183,15 +188,16 @@ __global__ __launch_bounds__(BAND_THREADS) void hq_band_kernel(const BandArgs a)
 
     // Half step h: item h is multiplied (by group h & 1) while item h-1 goes through the
     // epilogue (in the other group, which multiplied it during half step h-1).
-    for (int h = 0; h <= nitem; h++) {
-        const bool mfma_phase = (h & 1) == grp;
-        const int item = mfma_phase ? h : h - 1;           // this group's item in this half step
+    const int nhalf = NG == 2 ? nitem + 1 : 2 * nitem;
+    for (int h = 0; h < nhalf; h++) {
+        const bool mfma_phase = NG == 2 ? (h & 1) == grp : (h & 1) == 0;
+        const int item = NG == 2 ? (mfma_phase ? h : h - 1) : h >> 1;       // this group's item in this half step
         if (item >= 0 && item < nitem) {
             const int tile = item / nchunk, nc = item - tile * nchunk;
             const int ps = p0 + tile * BM;
             if (mfma_phase) {
                 // -------------------------------------------------- matrix-core phase
-                const int nxt = item + 2;
+                const int nxt = item + NG;
                 have_pf = nxt < nitem && nxt / nchunk != tile;
                 const bool active = ps + gwave * 64 < p1;
                 // the next tile's patch rows are requested between the taps (a few per tap), where the
@@ -325,23 +331,29 @@ unsigned magic32(unsigned d) { return (unsigned)(((1ull << 32) + d - 1) / d); }
 
 constexpr size_t BAND_LDS_MAX = 160 * 1024;
 
-template <int C, int KSZ, int NT, int PR, int PJ>
+template <int C, int KSZ, int NT, int PR, int PJ, int NG>
 int launch_band(const BandArgs &a, int blocks, size_t lds, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, true>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, NG, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, false>),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, NG, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX) != hipSuccess)
             return HQ_E_HIP;
         configured = true;
     }
     if (a.out32 == nullptr)
-        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, true>), dim3(blocks), dim3(BAND_THREADS), lds, s, a);
+        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, NG, true>), dim3(blocks), dim3(256 * NG), lds, s, a);
     else
-        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, false>), dim3(blocks), dim3(BAND_THREADS), lds, s, a);
+        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, NG, false>), dim3(blocks), dim3(256 * NG), lds, s, a);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+}
+
+template <int C, int KSZ, int NT, int PR, int PJ>
+int launch_band_ng(const BandArgs &a, int ng, int blocks, size_t lds, hipStream_t s)
+{
+    return ng == 1 ? launch_band<C, KSZ, NT, PR, PJ, 1>(a, blocks, lds, s) : launch_band<C, KSZ, NT, PR, PJ, 2>(a, blocks, lds, s);
 }
 
 } // namespace
@@ -378,38 +390,45 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
     a.PW = (a.Wo - 1) * a.stride + KSZ;
     if (a.PW * (C / 16) > 256 * PJ) return HQ_E_BADSHAPE;
 
-    // bands: one workgroup per CU when the batch allows it
-    int bpi = (256 + p->B - 1) / p->B;
-    if (bpi > a.Ho) bpi = a.Ho;
-    if (bpi < 1) bpi = 1;
-    a.rows_per_band = (a.Ho + bpi - 1) / bpi;
-    a.bands_per_image = (a.Ho + a.rows_per_band - 1) / a.rows_per_band;
-    // most patch rows any tile needs
-    int prmax = 0;
-    for (int band = 0; band < a.bands_per_image; band++) {
-        const int r0 = band * a.rows_per_band, r1 = (r0 + a.rows_per_band < a.Ho) ? r0 + a.rows_per_band : a.Ho;
-        for (int ps = r0 * a.Wo; ps < r1 * a.Wo; ps += BM) {
-            const int last = (ps + BM < r1 * a.Wo ? ps + BM : r1 * a.Wo) - 1;
-            const int rows = (last / a.Wo - ps / a.Wo) * a.stride + KSZ;
-            if (rows > prmax) prmax = rows;
+    // bands: one two-group workgroup per CU, or (1x1 layers, where it measured faster: short tiles,
+    // small weights) two independent one-group workgroups when the LDS holds both
+    size_t lds = 0;
+    int ng = 1, prmax = 0;
+    for (ng = KSZ == 1 ? 1 : 2; ng <= 2; ng++) {
+        int bpi = ((ng == 1 ? 512 : 256) + p->B - 1) / p->B;
+        if (bpi > a.Ho) bpi = a.Ho;
+        if (bpi < 1) bpi = 1;
+        a.rows_per_band = (a.Ho + bpi - 1) / bpi;
+        a.bands_per_image = (a.Ho + a.rows_per_band - 1) / a.rows_per_band;
+        // most patch rows any tile needs
+        prmax = 0;
+        for (int band = 0; band < a.bands_per_image; band++) {
+            const int r0 = band * a.rows_per_band, r1 = (r0 + a.rows_per_band < a.Ho) ? r0 + a.rows_per_band : a.Ho;
+            for (int ps = r0 * a.Wo; ps < r1 * a.Wo; ps += BM) {
+                const int last = (ps + BM < r1 * a.Wo ? ps + BM : r1 * a.Wo) - 1;
+                const int rows = (last / a.Wo - ps / a.Wo) * a.stride + KSZ;
+                if (rows > prmax) prmax = rows;
+            }
         }
+        lds = (size_t)a.npad * KSZ * KSZ * C + (size_t)a.npad * 4 + ng * (size_t)prmax * a.PW * (C + 16) + 128;
+        if (ng == 1 && 2 * (lds + 1024) <= BAND_LDS_MAX) break;      // two workgroups fit (1 KiB each of slack)
+        if (ng == 2) break;
     }
     a.PRmax = prmax;
-    const size_t lds = (size_t)a.npad * KSZ * KSZ * C + (size_t)a.npad * 4 + 2 * (size_t)prmax * a.PW * (C + 16) + 128;
     if (lds > BAND_LDS_MAX) return HQ_E_BADSHAPE;
     a.magic_Wo = magic32((unsigned)a.Wo);
     a.count = (unsigned long long)p->B * a.Ho * a.Wo * a.N;
     const int blocks = p->B * a.bands_per_image;
     if (C == 64) {
-        if (prmax <= 8) return launch_band<64, 3, 2, 8, 1>(a, blocks, lds, stream);
-        if (prmax <= 12) return launch_band<64, 3, 2, 12, 1>(a, blocks, lds, stream);
+        if (prmax <= 8) return launch_band_ng<64, 3, 2, 8, 1>(a, ng, blocks, lds, stream);
+        if (prmax <= 12) return launch_band_ng<64, 3, 2, 12, 1>(a, ng, blocks, lds, stream);
         return HQ_E_BADSHAPE;
     }
     if (C == 32) {
-        if (prmax <= 6) return launch_band<32, 1, 2, 6, 1>(a, blocks, lds, stream);
-        if (prmax <= 14) return launch_band<32, 1, 2, 14, 1>(a, blocks, lds, stream);
+        if (prmax <= 6) return launch_band_ng<32, 1, 2, 6, 1>(a, ng, blocks, lds, stream);
+        if (prmax <= 14) return launch_band_ng<32, 1, 2, 14, 1>(a, ng, blocks, lds, stream);
         return HQ_E_BADSHAPE;
     }
-    if (prmax <= 6) return launch_band<192, 1, 1, 6, 3>(a, blocks, lds, stream);
+    if (prmax <= 6) return launch_band_ng<192, 1, 1, 6, 3>(a, ng, blocks, lds, stream);
     return HQ_E_BADSHAPE;
 }
