@@ -215,6 +215,8 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
         return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     rc = hq_try_launch_direct(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     if (rc != HQ_E_BADSHAPE) return rc;
+    rc = hq_try_launch_bandw(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
+    if (rc != HQ_E_BADSHAPE) return rc;
     rc = hq_try_launch_band(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     if (rc != HQ_E_BADSHAPE) return rc;
     return hq_launch_gemm(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));

@@ -159,6 +159,28 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
         ay[i] = CLASSED ? y + dh : STRIDED ? y + a.pad : y * a.stride - a.pad;
         ax[i] = CLASSED ? x + dw : STRIDED ? x + a.pad : x * a.stride - a.pad;
     }
+    // Aligned form: per row, the address of tap (0, 0) and a bit per tap that says whether the tap has a
+    // source pixel, so that a stage costs one 64-bit add and one bit test per row instead of the
+    // bounds arithmetic and a 64-bit multiply (up to 64 taps; larger filters test bounds per stage).
+    const int taps_eff = CLASSED ? nr * ns : a.taps, tapw_eff = CLASSED ? ns : a.S;
+    const bool use_mask = ALIGNED && taps_eff <= 64;
+    const int8_t *arow[AROWS];
+    unsigned long long amask[AROWS];
+    if (ALIGNED) {
+#pragma unroll
+        for (int i = 0; i < AROWS; i++) {
+            arow[i] = abase[i] + ((ptrdiff_t)ay[i] * a.Ws + ax[i]) * a.Cs;
+            unsigned long long mk = 0;
+            if (use_mask && arow_ok[i]) {
+                for (int t = 0; t < taps_eff; t++) {
+                    const int r = t / tapw_eff, c = t - r * tapw_eff;
+                    const int iy = CLASSED ? ay[i] - r : ay[i] + r, ix = CLASSED ? ax[i] - c : ax[i] + c;
+                    if (iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws) mk |= 1ull << t;
+                }
+            }
+            amask[i] = mk;
+        }
+    }
     const int8_t *bbase[BROWS];
     bool brow_ok[BROWS];
     const size_t brow_len = (size_t)a.taps * a.Cs;
@@ -187,18 +209,20 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
         const bool chunk_ok = chunk < nchunks;
         const int coff = c16 * 16;
         const v4i fillv = {fill, fill, fill, fill}, zerov = {0, 0, 0, 0};
+        const int tapoff = (CLASSED ? -(tr * a.Ws + ts) : tr * a.Ws + ts) * a.Cs + coff;   // from the row's tap (0, 0)
 #pragma unroll
         for (int i = 0; i < AROWS; i++) {
-            int iy, ix;
-            bool ok = chunk_ok && arow_ok[i];
-            if (CLASSED) { iy = ay[i] - tr; ix = ax[i] - ts; }
-            else { iy = ay[i] + tr; ix = ax[i] + ts; }
-            ok = ok && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
+            bool ok;
+            if (use_mask) {
+                ok = chunk_ok && ((amask[i] >> (tap & 63)) & 1ull) != 0;
+            } else {
+                const int iy = CLASSED ? ay[i] - tr : ay[i] + tr, ix = CLASSED ? ax[i] - ts : ax[i] + ts;
+                ok = chunk_ok && arow_ok[i] && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
+            }
             int8_t *dst = As + (size_t)buf * BM * BKB + 4096 * i + (tid & ~63) * 16;      // this wavefront's 1 KiB
             if (ok) {
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(abase[i] + ((size_t)iy * a.Ws + ix) * a.Cs + coff),
-                    (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(arow[i] + tapoff),
+                                                 (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
             } else {
                 *reinterpret_cast<v4i *>(dst + lane * 16) = fillv;
             }

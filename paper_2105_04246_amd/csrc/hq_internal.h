@@ -17,6 +17,12 @@ int hq_try_launch_direct(const hq_problem *p, int dgrad, const int8_t *A, const 
                          const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
                          int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
 
+// Fast path for 3x3 stride-1 layers with 128 or more channels on both sides (input patch staged once per
+// 64-channel chunk, weights streamed); HQ_E_BADSHAPE: not covered.
+int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
+                        const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
+                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+
 int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
                         const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
                         int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
