@@ -93,8 +93,10 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_kernel(const DwArgs a
 // 3x3, stride 1 (forward, and input gradient as the same stencil with mirrored taps): the
 // shape of the depthwise layers of MobileNetV2-style blocks (Table 5, DW rows).
 // A thread owns four channels of one output column and slides down a strip of rows, keeping
-// the 3x3 window unpacked in registers: per output row it loads three new words (one input
-// row of the window), so an input byte is requested 3 times (by the three neighbouring
+// the 3x3 window in registers as one word per (window row, channel) with the three horizontally
+// adjacent values in its bytes (two v_perm_b32 per word), so that an output is three 4-way byte
+// dot products (v_dot4) instead of nine multiply-adds on unpacked values.  Per output row the
+// thread loads three new words (one input row of the window), so an input byte is requested 3 times (by the three neighbouring
 // columns, which sit in adjacent lanes and hit the same cache lines) instead of 9.  Lanes run
 // along (column, channel) of a row, which is how NHWC lies in memory: loads and the 4-code
 // stores are contiguous across the wavefront.  The next row's words are requested before the
@@ -119,6 +121,19 @@ __device__ inline void dw_unpack(int v, int *dst)
     for (int e = 0; e < 4; e++) dst[e] = sbyte(v, e);
 }
 
+// Three packed words (four channels each of the pixels left, middle, right) -> four words, one per
+// channel, holding that channel's three horizontally adjacent values and a zero byte: the operand
+// of a 4-way byte dot product against the three taps of a filter row.
+__device__ inline void dw_transpose3(int l, int m, int r, int *t)
+{
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        // v_perm_b32: selector bytes 0..3 pick bytes of the second source, 4..7 of the first, 0x0c is zero
+        const unsigned lm = __builtin_amdgcn_perm((unsigned)m, (unsigned)l, 0x0c0c0000u | (unsigned)e | ((4u + e) << 8));
+        t[e] = (int)__builtin_amdgcn_perm((unsigned)r, lm, 0x0c000100u | ((4u + e) << 16));
+    }
+}
+
 __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
 {
     __shared__ int red[4 * (HQ_THREADS / 64)];
@@ -138,12 +153,18 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
     HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
     if (fused) ep = hq_make_epilogue(acc_scale, a.range);
 
-    // weights of the four channels, unpacked; mirrored for the input gradient
-    int w[9][4];
+    // weights of the four channels: per filter row and channel one word (w[r][0], w[r][1], w[r][2], 0);
+    // mirrored for the input gradient
+    int wt[3][4];
 #pragma unroll
-    for (int t = 0; t < 9; t++) {
-        const int ts = a.flip ? 8 - t : t;
-        dw_unpack(*reinterpret_cast<const int *>(a.Wt + (size_t)ts * a.C + c), w[t]);
+    for (int r = 0; r < 3; r++) {
+        int pk[3];
+#pragma unroll
+        for (int sx = 0; sx < 3; sx++) {
+            const int t = r * 3 + sx, ts = a.flip ? 8 - t : t;
+            pk[sx] = *reinterpret_cast<const int *>(a.Wt + (size_t)ts * a.C + c);
+        }
+        dw_transpose3(pk[0], pk[1], pk[2], wt[r]);
     }
     const v4i wsv = *reinterpret_cast<const v4i *>(a.wsum + c);
     int zw[4];
@@ -163,18 +184,16 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
 
     int mn = INT_MAX, mx = INT_MIN;
     unsigned nlo = 0, nhi = 0;
-    int win[3][3][4];                                                // [row slot][column][channel]
+    int win[3][4];                                                   // [row slot][channel]: (left, middle, right, 0)
     int ring[3][3];                                                  // packed words of the next three input rows
     if (live) {
         int tmp[3];
         load_row(pn, y0 > 0, tmp);                                   // row y0 - 1
         if (y0 > 0) pn += rowbytes;
-#pragma unroll
-        for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[0][s]);
+        dw_transpose3(tmp[0], tmp[1], tmp[2], win[0]);
         load_row(pn, true, tmp);                                     // row y0
         pn += rowbytes;
-#pragma unroll
-        for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[1][s]);
+        dw_transpose3(tmp[0], tmp[1], tmp[2], win[1]);
 #pragma unroll
         for (int k = 0; k < 3; k++) {                                // rows y0 + 1 .. y0 + 3 in flight
             load_row(pn, y0 + 1 + k < a.H, ring[k]);
@@ -184,14 +203,13 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
     // one output row; TOP / MID / BOT name the register slots of input rows oy-1, oy, oy+1
 #define DW_STEP(TOP, MID, BOT, RING)                                                                        \
     if (live && oy < y1) {                                                                            \
-        _Pragma("unroll") for (int s = 0; s < 3; s++) dw_unpack(ring[RING][s], win[BOT][s]);            \
+        dw_transpose3(ring[RING][0], ring[RING][1], ring[RING][2], win[BOT]);                           \
         if (oy + 3 < y1) { load_row(pn, oy + 4 < a.H, ring[RING]); pn += rowbytes; }                   \
         int cv[4];                                                                                    \
         _Pragma("unroll") for (int e = 0; e < 4; e++) {                                                 \
-            int acc = -zw[e];                                                                         \
-            _Pragma("unroll") for (int s = 0; s < 3; s++)                                               \
-                acc += __mul24(win[TOP][s][e], w[s][e]) + __mul24(win[MID][s][e], w[3 + s][e]) + __mul24(win[BOT][s][e], w[6 + s][e]); \
-            cv[e] = acc;                                                                              \
+            int acc = __builtin_amdgcn_sdot4(win[TOP][e], wt[0][e], -zw[e], false);                   \
+            acc = __builtin_amdgcn_sdot4(win[MID][e], wt[1][e], acc, false);                          \
+            cv[e] = __builtin_amdgcn_sdot4(win[BOT][e], wt[2][e], acc, false);                        \
         }                                                                                             \
         if (fused) {                                                                                  \
             int wd;                                                                                   \
