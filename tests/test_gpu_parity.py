@@ -72,6 +72,10 @@ SMALL = [
     wl.conv("band_multi_tile", 128, 36, 64, 64, 3),  # 4 bands per image of 9 rows: two tiles per band, second ragged
     wl.conv("wband_14", 3, 14, 64, 64, 3),           # weight-gradient band = one whole image, 28 pixels of padding
     wl.depthwise("dw_strips", 3, 40, 48),            # depthwise strips with a ragged last strip
+    wl.conv("bandw_multi_img", 3, 10, 128, 192, 3),  # streamed-weights path: tiles of two whole images (last one short), ragged channel chunk
+    wl.conv("bandw_rows", 2, 30, 192, 128, 3),       # ... tiles of rows, last tile of an image short; wgrad blocks 3 x 2
+    wl.conv("first_layer", 2, 23, 4, 48, 7, stride=2),   # 4-channel first layer: direct kernel, ragged channel block, odd size
+    wl.conv("c5x5_s3", 2, 17, 16, 32, 5, stride=3),  # stride 3: nine pixel classes in the input gradient
 ]
 
 
