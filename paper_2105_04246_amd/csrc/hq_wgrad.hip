@@ -343,26 +343,25 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
     const bool do_xsum = np == 0;
 
     // ---- per-thread staging plan (the same for every band)
-    int x_lds[WB_XLD], x_rel[WB_XLD], x_pr[WB_XLD], x_il[WB_XLD];
+    int x_rel[WB_XLD], x_rowimg[WB_XLD];                 // source offset; patch row | image << 16
     bool x_on[WB_XLD], x_col[WB_XLD];
 #pragma unroll
     for (int i = 0; i < WB_XLD; i++) {
         const int idx = tid + WB_THREADS * i, c16 = idx & 3, ppix = idx >> 2;
         const int prow = ppix / a.PW, pcol = ppix - prow * a.PW;
         x_on[i] = idx < a.xchunks;
-        x_il[i] = prow / (a.rows + 2); x_pr[i] = prow - x_il[i] * (a.rows + 2);
+        const int il = prow / (a.rows + 2), pr = prow - il * (a.rows + 2);
+        x_rowimg[i] = pr | (il << 16);
         x_col[i] = pcol >= 1 && pcol <= a.W;
-        x_lds[i] = ppix * WB_P + c16 * 16;
-        x_rel[i] = ((x_il[i] * a.H + x_pr[i] - 1) * a.W + (pcol - 1)) * a.C + c16 * 16;
+        x_rel[i] = ((il * a.H + pr - 1) * a.W + (pcol - 1)) * a.C + c16 * 16;
     }
-    int g_lds[WB_GLD], g_rel[WB_GLD], g_il[WB_GLD];
+    int g_rel[WB_GLD], g_il[WB_GLD];
     bool g_on[WB_GLD];
 #pragma unroll
     for (int i = 0; i < WB_GLD; i++) {
         const int idx = tid + WB_THREADS * i, c16 = idx & 3, p = idx >> 2;
         g_on[i] = idx < a.gchunks;
         g_il[i] = p / (a.rows * a.W);
-        g_lds[i] = p * WB_P + c16 * 16;
         g_rel[i] = p * a.N + c16 * 16;
     }
     v4i xreg[WB_XLD], greg[WB_GLD];
@@ -375,8 +374,8 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
         const int8_t *gs = a.G + pix0 * a.N + n0;
 #pragma unroll
         for (int i = 0; i < WB_XLD; i++) {
-            const bool img = b0 + x_il[i] < a.B;                    // images past the end of the batch count as zeros
-            const bool inside = img && x_col[i] && (unsigned)(y0 + x_pr[i] - 1) < (unsigned)a.H;
+            const bool img = b0 + (x_rowimg[i] >> 16) < a.B;        // images past the end of the batch count as zeros
+            const bool inside = img && x_col[i] && (unsigned)(y0 + (x_rowimg[i] & 0xffff) - 1) < (unsigned)a.H;
             const int f = img ? fillw : 0;                          // border of a real image: real zero
             v4i v = {f, f, f, f};
             if (x_on[i] && inside) v = *reinterpret_cast<const v4i *>(xs + x_rel[i]);
@@ -393,10 +392,16 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
         int8_t *xb = bufs + buf * a.buf_bytes, *gb = xb + xbytes;
 #pragma unroll
         for (int i = 0; i < WB_XLD; i++)
-            if (x_on[i]) *reinterpret_cast<v4i *>(xb + x_lds[i]) = xreg[i];
+            if (x_on[i]) {
+                const int idx = tid + WB_THREADS * i;
+                *reinterpret_cast<v4i *>(xb + (idx >> 2) * WB_P + (idx & 3) * 16) = xreg[i];
+            }
 #pragma unroll
         for (int i = 0; i < WB_GLD; i++)
-            if (g_on[i]) *reinterpret_cast<v4i *>(gb + g_lds[i]) = greg[i];
+            if (g_on[i]) {
+                const int idx = tid + WB_THREADS * i;
+                *reinterpret_cast<v4i *>(gb + (idx >> 2) * WB_P + (idx & 3) * 16) = greg[i];
+            }
     };
 
     // ---- start-up: first band on its way, pixel table, zero rows behind the last pixel of a band
