@@ -313,13 +313,13 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
     a.count = (unsigned long long)p->B * p->H * p->W * N;
     const size_t patch_bytes = ((size_t)a.patch_px * BW_CK + 1023) & ~(size_t)1023;
     const size_t lds = 4 * BW_BN * BW_CK + 2 * patch_bytes + 4 * BW_BN + 64;
-    if (lds > 78 * 1024) return HQ_E_BADSHAPE;             // two workgroups per compute unit
+    if (lds > 158 * 1024) return HQ_E_BADSHAPE;            // (two workgroups per compute unit up to 78 KiB)
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess ||
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return HQ_E_HIP;
         configured = true;
     }
