@@ -313,19 +313,35 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_wgrad_kernel(const Dw
 }
 
 // 3x3, stride 1, pad 1 weight gradient: the thread layout of hq_dw3x3_kernel (four channels of
-// one column, sliding down a strip of rows with the 3x3 input window unpacked in registers), so
-// an output row costs three new input words and one gradient word instead of ten loads with
-// their address arithmetic.  A workgroup walks over several images and keeps its 36 products
-// per thread in registers; threads that share channels meet in LDS, and the workgroup leaves
-// with one atomic per value.  The column sums of the input that remove the gradient's zero
-// point are only gathered when that zero point is not 0.
+// one column, sliding down a strip of rows), four output rows at a time.  The reduction runs over
+// pixels, so the rows are byte-transposed: four packed words (four rows, four channels each)
+// become four words holding four vertically adjacent values of one channel (eight v_perm_b32),
+// and a tap's contribution of the four rows is one 4-way dot product against the transposed
+// gradient word.  The three row taps are the transposed block shifted by one row either way
+// (v_alignbyte with the neighbouring blocks).  A workgroup walks over several images and keeps
+// its 36 sums per thread in registers; threads that share channels meet in LDS, and the workgroup
+// leaves with one atomic per value.  The column sums of the input that remove the gradient's
+// zero point are only gathered when that zero point is not 0.
 struct Dw3WgradArgs {
     const int8_t *X, *G;
     const hq_qparams *xq, *gq;
     int32_t *acc, *gsum, *xsum;
     int B, H, W, C;
-    int rows_per_strip;
+    int rows_per_strip;            // multiple of 4
 };
+
+// four words = four rows of four channels -> t[e] = (row0[e], row1[e], row2[e], row3[e])
+__device__ inline void dw_transpose4(int a0, int a1, int a2, int a3, int *t)
+{
+    const unsigned p0 = __builtin_amdgcn_perm((unsigned)a1, (unsigned)a0, 0x05010400u);   // (a0.0, a1.0, a0.1, a1.1)
+    const unsigned p1 = __builtin_amdgcn_perm((unsigned)a1, (unsigned)a0, 0x07030602u);   // (a0.2, a1.2, a0.3, a1.3)
+    const unsigned q0 = __builtin_amdgcn_perm((unsigned)a3, (unsigned)a2, 0x05010400u);
+    const unsigned q1 = __builtin_amdgcn_perm((unsigned)a3, (unsigned)a2, 0x07030602u);
+    t[0] = (int)__builtin_amdgcn_perm(q0, p0, 0x05040100u);
+    t[1] = (int)__builtin_amdgcn_perm(q0, p0, 0x07060302u);
+    t[2] = (int)__builtin_amdgcn_perm(q1, p1, 0x05040100u);
+    t[3] = (int)__builtin_amdgcn_perm(q1, p1, 0x07060302u);
+}
 
 __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_wgrad_kernel(const Dw3WgradArgs a)
 {
@@ -353,64 +369,81 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_wgrad_kernel(const Dw3Wgr
 
     if (live && y0 < y1) {
         for (int b = blockIdx.z; b < a.B; b += gridDim.z) {
-            const int8_t *pcol = a.X + (size_t)b * a.H * rowbytes + (size_t)ox * a.C + c;
-            const int8_t *pg = a.G + (size_t)b * a.H * rowbytes + (size_t)y0 * rowbytes + (size_t)ox * a.C + c;
-            auto load_row = [&](const int8_t *p, bool rowok, int *dst) {
-                dst[0] = (rowok && okl) ? *reinterpret_cast<const int *>(p - a.C) : fill;
-                dst[1] = rowok ? *reinterpret_cast<const int *>(p) : fill;
-                dst[2] = (rowok && okr) ? *reinterpret_cast<const int *>(p + a.C) : fill;
-            };
-            const int8_t *pn = pcol + (size_t)(y0 > 0 ? y0 - 1 : 0) * rowbytes;
-            int win[3][3][4], ring[3][3], gring[3];
-            {
-                int tmp[3];
-                load_row(pn, y0 > 0, tmp);
-                if (y0 > 0) pn += rowbytes;
+            const int8_t *ximg = a.X + (size_t)b * a.H * rowbytes + (size_t)ox * a.C + c;
+            const int8_t *gimg = a.G + (size_t)b * a.H * rowbytes + (size_t)ox * a.C + c;
+            // block of four input rows starting at row y: raw[row][column], zero-point code outside the image
+            auto load_x = [&](int y, int (&raw)[4][3]) {
 #pragma unroll
-                for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[0][s]);
-                load_row(pn, true, tmp);
-                pn += rowbytes;
-#pragma unroll
-                for (int s = 0; s < 3; s++) dw_unpack(tmp[s], win[1][s]);
-#pragma unroll
-                for (int k = 0; k < 3; k++) {
-                    load_row(pn, y0 + 1 + k < a.H, ring[k]);
-                    pn += rowbytes;
-                    gring[k] = y0 + k < y1 ? *reinterpret_cast<const int *>(pg) : 0;
-                    pg += rowbytes;
+                for (int k = 0; k < 4; k++) {
+                    const int iy = y + k;
+                    const bool rok = iy >= 0 && iy < a.H;
+                    const int8_t *p = ximg + (ptrdiff_t)iy * rowbytes;
+                    const int l = *reinterpret_cast<const int *>(rok && okl ? p - a.C : ximg);
+                    const int m = *reinterpret_cast<const int *>(rok ? p : ximg);
+                    const int r = *reinterpret_cast<const int *>(rok && okr ? p + a.C : ximg);
+                    raw[k][0] = rok && okl ? l : fill; raw[k][1] = rok ? m : fill; raw[k][2] = rok && okr ? r : fill;
                 }
+            };
+            // gradient rows y .. y+3 of this column; rows past the strip count as zero
+            auto load_g = [&](int y, int (&raw)[4]) {
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const bool rok = y + k < y1;
+                    const int v = *reinterpret_cast<const int *>(rok ? gimg + (size_t)(y + k) * rowbytes : gimg);
+                    raw[k] = rok ? v : 0;
+                }
+            };
+            auto transpose_x = [&](const int (&raw)[4][3], int (&t)[3][4]) {
+#pragma unroll
+                for (int sx = 0; sx < 3; sx++) dw_transpose4(raw[0][sx], raw[1][sx], raw[2][sx], raw[3][sx], t[sx]);
+            };
+            int prev[3][4], cur[3][4], nxt[3][4];             // [column][channel]: four rows in the bytes
+            int xraw[4][3], graw[4];
+            {
+                // of the block above the strip only its last row (y0 - 1) is ever read
+                const int iy = y0 - 1;
+                const bool rok = iy >= 0;
+                const int8_t *p = ximg + (ptrdiff_t)iy * rowbytes;
+                const int l = *reinterpret_cast<const int *>(rok && okl ? p - a.C : ximg);
+                const int m = *reinterpret_cast<const int *>(rok ? p : ximg);
+                const int r = *reinterpret_cast<const int *>(rok && okr ? p + a.C : ximg);
+                const int row3[3] = {rok && okl ? l : fill, rok ? m : fill, rok && okr ? r : fill};
+#pragma unroll
+                for (int sx = 0; sx < 3; sx++) dw_transpose4(0, 0, 0, row3[sx], prev[sx]);
             }
-#define DWW_STEP(TOP, MID, BOT, RING)                                                                      \
-            if (oy < y1) {                                                                                \
-                _Pragma("unroll") for (int s = 0; s < 3; s++) dw_unpack(ring[RING][s], win[BOT][s]);        \
-                int g[4];                                                                                 \
-                dw_unpack(gring[RING], g);                                                                \
-                if (oy + 3 < y1) {                                                                        \
-                    load_row(pn, oy + 4 < a.H, ring[RING]); pn += rowbytes;                               \
-                    gring[RING] = *reinterpret_cast<const int *>(pg); pg += rowbytes;                      \
-                }                                                                                         \
-                _Pragma("unroll") for (int e = 0; e < 4; e++) {                                             \
-                    gs[e] += g[e];                                                                        \
-                    _Pragma("unroll") for (int s = 0; s < 3; s++) {                                         \
-                        acc[s][e] += __mul24(win[TOP][s][e], g[e]);                                       \
-                        acc[3 + s][e] += __mul24(win[MID][s][e], g[e]);                                   \
-                        acc[6 + s][e] += __mul24(win[BOT][s][e], g[e]);                                   \
-                    }                                                                                     \
-                }                                                                                         \
-                if (want_xsum) {                                                                          \
-                    _Pragma("unroll") for (int e = 0; e < 4; e++)                                           \
-                        _Pragma("unroll") for (int s = 0; s < 3; s++) {                                     \
-                            xs[s][e] += win[TOP][s][e]; xs[3 + s][e] += win[MID][s][e]; xs[6 + s][e] += win[BOT][s][e]; \
-                        }                                                                                 \
-                }                                                                                         \
-            }                                                                                             \
-            oy++;
-            for (int oy = y0; oy < y1;) {
-                DWW_STEP(0, 1, 2, 0)
-                DWW_STEP(1, 2, 0, 1)
-                DWW_STEP(2, 0, 1, 2)
+            load_x(y0, xraw); transpose_x(xraw, cur);
+            load_x(y0 + 4, xraw);                                // in flight: rows y0+4 .. y0+7, gradient rows y0 .. y0+3
+            load_g(y0, graw);
+            for (int oy = y0; oy < y1; oy += 4) {
+                transpose_x(xraw, nxt);
+                int gt[4];
+                dw_transpose4(graw[0], graw[1], graw[2], graw[3], gt);
+                if (oy + 4 < y1) { load_x(oy + 8, xraw); load_g(oy + 4, graw); }
+                // rows of this block that exist as output rows: a byte of ones per row (input column sums)
+                const int nrow = min(4, y1 - oy);
+                const int ones = nrow >= 4 ? 0x01010101 : nrow == 3 ? 0x00010101 : nrow == 2 ? 0x00000101 : 0x00000001;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    gs[e] = __builtin_amdgcn_sdot4(gt[e], 0x01010101, gs[e], false);
+#pragma unroll
+                    for (int sx = 0; sx < 3; sx++) {
+                        const int top = (int)__builtin_amdgcn_alignbyte((unsigned)cur[sx][e], (unsigned)prev[sx][e], 3);   // rows oy-1 .. oy+2
+                        const int bot = (int)__builtin_amdgcn_alignbyte((unsigned)nxt[sx][e], (unsigned)cur[sx][e], 1);    // rows oy+1 .. oy+4
+                        acc[sx][e] = __builtin_amdgcn_sdot4(top, gt[e], acc[sx][e], false);
+                        acc[3 + sx][e] = __builtin_amdgcn_sdot4(cur[sx][e], gt[e], acc[3 + sx][e], false);
+                        acc[6 + sx][e] = __builtin_amdgcn_sdot4(bot, gt[e], acc[6 + sx][e], false);
+                        if (want_xsum) {
+                            xs[sx][e] = __builtin_amdgcn_sdot4(top, ones, xs[sx][e], false);
+                            xs[3 + sx][e] = __builtin_amdgcn_sdot4(cur[sx][e], ones, xs[3 + sx][e], false);
+                            xs[6 + sx][e] = __builtin_amdgcn_sdot4(bot, ones, xs[6 + sx][e], false);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int sx = 0; sx < 3; sx++)
+#pragma unroll
+                    for (int e = 0; e < 4; e++) { prev[sx][e] = cur[sx][e]; cur[sx][e] = nxt[sx][e]; }
             }
-#undef DWW_STEP
         }
 #pragma unroll
         for (int t = 0; t < 9; t++)
@@ -513,14 +546,15 @@ int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qpa
         d.X = X; d.G = dY; d.xq = xq; d.gq = gq; d.acc = a.acc; d.gsum = a.gsum; d.xsum = a.xsum;
         d.B = p->B; d.H = p->H; d.W = p->W; d.C = p->C;
         const int xb = (p->W * (p->C / 4) + HQ_THREADS - 1) / HQ_THREADS;
-        // about four workgroups per compute unit: strips of at least 6 rows, then images in turn
-        int strips = p->H / 6 > 0 ? p->H / 6 : 1;
+        // about four workgroups per compute unit: strips of at least 16 rows (a strip also reads the row
+        // above it and up to four rows below), then images in turn
+        int strips = p->H / 16 > 0 ? p->H / 16 : 1;
         while (strips > 1 && xb * strips > 1024) strips--;
         int rps = (p->H + strips - 1) / strips;
-        rps = (rps + 2) / 3 * 3;
+        rps = (rps + 3) / 4 * 4;
         d.rows_per_strip = rps;
         strips = (p->H + rps - 1) / rps;
-        int gz = 1024 / (xb * strips);
+        int gz = 768 / (xb * strips);
         if (gz < 1) gz = 1;
         if (gz > p->B) gz = p->B;
         hipLaunchKernelGGL(hq_dw3x3_wgrad_kernel, dim3((unsigned)xb, (unsigned)strips, (unsigned)gz), dim3(HQ_THREADS),
