@@ -115,12 +115,6 @@ struct Dw3Args {
     int rows_per_strip, flip;
 };
 
-__device__ inline void dw_unpack(int v, int *dst)
-{
-#pragma unroll
-    for (int e = 0; e < 4; e++) dst[e] = sbyte(v, e);
-}
-
 // Three packed words (four channels each of the pixels left, middle, right) -> four words, one per
 // channel, holding that channel's three horizontally adjacent values and a zero byte: the operand
 // of a 4-way byte dot product against the three taps of a filter row.
