@@ -177,6 +177,40 @@ def c5_step(hq, torch, wl, reps=3):
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb}}
 
 
+def range_tracking(hq, torch, lay, op, scales, report):
+    """How the in-hindsight range follows a tensor whose magnitude changes from one iteration to the
+    next (Sec. 4, eq. (2)-(3)): `op` ("fwd" or "dgrad") runs once per entry of `scales` with the
+    quantization scale of its data operand set to that entry (same codes, so the real-valued output
+    grows or shrinks by exactly that factor).  Iteration 0 sets the range from its own statistics;
+    every later one quantizes with the range it was handed and then updates it.  Reported for the
+    iterations in `report`: the share of outputs clipped, and the width of the range that was used
+    over the width of the tensor's own min / max."""
+    sym = op == "dgrad"
+    rng_, st = hq.new_range(0.9, sym), hq.new_stats(1)
+    keep = (lay.yr, lay.yst, lay.gr, lay.gst)
+    qp, run, dyn = (lay.gq, lay.dgrad, lay.dyn_dgrad) if sym else (lay.xq, lay.fwd, lay.dyn_fwd)
+    qp0 = qp.clone()
+    zp = int(hq.from_device(qp0, hq.QPARAMS)[0]["zero_point"])
+    if sym:
+        lay.gr, lay.gst = rng_, st
+    else:
+        lay.yr, lay.yst = rng_, st
+    rows = []
+    for t, sc in enumerate(scales):
+        qp.copy_(hq.new_qparams(sc, zp))
+        (dyn if t == 0 else run)()
+        hq.hq_stats_fold(st, 1)
+        s, r = hq.from_device(st, hq.STATS)[0], hq.from_device(rng_, hq.RANGE)[0]
+        if t in report:
+            true_w = (float(s["acc_max"]) - float(s["acc_min"])) * float(s["acc_scale"])
+            rows.append({"t": t, "clip_rate": float(s["clip_lo"] + s["clip_hi"]) / float(s["count"]),
+                         "range_over_minmax": (float(r["qmax"]) - float(r["qmin"])) / true_w if t else 1.0})
+        hq.hq_range_update(rng_, st)
+    qp.copy_(qp0)
+    lay.yr, lay.yst, lay.gr, lay.gst = keep
+    return rows
+
+
 def time_calls(torch, fn, reps, warmup=2):
     """Average milliseconds of fn() over `reps` back-to-back launches, HIP events on the launch stream."""
     for _ in range(warmup):
@@ -278,8 +312,15 @@ def main():
     names = {"fwd": "hq_band_kernel<64,3,2,8,1,fused> (forward)", "dgrad": "hq_band_kernel<64,3,2,8,1,fused> (dgrad)",
              "wgrad": "hq_wgrad_band_kernel + wband_finalize_kernel (one hq_gemm_wgrad call)"}
     achieved = ops_gemm / (dom_ms * 1e-3) / 1e12
+    # the int8 MFMA rate this device sustains in a register-only loop, next to the published peak
+    sink = torch.empty(2048 * 256, dtype=torch.int32, device="cuda")
+    probe_ops = hq.hq_probe_mfma_rate(2048, 512, sink)
+    probe_ms = time_calls(torch, lambda: hq.hq_probe_mfma_rate(2048, 4096, sink), 3, 1)
+    peak_measured = probe_ops * 8 / (probe_ms * 1e-3) / 1e12
+    del sink
     roofline = {"kernel": names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": achieved / PEAK_INT8_TOPS, "traffic": stored_traffic(dom),
+                "frac": achieved / PEAK_INT8_TOPS, "peak_measured": peak_measured,
+                "frac_of_measured": achieved / peak_measured, "traffic": stored_traffic(dom),
                 "algorithmic_bytes": wl.fused_bytes(L, dom), "avg_launch_ms": dom_ms,
                 "hbm_frac_of_8TBs": wl.fused_bytes(L, dom) / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
 
@@ -307,6 +348,10 @@ def main():
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb},
             "measured_hbm_bytes_per_step": stored_traffic("step")}
         lay.upd_y(); lay.upd_g()
+        # activations that grow 5 % per iteration (the range lags; eq. (2)-(3) settle at
+        # (1 - eta) / (1.05 - eta) = 2/3 of the tensor's width)
+        out["range_tracking"] = {"c2_fwd_growth_1.05_per_iter": range_tracking(
+            hq, torch, lay, "fwd", [float(X.scale) * 1.05 ** t for t in range(11)], range(11))}
 
         # ---- other layer shapes of the configurations (same kernels, single launches) ------
         extra = {}
@@ -328,6 +373,11 @@ def main():
                     row[op]["dynamic_ms"] = dms
                     row[op]["dynamic_alg_GBs"] = wl.dynamic_bytes(Ls, op) / (dms * 1e-3) / 1e9
             extra[name] = row
+            if name.startswith("c3"):
+                # gradients that decay 1 -> 1e-3 over 50 iterations: the range shrinks slower than the tensor
+                out["range_tracking"]["c3_dgrad_decay_1e-3_over_50_iters"] = range_tracking(
+                    hq, torch, ly, "dgrad", [1e-3 / 127.0 * wl.c3_grad_scale(t) for t in range(50)],
+                    (0, 1, 2, 5, 10, 20, 30, 40, 49))
             del ly
             torch.cuda.empty_cache()
         out["other_layers"] = extra

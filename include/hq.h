@@ -204,6 +204,13 @@ int hq_stats_fold(hq_stats *st, int32_t n, void *stream);
 int hq_weight_prepare(const hq_problem *p /* host */, const int8_t *W,
                       int8_t *Wd, int32_t *wsum, int32_t *wdsum, void *stream);
 
+/* Measurement aid, not part of the method: launches a kernel in which every wavefront issues
+ * iters * 8 int8 MFMAs (32x32x32, operands and accumulators in registers, no memory traffic
+ * except one 4-byte store per lane to sink [blocks * 256] at the end).  Timed by the caller, it
+ * gives the int8 MFMA rate this device sustains: blocks * 4 * iters * 8 * 2 * 32^3 operations.
+ * blocks in 1 .. 65536, iters in 1 .. 2^20.                                                   */
+int hq_probe_mfma_rate(int32_t blocks, int32_t iters, int32_t *sink, void *stream);
+
 /* Static text for a return code (host pointer, never NULL). */
 const char *hq_error_string(int code);
 

@@ -48,7 +48,8 @@ class HqError(RuntimeError):
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_wgrad", "hq_range_update",
            "hq_range_update_batch",
-           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_error_string")
+           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_probe_mfma_rate",
+           "hq_error_string")
 
 
 def lib():
@@ -73,6 +74,7 @@ def lib():
         L.hq_stats_reset.argtypes = [vp, C.c_int32, vp]
         L.hq_stats_fold.argtypes = [vp, C.c_int32, vp]
         L.hq_weight_prepare.argtypes = [PP, vp, vp, vp, vp, vp]
+        L.hq_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, vp, vp]
         for f in EXPORTS[1:-1]:
             getattr(L, f).restype = C.c_int
         _lib = L
@@ -144,6 +146,12 @@ def hq_stats_fold(st, n=1, stream=None):
 def hq_weight_prepare(p, W, Wd, wsum, wdsum, stream=None):
     _check("hq_weight_prepare", lib().hq_weight_prepare(C.byref(p), _ptr(W), _ptr(Wd), _ptr(wsum), _ptr(wdsum),
                                                         _stream(stream)))
+
+
+def hq_probe_mfma_rate(blocks, iters, sink, stream=None):
+    """Launches the register-only MFMA loop; returns the int8 operations it issues."""
+    _check("hq_probe_mfma_rate", lib().hq_probe_mfma_rate(blocks, iters, _ptr(sink), _stream(stream)))
+    return blocks * 4 * iters * 8 * 2 * 32 ** 3
 
 
 # ---------------------------------------------------------------------------

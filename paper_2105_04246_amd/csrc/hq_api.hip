@@ -174,6 +174,29 @@ size_t out_elems(const hq_problem *p, bool dgrad)
     return dgrad ? (size_t)p->B * p->H * p->W * p->C : (size_t)p->B * OH * OW * p->Cout;
 }
 
+// Register-only int8 MFMA loop: eight independent accumulator chains per wavefront, so that the
+// matrix pipeline never waits on a dependent result.
+__global__ __launch_bounds__(HQ_THREADS) void mfma_rate_kernel(int iters, int32_t *sink)
+{
+    const int tid = threadIdx.x;
+    v4i a = {tid, tid * 3, tid * 5, tid * 7}, b = {tid ^ 0x55, tid + 1, tid + 2, tid + 3};
+    v16i acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[j][e] = 0;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[j], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) s ^= acc[j][e];
+    sink[(size_t)blockIdx.x * HQ_THREADS + tid] = s;
+}
+
 } // namespace
 
 extern "C" {
@@ -324,6 +347,13 @@ int hq_weight_prepare(const hq_problem *p, const int8_t *W, int8_t *Wd, int32_t 
     if (wsum) hipLaunchKernelGGL(weight_rowsum_kernel, dim3((p->Cout + 3) / 4), dim3(256), 0, s, W, p->Cout, taps * p->C, wsum);
     if (wdsum) colsum(p->Cout, wdsum);
     if (Wd) hipLaunchKernelGGL(weight_relayout_kernel, dim3(1024), dim3(256), 0, s, W, p->Cout, taps, p->C, Wd);
+    return launch_status();
+}
+
+int hq_probe_mfma_rate(int32_t blocks, int32_t iters, int32_t *sink, void *stream)
+{
+    if (!sink || blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20)) return HQ_E_BADARG;
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(HQ_THREADS), 0, as_stream(stream), iters, sink);
     return launch_status();
 }
 

@@ -84,5 +84,6 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.hq_gemm_fwd(ctypes.byref(bad), *([nul] * 10)) == hq.HQ_E_BADSHAPE
     assert L.hq_gemm_fwd(ctypes.byref(good), *([nul] * 10)) == hq.HQ_E_BADARG
     assert L.hq_range_update(nul, nul, nul) == hq.HQ_E_BADARG
+    assert L.hq_probe_mfma_rate(4, 4, nul, nul) == hq.HQ_E_BADARG
     dw_bad = hq.problem(hq.HQ_DEPTHWISE, 1, 8, 8, 16, 3, 3, 1, 1, 32)
     assert L.hq_gemm_fwd(ctypes.byref(dw_bad), *([nul] * 10)) == hq.HQ_E_BADSHAPE

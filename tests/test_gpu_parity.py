@@ -263,6 +263,11 @@ def test_error_codes(H, hq):
     with pytest.raises(hq.HqError) as e:
         hq.hq_gemm_dynamic(7, 0, H.hq_problem(L), Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, r, out, outq, st, ws, 64)
     assert e.value.code == hq.HQ_E_BADARG
+    sink = torch.full((2 * 256,), 7, dtype=torch.int32, device="cuda")
+    assert hq.hq_probe_mfma_rate(2, 3, sink) == 2 * 4 * 3 * 8 * 2 * 32 ** 3
+    with pytest.raises(hq.HqError) as e:
+        hq.hq_probe_mfma_rate(0, 3, sink)
+    assert e.value.code == hq.HQ_E_BADARG
     lin_bad = hq.problem(hq.HQ_LINEAR, 8, 2, 1, 16, 1, 1, 1, 0, 16)
     assert hq.hq_workspace_bytes(hq.HQ_ENTRY_WGRAD, lin_bad) == 0
     torch.cuda.synchronize()
