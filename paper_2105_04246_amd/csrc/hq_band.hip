@@ -45,6 +45,7 @@ struct BandArgs {
     int Hs, Ws, Ho, Wo;            // source image, output image
     int stride, pad, flip;         // effective padding; flip = weight taps mirrored (dgrad)
     int PW, PRmax;                 // patch width (pixels), most patch rows any tile needs
+    int tail_patch;                // 1: the LDS holds a third patch, for a short last tile taken early
     int rows_per_band, bands_per_image;
     unsigned magic_Wo;             // ceil(2^32 / Wo)
     unsigned long long count;      // outputs of the whole tensor
@@ -76,7 +77,8 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
     int8_t *Wl = smem;                                     // [npad][TAPS][C], chunks swizzled
     int *bz = reinterpret_cast<int *>(smem + (size_t)a.npad * WROW);     // [npad]  z_a * bsum[n]
     int8_t *Pl = reinterpret_cast<int8_t *>(bz + a.npad);  // one patch per group [PRmax * PW][PP]
-    int *red = reinterpret_cast<int *>(Pl + NG * (size_t)patch_bytes);
+    int8_t *Pt = Pl + NG * (size_t)patch_bytes;            // patch of an early last tile (if a.tail_patch)
+    int *red = reinterpret_cast<int *>(Pl + (NG + a.tail_patch) * (size_t)patch_bytes);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = NG == 2 ? wave >> 2 : 0, gwave = wave & 3, gtid = tid & 255;
@@ -114,7 +116,8 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
     int pf_nrows = 0, pf_iy = 0;                           // rows of the patch being prefetched, its first input row
     auto prefetch_setup = [&](int tile) {
         const int ps = p0 + tile * BM;
-        const int oy0 = ps / a.Wo, oy1 = (min(ps + BM, p1) - 1) / a.Wo;
+        const int oy0 = (int)hq_magic_div((unsigned)ps, a.magic_Wo);
+        const int oy1 = (int)hq_magic_div((unsigned)(min(ps + BM, p1) - 1), a.magic_Wo);
         pf_nrows = (oy1 - oy0) * a.stride + KSZ;
         pf_iy = oy0 * a.stride - a.pad;
     };
@@ -134,41 +137,55 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
 #pragma unroll
         for (int k = 0; k < PR; k++) prefetch_row(k);
     };
-    auto stash = [&]() {
+    auto stash = [&](int8_t *dst) {
 #pragma unroll
         for (int k = 0; k < PR; k++)
 #pragma unroll
             for (int j = 0; j < PJ; j++)
                 if (k < a.PRmax && col_in[j])
-                    *reinterpret_cast<v4i *>(Pg + k * a.PW * PP + col_lds[j]) = pf[k][j];
+                    *reinterpret_cast<v4i *>(dst + k * a.PW * PP + col_lds[j]) = pf[k][j];
     };
 
     // ---- start-up: request the group's first patch and the weights before anything waits
-    if (grp < nitem) prefetch(grp / nchunk);
+    // A last tile that one wavefront covers does not get half steps of its own: the second group,
+    // which would idle through half step 0, multiplies and requantizes it there, from a patch
+    // buffer of its own (so that the group's first regular patch can be written meanwhile).
+    const bool early_tail = NG == 2 && a.tail_patch && nchunk == 1 && nitem >= 2 && (p1 - p0) - (ntile - 1) * BM <= 64;
+    const int nmain = early_tail ? nitem - 1 : nitem;      // items that take turns in the half steps
+    const bool tail_grp = early_tail && grp == 1;
+    if (tail_grp) {
+        prefetch(ntile - 1);
+        stash(Pt);
+    }
+    if (grp < nmain) prefetch(grp / nchunk);
+    // every workgroup copies the same weights: each starts at another place of the array, so that
+    // the workgroups of a launch do not walk the same cache lines in the same order
     constexpr int WB = 6;
     const int wchunks = a.npad * TAPS * NCH;
+    const int wrot = (int)(((blockIdx.x & 15u) * (unsigned)wchunks) >> 4) & ~7;
+    auto rotated = [&](int i) { const int r = i + wrot; return r >= wchunks ? r - wchunks : r; };
     for (int base = 0; base < wchunks; base += BAND_THREADS * WB) {
         v4i wv[WB];
 #pragma unroll
         for (int k = 0; k < WB; k++) {
-            const int idx = base + tid + BAND_THREADS * k;
+            const int lin = base + tid + BAND_THREADS * k, idx = rotated(lin);
             const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
             const int n = (row & ~31) + sigma32(row & 31);
             const int tsrc = a.flip ? TAPS - 1 - t : t;
             wv[k] = v4i{0, 0, 0, 0};
-            if (idx < wchunks && n < a.N)
+            if (lin < wchunks && n < a.N)
                 wv[k] = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
         }
 #pragma unroll
         for (int k = 0; k < WB; k++) {
-            const int idx = base + tid + BAND_THREADS * k;
+            const int lin = base + tid + BAND_THREADS * k, idx = rotated(lin);
             const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
-            if (idx < wchunks)
+            if (lin < wchunks)
                 *reinterpret_cast<v4i *>(Wl + row * WROW + t * C + 16 * (cq ^ wswz<C>(row & 31))) = wv[k];
         }
     }
     for (int n = tid; n < a.npad; n += BAND_THREADS) bz[n] = n < a.N ? za * a.bsum[n] : 0;
-    if (grp < nitem) stash();
+    if (grp < nmain && !tail_grp) stash(Pg);               // the tail group keeps its first patch in registers
     __syncthreads();
 
     // per-lane weight fragment addresses (row i = lane % 32 of each 32-row block)
@@ -186,51 +203,60 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
     bool ok[2] = {false, false};
     bool have_pf = false;
 
+    // -z_a * bsum[n] of the lane's 16 channels per column block: the matrix cores' first addend
+    v16i nbz[NT];
+    int nbz_chunk = -1;
+
     // Half step h: item h is multiplied (by group h & 1) while item h-1 goes through the
     // epilogue (in the other group, which multiplied it during half step h-1).
-    const int nhalf = NG == 2 ? nitem + 1 : 2 * nitem;
+    const int nhalf = NG == 2 ? nmain + 1 : 2 * nitem;
     for (int h = 0; h < nhalf; h++) {
-        const bool mfma_phase = NG == 2 ? (h & 1) == grp : (h & 1) == 0;
-        const int item = NG == 2 ? (mfma_phase ? h : h - 1) : h >> 1;       // this group's item in this half step
-        if (item >= 0 && item < nitem) {
-            const int tile = item / nchunk, nc = item - tile * nchunk;
+      const bool tail_now = tail_grp && h == 0;
+      const int8_t *Psrc = tail_now ? Pt : Pg;
+      for (int sub = 0; sub < (tail_now ? 2 : 1); sub++) {
+        const bool mfma_phase = tail_now ? sub == 0 : NG == 2 ? (h & 1) == grp : (h & 1) == 0;
+        // this group's item in this half step
+        const int item = tail_now ? nitem - 1 : NG == 2 ? (mfma_phase ? h : h - 1) : h >> 1;
+        if (item >= 0 && (item < nmain || tail_now)) {
+            const int tile = nchunk == 1 ? item : item / nchunk, nc = item - tile * nchunk;
             const int ps = p0 + tile * BM;
             if (mfma_phase) {
                 // -------------------------------------------------- matrix-core phase
+                if (tail_now && grp < nmain) stash(Pg);    // nobody reads this group's patch in this half step
                 const int nxt = item + NG;
-                have_pf = nxt < nitem && nxt / nchunk != tile;
+                have_pf = !tail_now && nxt < nmain && (nchunk == 1 || nxt / nchunk != tile);
                 const bool active = ps + gwave * 64 < p1;
                 // the next tile's patch rows are requested between the taps (a few per tap), where the
                 // wait for a slot in the memory pipeline overlaps the MFMAs already issued
                 constexpr int RPT = (PR + TAPS - 1) / TAPS;
                 if (have_pf) {
-                    prefetch_setup(nxt / nchunk);
+                    prefetch_setup(nchunk == 1 ? nxt : nxt / nchunk);
                     if (!active) {
 #pragma unroll
                         for (int k = 0; k < PR; k++) prefetch_row(k);
                     }
                 }
-                const int oy0 = ps / a.Wo;
+                const int oy0 = (int)hq_magic_div((unsigned)ps, a.magic_Wo);
                 int abase[2];
 #pragma unroll
                 for (int i = 0; i < 2; i++) {
                     const int p = ps + gwave * 64 + i * 32 + (lane & 31);
                     ok[i] = p < p1;
                     pix[i] = ok[i] ? p : ps;
-                    const int oy = (int)__umulhi((unsigned)pix[i], a.magic_Wo), ox = pix[i] - oy * a.Wo;
+                    const int oy = (int)hq_magic_div((unsigned)pix[i], a.magic_Wo), ox = pix[i] - oy * a.Wo;
                     abase[i] = (((oy - oy0) * a.stride) * a.PW + ox * a.stride) * PP + (lane >> 5) * 16;
                 }
-                // accumulators start at -z_a * bsum[n] (lane = 16 consecutive channels per column block)
+                if (nc != nbz_chunk) {
+                    nbz_chunk = nc;
 #pragma unroll
-                for (int j = 0; j < NT; j++)
+                    for (int j = 0; j < NT; j++)
 #pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        const v4i bzv = *reinterpret_cast<const v4i *>(bz + nc * BN + j * 32 + 16 * (lane >> 5) + 4 * g);   // < npad
+                        for (int g = 0; g < 4; g++) {
+                            const v4i bzv = *reinterpret_cast<const v4i *>(bz + nc * BN + j * 32 + 16 * (lane >> 5) + 4 * g);   // < npad
 #pragma unroll
-                        for (int i = 0; i < 2; i++)
-#pragma unroll
-                            for (int e = 0; e < 4; e++) acc[i][j][4 * g + e] = -bzv[e];
-                    }
+                            for (int e = 0; e < 4; e++) nbz[j][4 * g + e] = -bzv[e];
+                        }
+                }
                 if (active) {
                     // Fragments of tap t+1 are requested before the MFMAs of tap t are issued, so
                     // LDS latency hides behind the matrix cores (two register buffers).
@@ -245,24 +271,25 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
                                 wf[ks][j] = *reinterpret_cast<const v4i *>(Wc + wbase[j][ks] + t * C);
 #pragma unroll
                             for (int i = 0; i < 2; i++)
-                                af[ks][i] = *reinterpret_cast<const v4i *>(Pg + abase[i] + toff + ks * 32);
+                                af[ks][i] = *reinterpret_cast<const v4i *>(Psrc + abase[i] + toff + ks * 32);
                         }
                     };
-                    auto mfma_tap = [&](v4i (&wf)[KS][NT], v4i (&af)[KS][2]) {
+                    auto mfma_tap = [&](v4i (&wf)[KS][NT], v4i (&af)[KS][2], auto first) {
 #pragma unroll
                         for (int ks = 0; ks < KS; ks++)
 #pragma unroll
                             for (int i = 0; i < 2; i++)
 #pragma unroll
                                 for (int j = 0; j < NT; j++)
-                                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+                                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                                        wf[ks][j], af[ks][i], (decltype(first)::value && ks == 0) ? nbz[j] : acc[i][j], 0, 0, 0);
                     };
                     load_tap(0, wfA, afA);
 #pragma unroll
                     for (int t = 0; t < TAPS; t += 2) {
                         if (t + 1 < TAPS) load_tap(t + 1, wfB, afB);
                         __builtin_amdgcn_sched_barrier(0);
-                        mfma_tap(wfA, afA);
+                        if (t == 0) mfma_tap(wfA, afA, std::true_type()); else mfma_tap(wfA, afA, std::false_type());
                         __builtin_amdgcn_sched_barrier(0);
                         if (have_pf) {
 #pragma unroll
@@ -271,7 +298,7 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
                         if (t + 2 < TAPS) load_tap(t + 2, wfA, afA);
                         __builtin_amdgcn_sched_barrier(0);
                         if (t + 1 < TAPS) {
-                            mfma_tap(wfB, afB);
+                            mfma_tap(wfB, afB, std::false_type());
                             __builtin_amdgcn_sched_barrier(0);
                             if (have_pf) {
 #pragma unroll
@@ -283,7 +310,7 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
                 }
             } else {
                 // -------------------------------------------------- vector-ALU phase
-                if (have_pf) stash();                      // nobody reads this group's patch now
+                if (have_pf) stash(Pg);                    // nobody reads this group's patch now
                 auto epilogue = [&](auto full) {
                     constexpr bool FULL = decltype(full)::value;
 #pragma unroll
@@ -316,6 +343,7 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
                 if (ep.full_grid) epilogue(std::true_type()); else epilogue(std::false_type());
             }
         }
+      }
         __syncthreads();
     }
 
@@ -326,8 +354,6 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
         if (FUSED) *a.outq = a.range->qp;
     }
 }
-
-unsigned magic32(unsigned d) { return (unsigned)(((1ull << 32) + d - 1) / d); }
 
 constexpr size_t BAND_LDS_MAX = 160 * 1024;
 
@@ -415,8 +441,13 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
         if (ng == 2) break;
     }
     a.PRmax = prmax;
+    a.tail_patch = 0;
+    if (ng == 2 && lds + (size_t)prmax * a.PW * (C + 16) <= BAND_LDS_MAX) {
+        a.tail_patch = 1;
+        lds += (size_t)prmax * a.PW * (C + 16);
+    }
     if (lds > BAND_LDS_MAX) return HQ_E_BADSHAPE;
-    a.magic_Wo = magic32((unsigned)a.Wo);
+    a.magic_Wo = hq_magic32((unsigned)a.Wo);
     a.count = (unsigned long long)p->B * a.Ho * a.Wo * a.N;
     const int blocks = p->B * a.bands_per_image;
     if (C == 64) {

@@ -95,8 +95,8 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             for (int q0 = 0; q0 < a.patch_px * 4; q0 += HQ_THREADS) {
                 const int q = q0 + tid;
                 const int ppix = q >> 2, ck = (q & 3) ^ bw_swz(ppix);
-                const int il = (int)__umulhi((unsigned)ppix, a.magic_img), r1 = ppix - il * (a.PH * a.PW);
-                const int pr = (int)__umulhi((unsigned)r1, a.magic_PW), pc = r1 - pr * a.PW;
+                const int il = (int)hq_magic_div((unsigned)ppix, a.magic_img), r1 = ppix - il * (a.PH * a.PW);
+                const int pr = (int)hq_magic_div((unsigned)r1, a.magic_PW), pc = r1 - pr * a.PW;
                 const int iy = y0 + pr - a.pad, ix = pc - a.pad;
                 const bool inside = q < a.patch_px * 4 && il < timg && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
                 int8_t *dst = dstp + (size_t)(q0 + (tid & ~63)) * 16;   // this wavefront's 1 KiB
@@ -308,8 +308,8 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
     a.nchunks = (N + BW_BN - 1) / BW_BN;
     a.PH = a.rows + 2; a.PW = p->W + 2;
     a.patch_px = a.nimg * a.PH * a.PW;
-    a.magic_img = (unsigned)(((1ull << 32) + a.PH * a.PW - 1) / (a.PH * a.PW));
-    a.magic_PW = (unsigned)(((1ull << 32) + a.PW - 1) / a.PW);
+    a.magic_img = hq_magic32((unsigned)(a.PH * a.PW));
+    a.magic_PW = hq_magic32((unsigned)a.PW);
     a.count = (unsigned long long)p->B * p->H * p->W * N;
     const size_t patch_bytes = ((size_t)a.patch_px * BW_CK + 1023) & ~(size_t)1023;
     const size_t lds = 4 * BW_BN * BW_CK + 2 * patch_bytes + 4 * BW_BN + 64;

@@ -10,6 +10,11 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 #define HQ_THREADS 256                     // every compute kernel runs 4 wavefronts of 64 lanes
 
+// x / d by multiplication, for d >= 1 and x * d < 2^32: magic = (unsigned)ceil(2^32 / d), which for
+// d == 1 wraps to 0 and is then taken as "no division".  The host computes the constant.
+__host__ __device__ inline unsigned hq_magic32(unsigned d) { return (unsigned)(((1ull << 32) + d - 1) / d); }
+__device__ inline unsigned hq_magic_div(unsigned x, unsigned magic) { return magic ? __umulhi(x, magic) : x; }
+
 // ---------------------------------------------------------------------------------------
 // Quantizer arithmetic.  Each fp32 operation rounds once (no contraction), so that the
 // result is a function of the operands alone.

@@ -82,8 +82,8 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
             const int m = tile * (32 * DR_MI) + i * 32 + (lane & 31);
             const bool ok = tile < a.tiles && m < a.M;
             const unsigned mm = ok ? (unsigned)m : 0u;
-            const unsigned t = __umulhi(mm, a.magic_Wo), ox = mm - t * a.Wo;         // t = b * Ho + oy
-            const unsigned b = __umulhi(t, a.magic_Ho), oy = t - b * a.Ho;
+            const unsigned t = hq_magic_div(mm, a.magic_Wo), ox = mm - t * a.Wo;         // t = b * Ho + oy
+            const unsigned b = hq_magic_div(t, a.magic_Ho), oy = t - b * a.Ho;
             const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad + 4 * half;   // C == 4: tap = word
             const int8_t *p0 = a.A + ((size_t)b * a.H * a.W + ix0) * a.C;
             bool wok[4];
@@ -201,8 +201,9 @@ int hq_try_launch_direct(const hq_problem *p, int dgrad, const int8_t *A, const 
     a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
     a.M = p->B * OH * OW; a.N = p->Cout; a.C = p->C; a.R = p->R; a.S = p->S; a.H = p->H; a.W = p->W;
     a.Ho = OH; a.Wo = OW; a.stride = p->stride; a.pad = p->pad;
-    a.magic_Wo = (unsigned)(((1ull << 32) + OW - 1) / OW);
-    a.magic_Ho = (unsigned)(((1ull << 32) + OH - 1) / OH);
+    if ((unsigned long long)a.M * (unsigned long long)(OW > OH ? OW : OH) >= (1ull << 32)) return HQ_E_BADSHAPE;   // hq_magic_div's range
+    a.magic_Wo = hq_magic32((unsigned)OW);
+    a.magic_Ho = hq_magic32((unsigned)OH);
     a.tiles = (a.M + 32 * DR_MI - 1) / (32 * DR_MI);
     int blocks = (a.tiles + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;

@@ -48,7 +48,7 @@ struct GemmArgs {
     int cpt;                       // aligned: 16-byte chunks per tap = Cs / 16
     int nchunks;                   // 16-byte chunks of the reduction: taps * cpt, or ceil(taps * Cs / 16)
     int kcols;                     // taps * Cs
-    unsigned magic_Cs, magic_S;    // ceil(2^32 / d): x / d == umulhi(x, magic) for the small x used here
+    unsigned magic_Cs, magic_S;    // for hq_magic_div
     int taps, S;
     int Hs, Ws;                    // spatial size of the gathered tensor A
     int Ho, Wo;                    // spatial size the row index m runs over
@@ -257,8 +257,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
             for (int d = 0; d < 4; d++) {
                 const int kc = chunk * 16 + 4 * d;
                 dok[d] = kc < a.kcols;
-                const int t = (int)__umulhi((unsigned)kc, a.magic_Cs), cx = kc - t * a.Cs;
-                dr[d] = (int)__umulhi((unsigned)t, a.magic_S); ds[d] = t - dr[d] * a.S;
+                const int t = (int)hq_magic_div((unsigned)kc, a.magic_Cs), cx = kc - t * a.Cs;
+                dr[d] = (int)hq_magic_div((unsigned)t, a.magic_S); ds[d] = t - dr[d] * a.S;
                 doff[d] = cx;
                 dw[d] = (a.flip ? a.taps - 1 - t : t) * a.Cs + cx;
             }
@@ -518,8 +518,10 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
     a.kcols = a.taps * a.Cs;
     a.cpt = aligned ? a.Cs / 16 : 1;
     a.nchunks = aligned ? a.taps * a.cpt : (a.kcols + 15) / 16;
-    a.magic_Cs = (unsigned)(((1ull << 32) + a.Cs - 1) / a.Cs);
-    a.magic_S = (unsigned)(((1ull << 32) + a.S - 1) / a.S);
+    // (the 4-byte path divides reduction offsets by the channel count with hq_magic_div)
+    if (!aligned && (unsigned long long)a.kcols * (unsigned long long)a.Cs >= (1ull << 32)) return HQ_E_BADSHAPE;
+    a.magic_Cs = hq_magic32((unsigned)a.Cs);
+    a.magic_S = hq_magic32((unsigned)a.S);
     if (a.N > 64) {
         // 128-byte stages halve the barriers per tile; with enough tiles to keep three or more
         // workgroups on every compute unit, 64-byte stages (half the LDS, four resident workgroups)

@@ -76,6 +76,9 @@ SMALL = [
     wl.conv("bandw_rows", 2, 30, 192, 128, 3),       # ... tiles of rows, last tile of an image short; wgrad blocks 3 x 2
     wl.conv("first_layer", 2, 23, 4, 48, 7, stride=2),   # 4-channel first layer: direct kernel, ragged channel block, odd size
     wl.conv("c5x5_s3", 2, 17, 16, 32, 5, stride=3),  # stride 3: nine pixel classes in the input gradient
+    wl.conv("band_early_tail", 128, 24, 64, 64, 3),  # bands of 288 pixels: the 32-pixel last tile is taken in the first half step
+    wl.LayerShape("c2x1_s3", wl.CONV, 1, 2, 10, 4, 2, 1, 3, 0, 36),   # filter of width 1 and height 2 (division by 1 in the tap arithmetic)
+    wl.LayerShape("c1x3_w1", wl.CONV, 2, 9, 1, 16, 1, 1, 1, 0, 32),   # images one pixel wide
 ]
 
 
@@ -85,6 +88,62 @@ def test_small_shapes_all_ops(H, hq, L):
     Wdev = None
     for t in range(3):
         X, W, dY = rand_layer_inputs(L, 1000 + t)
+        if Wdev is None:
+            W0, Wdev = W, H.DevWeights(L, W)
+        Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+        y_track.step(L, "fwd", X, W0, Xd, Wdev)
+        g_track.step(L, "dgrad", dY, W0, dYd, Wdev)
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref)
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+
+
+def random_shapes(n, seed):
+    """Seeded random layer shapes inside the documented limits (channels % 4 == 0, pad < filter size,
+    at least one output pixel): non-square images and filters, strides 1..3, channel counts around the
+    kernels' tile sizes.  Small enough for the oracle."""
+    g = np.random.default_rng(seed)
+    chans = [4, 8, 12, 16, 20, 24, 32, 36, 48, 64, 64, 72, 96, 128, 128, 132, 192, 256]
+    shapes = []
+    while len(shapes) < n:
+        kind = g.choice([wl.CONV, wl.CONV, wl.CONV, wl.LINEAR, wl.DEPTHWISE])
+        i = len(shapes)
+        if kind == wl.LINEAR:
+            shapes.append(wl.LayerShape("rnd%d_lin" % i, wl.LINEAR, int(g.integers(1, 400)), 1, 1, int(g.choice(chans)) * int(g.integers(1, 3)),
+                                        1, 1, 1, 0, int(g.choice(chans))))
+            continue
+        R, S = (int(g.choice([1, 2, 3, 3, 3, 5])),) * 2 if g.random() < 0.7 else (int(g.integers(1, 5)), int(g.integers(1, 5)))
+        if kind == wl.DEPTHWISE:
+            R = S = 3
+        pad = int(g.integers(0, min(R, S)))
+        stride = int(g.choice([1, 1, 1, 2, 2, 3]))
+        Hh, Ww = int(g.integers(max(R - 2 * pad, 1), 26)), int(g.integers(max(S - 2 * pad, 1), 26))
+        C = int(g.choice(chans))
+        Cout = C if kind == wl.DEPTHWISE else int(g.choice(chans))
+        if kind == wl.DEPTHWISE and pad != 1:
+            pad = 1
+        B = int(g.integers(1, 5))
+        OH, OW = (Hh + 2 * pad - R) // stride + 1, (Ww + 2 * pad - S) // stride + 1
+        if OH < 1 or OW < 1 or B * OH * OW * Cout * R * S * (1 if kind == wl.DEPTHWISE else C) > 60e6:
+            continue
+        shapes.append(wl.LayerShape("rnd%d_%s" % (i, "dw" if kind == wl.DEPTHWISE else "conv"), int(kind), B, Hh, Ww, C, R, S,
+                                    stride, pad, Cout))
+    return shapes
+
+
+RANDOM = random_shapes(40, 20260) + random_shapes(50, 7)
+
+
+@pytest.mark.parametrize("L", RANDOM, ids=["%s_b%d_%dx%d_c%d_%dx%d_s%d_p%d_n%d" % (l.name, l.B, l.H, l.W, l.C, l.R, l.S, l.stride, l.pad, l.Cout)
+                                           for l in RANDOM])
+def test_random_shapes_all_ops(H, hq, L):
+    # every third shape with the zero point on the gradient side instead of the input side
+    swap = sum(map(ord, L.name)) % 3 == 0
+    y_track, g_track = H.TensorTrack(0.9, swap), H.TensorTrack(0.9, not swap)
+    Wdev = None
+    for t in range(2):
+        X, W, dY = rand_layer_inputs(L, 3000 + t, x_asym=not swap, g_asym=swap)
         if Wdev is None:
             W0, Wdev = W, H.DevWeights(L, W)
         Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
