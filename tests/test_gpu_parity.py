@@ -132,7 +132,44 @@ def random_shapes(n, seed):
     return shapes
 
 
-RANDOM = random_shapes(40, 20260) + random_shapes(50, 7)
+def random_fast_path_shapes(n, seed):
+    """Seeded random geometry for the shapes the specialised kernels take: 3x3 with 64 input channels
+    (weights in LDS, bands and tiles of all lengths), 1x1 with 32 / 192, 3x3 with 128+ channels on both
+    sides (streamed weights), 4-channel first layers, depthwise strips, and the banded weight gradient."""
+    g = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < n:
+        fam = int(g.integers(0, 6))
+        i = len(shapes)
+        B = int(g.choice([1, 2, 3, 5, 17, 64, 130, 257]))
+        Hh, Ww = int(g.integers(3, 41)), int(g.integers(3, 41))
+        if fam == 0:      # weights-resident 3x3
+            L = wl.LayerShape("fp%d_band3" % i, wl.CONV, B, Hh, Ww, 64, 3, 3, int(g.choice([1, 1, 2])), int(g.integers(0, 3)),
+                              16 * int(g.integers(1, 6)))
+        elif fam == 1:    # weights-resident 1x1
+            L = wl.LayerShape("fp%d_band1" % i, wl.CONV, B, Hh, Ww, int(g.choice([32, 192])), 1, 1, int(g.choice([1, 1, 2])), 0,
+                              16 * int(g.integers(1, 14)))
+        elif fam == 2:    # streamed weights
+            L = wl.LayerShape("fp%d_bandw" % i, wl.CONV, B, Hh, Ww, 64 * int(g.integers(2, 5)), 3, 3, 1, 1, 16 * int(g.integers(8, 17)))
+        elif fam == 3:    # first layer
+            S = int(g.integers(1, 9))
+            R = int(g.integers(1, 8))
+            L = wl.LayerShape("fp%d_first" % i, wl.CONV, B, Hh + 6, Ww + 6, 4, R, S, int(g.integers(1, 4)), int(g.integers(0, min(R, S))),
+                              16 * int(g.integers(1, 5)))
+        elif fam == 4:    # depthwise strips
+            L = wl.LayerShape("fp%d_dw" % i, wl.DEPTHWISE, B, Hh + 20, Ww + 20, 4 * int(g.integers(1, 81)), 3, 3, int(g.choice([1, 2])), 1, 0)
+            L = L._replace(Cout=L.C)
+        else:             # banded weight gradient (also 3x3 forward paths)
+            L = wl.LayerShape("fp%d_wband" % i, wl.CONV, B, Hh, Ww, 64 * int(g.integers(1, 4)), 3, 3, 1, 1, 64 * int(g.integers(1, 4)))
+        OH, OW = (L.H + 2 * L.pad - L.R) // L.stride + 1, (L.W + 2 * L.pad - L.S) // L.stride + 1
+        macs = L.B * OH * OW * L.Cout * L.R * L.S * (1 if L.kind == wl.DEPTHWISE else L.C)
+        if OH < 1 or OW < 1 or macs > 1.0e9 or L.B * L.H * L.W * L.C > 3e7:
+            continue
+        shapes.append(L)
+    return shapes
+
+
+RANDOM = random_shapes(40, 20260) + random_shapes(50, 7) + random_fast_path_shapes(48, 11)
 
 
 @pytest.mark.parametrize("L", RANDOM, ids=["%s_b%d_%dx%d_c%d_%dx%d_s%d_p%d_n%d" % (l.name, l.B, l.H, l.W, l.C, l.R, l.S, l.stride, l.pad, l.Cout)
