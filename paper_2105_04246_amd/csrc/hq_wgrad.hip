@@ -467,32 +467,32 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
                     xf[u] = v4i{lo[0], lo[1], hi[0], hi[1]};
                 }
             }
+            // the column sums ride behind the MFMAs of their own fragment (four dot products per tap, in the
+            // shadow of the matrix cores); issued after all ten MFMAs they would hold up the next k-step
 #pragma unroll
             for (int u = 0; u < 5; u++) {
                 if (u < nt) {
 #pragma unroll
                     for (int i = 0; i < 2; i++)
                         acc[i][u] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gf[i], xf[u], acc[i][u], 0, 0, 0);
-                }
-            }
-            if (do_gsum) {
-#pragma unroll
-                for (int i = 0; i < 2; i++)
-#pragma unroll
-                    for (int d = 0; d < 4; d++) gsv[i] = __builtin_amdgcn_sdot4(gf[i][d], 0x01010101, gsv[i], false);
-            }
-            if (do_xsum) {
-#pragma unroll
-                for (int u = 0; u < 5; u++) {
-                    if (u < nt) {
+                    if (do_xsum) {
 #pragma unroll
                         for (int d = 0; d < 4; d++) xsv[u] = __builtin_amdgcn_sdot4(xf[u][d], 0x01010101, xsv[u], false);
-                        // the last k-step read patch row 0 for its `ninv` pixels past the band: take that back
-                        if (ninv > 0 && ks == nks - 1 && lane < 32)
-                            xsv[u] -= ninv * (int)xb[tapoff[u] - fcol + (lane & 31)];
+                    }
+                    if (do_gsum && u < 2) {
+#pragma unroll
+                        for (int d = 0; d < 4; d++) gsv[u] = __builtin_amdgcn_sdot4(gf[u][d], 0x01010101, gsv[u], false);
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+        // the band's last k-step read patch row 0 for its `ninv` pixels past the band: take that back
+        // (in the group that took that k-step)
+        if (do_xsum && ninv > 0 && ((nks - 1 - grp - it) & 1) == 0 && lane < 32) {
+#pragma unroll
+            for (int u = 0; u < 5; u++)
+                if (u < nt) xsv[u] -= ninv * (int)xb[tapoff[u] - fcol + (lane & 31)];
         }
         if (more) store_stage(buf ^ 1);
         __syncthreads();
