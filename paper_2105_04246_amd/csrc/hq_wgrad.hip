@@ -107,8 +107,9 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     const int m_end = min(a.M, m_begin + a.m_per_split);
     const int zx = a.xq->zero_point;
     const int fill = (zx & 0xff) * 0x01010101;
-    const bool do_gsum = bx == 0 && wk == 0;     // column sums of G: first tile column
-    const bool do_xsum = by == 0 && wn == 0;     // column sums of Xg: first tile row
+    // (a column sum is only ever multiplied by the other operand's zero point: not formed when that is 0)
+    const bool do_gsum = bx == 0 && wk == 0 && zx != 0;                      // column sums of G: first tile column
+    const bool do_xsum = by == 0 && wn == 0 && a.gq->zero_point != 0;        // column sums of Xg: first tile row
 
     int pk_r[4], pk_s[4], pk_off[4], pk_ow[XLD], pk_oh[XLD], pk_b[XLD];
     if (PACKED) {
@@ -296,7 +297,7 @@ constexpr int WB_SUMS = 64 + 9 * 64;          // column sums a group of a workgr
 
 struct WbandArgs {
     const int8_t *X, *G;
-    const hq_qparams *xq;
+    const hq_qparams *xq, *gq;
     int32_t *partial;              // [slot][WB_SLOT_V4] 16-byte words: this workgroup's 64 x 9 x 64 sums
     int32_t *sums;                 // [slot][2 groups][64 + 9 * 64]: column sums of dY and of the input taps
     int B, H, W, C, N;
@@ -339,8 +340,10 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
     const int s_begin = split * a.stages_per_block, s_end = min(a.nstages, s_begin + a.stages_per_block);
     const int zx = a.xq->zero_point;
     const int fillw = (zx & 0xff) * 0x01010101;
-    const bool do_gsum = cp == 0 && cblk == 0 && th == 0;
-    const bool do_xsum = np == 0;
+    // a column sum is only ever multiplied by the other operand's zero point (the finalize kernel's
+    // correction terms): with that zero point at 0 it is not formed at all
+    const bool do_gsum = cp == 0 && cblk == 0 && th == 0 && zx != 0;
+    const bool do_xsum = np == 0 && a.gq->zero_point != 0;
 
     // ---- per-thread staging plan (the same for every band)
     int x_rel[WB_XLD], x_rowimg[WB_XLD];                 // source offset; patch row | image << 16
@@ -685,7 +688,7 @@ bool launch_wgrad_band(const hq_problem *p, const WbandPlan &pl, const WgradArgs
                        hipStream_t stream)
 {
     WbandArgs a;
-    a.X = w.X; a.G = w.G; a.xq = w.xq; a.partial = partial; a.sums = sums;
+    a.X = w.X; a.G = w.G; a.xq = w.xq; a.gq = w.gq; a.partial = partial; a.sums = sums;
     a.B = p->B; a.H = p->H; a.W = p->W; a.C = p->C; a.N = p->Cout;
     a.rows = pl.rows; a.nimg = pl.nimg;
     a.bands_per_img = p->H / pl.rows;
