@@ -57,7 +57,7 @@ __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4
 
 template <int C> __device__ inline int wswz(int i)
 {
-    return (C % 128 == 0) ? (i & 7) : (C % 64 == 0) ? ((i >> 1) & 3) : ((i >> 2) & 1);
+    return (C % 128 == 0) ? (i & 7) : (C % 64 == 0) ? ((i >> 2) & 3) : ((i >> 3) & 1);
 }
 
 // PR: patch rows prefetched per tile (>= PRmax), PJ: 16-byte column chunks per thread and row.
