@@ -47,7 +47,7 @@ struct BandwArgs {
 };
 
 __device__ inline int bw_sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
-__device__ inline int bw_swz(int row) { return (row >> 1) & 3; }
+__device__ inline int bw_swz(int row) { return (row >> 2) & 3; }
 
 template <bool FUSED>
 __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs a)

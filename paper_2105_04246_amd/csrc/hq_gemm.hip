@@ -195,7 +195,7 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
     // index, which keeps the fragment reads free of bank conflicts without padding.  The LDS slot of
     // a thread is fixed (slot = thread: that is where a direct-to-LDS load of lane l lands), so the
     // swizzle is applied to the chunk the thread fetches instead.
-    auto swz = [](int row) { return CPS == 8 ? (row & 7) : ((row >> 1) & (CPS - 1)); };
+    auto swz = [](int row) { return CPS == 8 ? ((row >> 1) & 7) : ((row >> 2) & (CPS - 1)); };
     const int csrc = ALIGNED ? (cc ^ swz(lrow)) : cc;
     int chunk = csrc, c16 = csrc % a.cpt, tap = csrc / a.cpt;
     const int tapw = CLASSED ? ns : a.S;             // taps per row of the tap grid the chunks run over
