@@ -83,6 +83,40 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = NG == 2 ? wave >> 2 : 0, gwave = wave & 3, gtid = tid & 255;
     int8_t *Pg = Pl + grp * patch_bytes;                   // this group's patch
+
+    // ---- start-up, part 1: everything that does not depend on other loads is requested before anything
+    // waits (the first pass of the weight copy, the weight sums, then the scalars below), so that the
+    // memory round trips of the start-up overlap instead of following one another.
+    // Every workgroup copies the same weights: each starts at another place of the array, so that
+    // the workgroups of a launch do not walk the same cache lines in the same order.
+    constexpr int WB = 6;
+    const int wchunks = a.npad * TAPS * NCH;
+    const int wrot = (int)(((blockIdx.x & 15u) * (unsigned)wchunks) >> 4) & ~7;
+    auto rotated = [&](int i) { const int r = i + wrot; return r >= wchunks ? r - wchunks : r; };
+    auto wload = [&](int base, v4i (&wv)[WB]) {
+#pragma unroll
+        for (int k = 0; k < WB; k++) {
+            const int lin = base + tid + BAND_THREADS * k, idx = rotated(lin);
+            const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
+            const int n = (row & ~31) + sigma32(row & 31);
+            const int tsrc = a.flip ? TAPS - 1 - t : t;
+            wv[k] = v4i{0, 0, 0, 0};
+            if (lin < wchunks && n < a.N)
+                wv[k] = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
+        }
+    };
+    auto wstore = [&](int base, const v4i (&wv)[WB]) {
+#pragma unroll
+        for (int k = 0; k < WB; k++) {
+            const int lin = base + tid + BAND_THREADS * k, idx = rotated(lin);
+            const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
+            if (lin < wchunks)
+                *reinterpret_cast<v4i *>(Wl + row * WROW + t * C + 16 * (cq ^ wswz<C>(row & 31))) = wv[k];
+        }
+    };
+    v4i wv0[WB];
+    wload(0, wv0);
+    const int bs0 = tid < a.N ? a.bsum[tid] : 0;
     const int za = a.aq->zero_point;
     const int fillw = (za & 0xff) * 0x01010101;
     const v4i fill = {fillw, fillw, fillw, fillw};
@@ -158,33 +192,14 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
         stash(Pt);
     }
     if (grp < nmain) prefetch(grp / nchunk);
-    // every workgroup copies the same weights: each starts at another place of the array, so that
-    // the workgroups of a launch do not walk the same cache lines in the same order
-    constexpr int WB = 6;
-    const int wchunks = a.npad * TAPS * NCH;
-    const int wrot = (int)(((blockIdx.x & 15u) * (unsigned)wchunks) >> 4) & ~7;
-    auto rotated = [&](int i) { const int r = i + wrot; return r >= wchunks ? r - wchunks : r; };
-    for (int base = 0; base < wchunks; base += BAND_THREADS * WB) {
+    wstore(0, wv0);
+    for (int base = BAND_THREADS * WB; base < wchunks; base += BAND_THREADS * WB) {
         v4i wv[WB];
-#pragma unroll
-        for (int k = 0; k < WB; k++) {
-            const int lin = base + tid + BAND_THREADS * k, idx = rotated(lin);
-            const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
-            const int n = (row & ~31) + sigma32(row & 31);
-            const int tsrc = a.flip ? TAPS - 1 - t : t;
-            wv[k] = v4i{0, 0, 0, 0};
-            if (lin < wchunks && n < a.N)
-                wv[k] = *reinterpret_cast<const v4i *>(a.Bw + ((size_t)n * TAPS + tsrc) * C + cq * 16);
-        }
-#pragma unroll
-        for (int k = 0; k < WB; k++) {
-            const int lin = base + tid + BAND_THREADS * k, idx = rotated(lin);
-            const int cq = idx % NCH, t = (idx / NCH) % TAPS, row = idx / (NCH * TAPS);
-            if (lin < wchunks)
-                *reinterpret_cast<v4i *>(Wl + row * WROW + t * C + 16 * (cq ^ wswz<C>(row & 31))) = wv[k];
-        }
+        wload(base, wv);
+        wstore(base, wv);
     }
-    for (int n = tid; n < a.npad; n += BAND_THREADS) bz[n] = n < a.N ? za * a.bsum[n] : 0;
+    if (tid < a.npad) bz[tid] = za * bs0;
+    for (int n = tid + BAND_THREADS; n < a.npad; n += BAND_THREADS) bz[n] = n < a.N ? za * a.bsum[n] : 0;
     if (grp < nmain && !tail_grp) stash(Pg);               // the tail group keeps its first patch in registers
     __syncthreads();
 
