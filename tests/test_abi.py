@@ -85,5 +85,15 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.hq_gemm_fwd(ctypes.byref(good), *([nul] * 10)) == hq.HQ_E_BADARG
     assert L.hq_range_update(nul, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_probe_mfma_rate(4, 4, nul, nul) == hq.HQ_E_BADARG
+    # sizes past the documented maxima (31-bit pixel and weight counts, 32-bit byte offsets) are refused
+    for huge in (hq.problem(hq.HQ_CONV2D, 1 << 20, 64, 64, 16, 3, 3, 1, 1, 16),          # B*H*W = 2^32
+                 hq.problem(hq.HQ_CONV2D, 1 << 16, 64, 64, 64, 1, 1, 1, 0, 4),           # B*H*W*C = 2^34 bytes
+                 hq.problem(hq.HQ_LINEAR, 4, 1, 1, 1 << 16, 1, 1, 1, 0, 1 << 15),        # C*Cout = 2^31 weights
+                 hq.problem(hq.HQ_CONV2D, 0, 8, 8, 16, 3, 3, 1, 1, 16),                  # empty batch
+                 hq.problem(hq.HQ_CONV2D, 1, 2, 2, 16, 5, 5, 1, 1, 16),                  # no output pixel
+                 hq.problem(hq.HQ_CONV2D, 1, 8, 8, 16, 3, 3, 1, 3, 16)):                 # padding >= filter size
+        assert L.hq_gemm_fwd(ctypes.byref(huge), *([nul] * 10)) == hq.HQ_E_BADSHAPE
+        assert L.hq_gemm_dgrad(ctypes.byref(huge), *([nul] * 10)) == hq.HQ_E_BADSHAPE
+        assert hq.hq_workspace_bytes(hq.HQ_ENTRY_WGRAD, huge) == 0
     dw_bad = hq.problem(hq.HQ_DEPTHWISE, 1, 8, 8, 16, 3, 3, 1, 1, 32)
     assert L.hq_gemm_fwd(ctypes.byref(dw_bad), *([nul] * 10)) == hq.HQ_E_BADSHAPE

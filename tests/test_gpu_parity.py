@@ -332,6 +332,59 @@ def test_repeat_runs_are_bit_identical(H, hq):
 
 
 # ---------------------------------------------------------------------------------------
+# Degenerate tensors and ranges
+# ---------------------------------------------------------------------------------------
+def _const_tensor(shape, code, scale, zp):
+    from collections import namedtuple
+    Q = namedtuple("Q", "codes scale zero_point")
+    return Q(np.full(shape, code, dtype=np.int8), np.float32(scale), int(zp))
+
+
+@pytest.mark.parametrize("L", [wl.conv("deg_band", 2, 20, 64, 64, 3), wl.conv("deg_gemm", 2, 9, 24, 40, 3),
+                               wl.conv("deg_bandw", 1, 12, 128, 128, 3), wl.depthwise("deg_dw", 1, 10, 32),
+                               wl.linear("deg_lin1", 1, 4, 4)], ids=lambda l: l.name)
+def test_degenerate_tensors(H, hq, L):
+    """All-zero tensors (the range collapses to a point and the quantizer falls back to scale 1),
+    then extreme codes on both operands (largest accumulators, one-sided ranges), then an ordinary
+    tensor quantized with the collapsed / one-sided range it inherits (everything clips)."""
+    g = np.random.default_rng(12)
+    W = wl.he_weight(g, L)
+    Wmax = W._replace(codes=np.where(g.random(W.codes.shape) < 0.5, 127, -127).astype(np.int8))
+    for Wq in (W, Wmax):
+        Wdev = H.DevWeights(L, Wq)
+        y_track, g_track = H.TensorTrack(0.9, False), H.TensorTrack(0.9, True)
+        X_seq = [_const_tensor(wl.in_shape(L), -128, 0.02, -128),          # real zeros on the unsigned grid
+                 _const_tensor(wl.in_shape(L), -128, 0.02, -128),          # again: fused path with the collapsed range
+                 _const_tensor(wl.in_shape(L), 127, 0.02, -128),           # every input at the top code
+                 wl.relu_activation(g, wl.in_shape(L))]
+        G_seq = [_const_tensor(wl.out_shape(L), 0, 1e-4, 0), _const_tensor(wl.out_shape(L), 0, 1e-4, 0),
+                 _const_tensor(wl.out_shape(L), -127, 1e-4, 0), wl.laplace_gradient(g, wl.out_shape(L), 1e-3)]
+        for X, dY in zip(X_seq, G_seq):
+            Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+            y_track.step(L, "fwd", X, Wq, Xd, Wdev)
+            g_track.step(L, "dgrad", dY, Wq, dYd, Wdev)
+            dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+            ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+            assert np.array_equal(dWa, ref)
+            assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+
+
+@pytest.mark.parametrize("eta", [0.0, 1.0, 0.5])
+def test_special_momenta_on_device(H, hq, eta):
+    """Eq. (2)-(3) with eta = 0 (the range is last iteration's min-max), eta = 1 (the range never
+    moves after its initialisation) and 0.5, over a tensor that grows 1.6x per iteration."""
+    L = wl.conv("eta", 2, 12, 32, 32, 3)
+    W = wl.he_weight(np.random.default_rng(2), L)
+    Wdev = H.DevWeights(L, W)
+    y_track = H.TensorTrack(eta, False)
+    for t in range(4):
+        X = wl.relu_activation(np.random.default_rng(20 + t), wl.in_shape(L), gain=1.6 ** t)
+        _, ref = y_track.step(L, "fwd", X, W, H.DevTensor(X), Wdev)
+        if t >= 2 and eta > 0.0:
+            assert ref["clip_hi"] > 0                     # the lagging range clips the grown tensor
+
+
+# ---------------------------------------------------------------------------------------
 # Error behaviour (nothing is launched on error)
 # ---------------------------------------------------------------------------------------
 def test_error_codes(H, hq):
