@@ -83,6 +83,10 @@ def lib():
                                   C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.hqo_requant.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, C.c_int, C.c_int, C.c_int,
                                   i8p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.hqo_requant_sr.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, C.c_int, C.c_int, C.c_int,
+                                     C.c_uint64, C.c_uint64, i8p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.hqo_sr_bits.argtypes = [C.c_uint64, C.c_uint64]
+        L.hqo_sr_bits.restype = C.c_uint32
         L.hqo_range_update.argtypes = [C.POINTER(Range), C.c_int32, C.c_int32, C.c_float]
         L.hqo_wgrad_scale.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, f32p]
         for f in ("hqo_fwd", "hqo_fwd_rows", "hqo_dgrad", "hqo_dgrad_rows", "hqo_wgrad"):
@@ -178,6 +182,22 @@ def requant(c, acc_scale, s_y, z_y, qlo, qhi):
     return out, lo.value, hi.value
 
 
+def sr_bits(idx, seed):
+    """The 32 random bits stochastic rounding draws for element ``idx`` under ``seed``."""
+    return int(lib().hqo_sr_bits(int(idx), int(seed)))
+
+
+def requant_stochastic(c, acc_scale, s_y, z_y, qlo, qhi, seed, idx0=0):
+    """Static quantization with stochastic rounding (Sec. 5, experimental setup); element i of
+    the flattened tensor draws its random bits from (idx0 + i, seed).  Returns (codes, clip_lo, clip_hi)."""
+    c = np.ascontiguousarray(c, np.int32)
+    out = np.empty(c.shape, np.int8)
+    lo, hi = C.c_uint64(), C.c_uint64()
+    lib().hqo_requant_sr(_p(c, C.c_int32), c.size, float(acc_scale), float(s_y), int(z_y), int(qlo), int(qhi),
+                         int(idx0), int(seed), _p(out, C.c_int8), C.byref(lo), C.byref(hi))
+    return out, lo.value, hi.value
+
+
 def range_update(r, acc_min, acc_max, acc_scale):
     """eq. (2)-(3) in place on ``r``; the first call sets q^0."""
     lib().hqo_range_update(C.byref(r), int(acc_min), int(acc_max), float(acc_scale))
@@ -201,12 +221,16 @@ def acc_scale(sa, sb):
 # in-hindsight step built on the static one (Sec. 4.1).
 # ---------------------------------------------------------------------------
 
-def quantize_static(c, a_scale, r):
+def quantize_static(c, a_scale, r, seed=None):
     """Static quantization with the pre-computed range held in ``r`` (step 1 of Sec. 4);
-    the statistics of the current tensor are gathered on the side (step 2).
+    the statistics of the current tensor are gathered on the side (step 2).  With a ``seed``
+    the rounding is stochastic (gradients, Sec. 5), otherwise to nearest even.
     Returns dict(codes, scale, zero_point, acc_min, acc_max, clip_lo, clip_hi, count)."""
     mn, mx = minmax(c)
-    codes, lo, hi = requant(c, a_scale, r.scale, r.zero_point, r.qlo, r.qhi)
+    if seed is None:
+        codes, lo, hi = requant(c, a_scale, r.scale, r.zero_point, r.qlo, r.qhi)
+    else:
+        codes, lo, hi = requant_stochastic(c, a_scale, r.scale, r.zero_point, r.qlo, r.qhi, seed)
     return dict(codes=codes, scale=np.float32(r.scale), zero_point=r.zero_point,
                 acc_min=mn, acc_max=mx, clip_lo=lo, clip_hi=hi, count=c.size)
 
@@ -222,7 +246,7 @@ def quantize_dynamic(c, a_scale, symmetric, qlo, qhi):
                 clip_lo=lo, clip_hi=hi, count=c.size)
 
 
-def in_hindsight_step(c, a_scale, r):
+def in_hindsight_step(c, a_scale, r, seed=None):
     """One iteration of in-hindsight min-max for one tensor (Sec. 4.1).
 
     t = 0 (``r`` not initialised): the range of the first batch is its own min-max,
@@ -233,6 +257,6 @@ def in_hindsight_step(c, a_scale, r):
         out = quantize_dynamic(c, a_scale, r.symmetric, r.qlo, r.qhi)
         range_update(r, out["acc_min"], out["acc_max"], a_scale)      # sets q^0
     else:
-        out = quantize_static(c, a_scale, r)
+        out = quantize_static(c, a_scale, r, seed)
     range_update(r, out["acc_min"], out["acc_max"], a_scale)          # q^{t+1}
     return out

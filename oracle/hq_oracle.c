@@ -297,6 +297,46 @@ void hqo_requant(const int32_t *c, int64_t n, float acc_scale, float s_y, int z_
     *clip_lo = nlo; *clip_hi = nhi;
 }
 
+/* Random bits for stochastic rounding: a counter-based generator, so that any implementation
+ * reproduces the same decision for the same (element index, seed).  The low index word goes
+ * through the finalizer of MurmurHash3 (two multiply / xor-shift rounds); between its rounds the
+ * first key word is added and the high index word (times an odd constant) plus the second key word
+ * are folded in; a third multiply (golden-ratio constant) / xor-shift closes.  The key enters after
+ * a non-linear step, so two seeds do not give the same stream with relabelled elements.       */
+uint32_t hqo_sr_bits(uint64_t idx, uint64_t seed)
+{
+    uint32_t h = (uint32_t)idx;
+    h ^= h >> 16; h *= 0x85ebca6bu; h += (uint32_t)seed;
+    h ^= (uint32_t)(idx >> 32) * 0x85ebca77u + (uint32_t)(seed >> 32);
+    h ^= h >> 13; h *= 0xc2b2ae35u; h ^= h >> 16;
+    h *= 0x9e3779b1u; h ^= h >> 15;
+    return h;
+}
+
+/* Static quantization with stochastic rounding (the paper quantizes gradients this way, Sec. 5
+ * experimental setup, after Gupta et al. 2015): x = fp32(c) * m as in hqo_requant, then x is
+ * rounded up with probability x - floor(x) and down otherwise: up iff the fraction exceeds
+ * u = (top 24 random bits) / 2^24, the draw of element i being hqo_sr_bits(idx0 + i, seed).
+ * Clamping and clip counting as in hqo_requant, on the rounded value.                        */
+void hqo_requant_sr(const int32_t *c, int64_t n, float acc_scale, float s_y, int z_y, int qlo, int qhi,
+                    uint64_t idx0, uint64_t seed, int8_t *out, uint64_t *clip_lo, uint64_t *clip_hi)
+{
+    float m = acc_scale / s_y;
+    float flo = (float)(qlo - z_y), fhi = (float)(qhi - z_y);
+    uint64_t nlo = 0, nhi = 0;
+    for (int64_t i = 0; i < n; i++) {
+        float x = (float)c[i] * m;
+        float f = floorf(x);
+        float frac = x - f;                                  /* exact */
+        float u = (float)(hqo_sr_bits(idx0 + (uint64_t)i, seed) >> 8) * (1.0f / 16777216.0f);
+        float r = frac > u ? f + 1.0f : f;
+        if (r < flo) { r = flo; nlo++; }
+        if (r > fhi) { r = fhi; nhi++; }
+        out[i] = (int8_t)((int)r + z_y);
+    }
+    *clip_lo = nlo; *clip_hi = nhi;
+}
+
 /* In-hindsight min-max, eq. (2)-(3); first call sets q^0 (Sec. 4.1).         */
 void hqo_range_update(hqo_range *r, int32_t acc_min, int32_t acc_max, float acc_scale)
 {

@@ -391,6 +391,113 @@ def test_in_hindsight_sequence_uses_previous_range():
     assert abs(hist[-1][0] - q) <= 1e-5 * abs(q)
 
 
+# ---------------------------------------------------------------------------------------
+# Stochastic rounding (the paper's gradient quantizer, Sec. 5 experimental setup)
+# ---------------------------------------------------------------------------------------
+def _py_sr_bits(idx, seed):
+    """The generator in Python integers, 32-bit wrap-around written out."""
+    M = 0xffffffff
+    h = idx & M
+    h ^= h >> 16; h = (h * 0x85ebca6b) & M; h = (h + (seed & M)) & M
+    h ^= (((idx >> 32) & M) * 0x85ebca77 + ((seed >> 32) & M)) & M
+    h ^= h >> 13; h = (h * 0xc2b2ae35) & M; h ^= h >> 16
+    h = (h * 0x9e3779b1) & M; h ^= h >> 15
+    return h
+
+
+def test_sr_bits_match_integer_arithmetic_and_depend_on_every_input():
+    g = np.random.default_rng(5)
+    for _ in range(200):
+        idx, seed = int(g.integers(0, 2**63)), int(g.integers(0, 2**63))
+        assert oracle.sr_bits(idx, seed) == _py_sr_bits(idx, seed)
+    # flipping any single bit of the index or the seed flips about half of the output bits
+    flips = []
+    for bit in range(64):
+        for which in range(2):
+            d = []
+            for k in range(64):
+                idx, seed = int(g.integers(0, 2**63)), int(g.integers(0, 2**63))
+                a = oracle.sr_bits(idx, seed)
+                b = oracle.sr_bits(idx ^ (1 << bit), seed) if which == 0 else oracle.sr_bits(idx, seed ^ (1 << bit))
+                d.append(bin(a ^ b).count("1"))
+            flips.append(np.mean(d))
+    assert min(flips) > 11.0 and max(flips) < 21.0, (min(flips), max(flips))
+
+
+def test_sr_bits_are_uniform_over_consecutive_elements():
+    """What the rounding uses: the top 24 bits of consecutive element indices.  Chi-square over
+    256 equal bins, lag-1 correlation, and independence of two seeds' streams."""
+    n = 1 << 16
+    for seed in (0, 1, 0xdeadbeefcafe):
+        u = np.array([oracle.sr_bits(i, seed) >> 8 for i in range(n)], dtype=np.float64) / 2.0**24
+        counts = np.bincount((u * 256).astype(int), minlength=256)
+        chi2 = float(((counts - n / 256) ** 2 / (n / 256)).sum())
+        assert chi2 < 360.0, (seed, chi2)                   # 255 dof: mean 255, sd 22.6
+        assert abs(u.mean() - 0.5) < 4 * (1 / 12 / n) ** 0.5
+        assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.02
+    a = np.array([oracle.sr_bits(i, 7) >> 8 for i in range(n)], dtype=np.float64)
+    b = np.array([oracle.sr_bits(i, 8) >> 8 for i in range(n)], dtype=np.float64)
+    assert abs(np.corrcoef(a, b)[0, 1]) < 0.02
+
+
+def test_stochastic_rounding_is_a_floor_or_ceil_and_unbiased():
+    """Gupta et al. (2015) as the paper uses it: x rounds up with probability x - floor(x).  Every
+    code is floor(x) or floor(x) + 1, whole numbers are kept, the mean over many draws is x, and the
+    share of round-ups follows the fraction (so the comparison is the right way round)."""
+    n = 200000
+    for c_val, a_scale, s_y in ((7, 0.3, 1.0), (-7, 0.3, 1.0), (3, 0.25, 1.0), (-3, 0.25, 1.0), (9, 0.1, 1.0), (40, 0.5, 2.0)):
+        m = np.float32(a_scale) / np.float32(s_y)
+        x = float(np.float32(c_val) * m)
+        c = np.full(n, c_val, dtype=np.int32)
+        codes, lo, hi = oracle.requant_stochastic(c, a_scale, s_y, 0, -128, 127, seed=99)
+        fl = int(np.floor(x))
+        assert set(np.unique(codes).tolist()) <= {fl, fl + 1} and lo == 0 and hi == 0
+        p = x - fl
+        ups = float((codes == fl + 1).mean())
+        assert abs(ups - p) < 4 * max(p * (1 - p) / n, 1e-12) ** 0.5 + 1e-6, (x, ups, p)
+        assert abs(codes.astype(np.float64).mean() - x) < 4 * max(p * (1 - p) / n, 1e-12) ** 0.5 + 1e-6
+    # whole numbers never move, with any draw
+    c = np.arange(-100, 100, dtype=np.int32)
+    assert np.array_equal(oracle.requant_stochastic(c, 1.0, 1.0, 0, -128, 127, seed=3)[0], c.astype(np.int8))
+    # the decision of element i is the comparison of its own draw with its own fraction
+    g = np.random.default_rng(0)
+    c = g.integers(-5000, 5000, 5000).astype(np.int32)
+    a_scale, s_y, z = np.float32(0.0123), np.float32(0.31), -5
+    codes, lo, hi = oracle.requant_stochastic(c, a_scale, s_y, z, -128, 127, seed=0x1234567890, idx0=10**12)
+    m = a_scale / s_y
+    want, wlo, whi = [], 0, 0
+    for i, ci in enumerate(c):
+        x = np.float32(ci) * m
+        f = np.floor(x)
+        u = np.float32(_py_sr_bits(10**12 + i, 0x1234567890) >> 8) * np.float32(2.0**-24)
+        r = float(f + 1 if np.float32(x - f) > u else f)
+        if r < -128 - z: r = -128 - z; wlo += 1
+        if r > 127 - z: r = 127 - z; whi += 1
+        want.append(int(r) + z)
+    assert np.array_equal(codes, np.array(want, dtype=np.int8)) and (lo, hi) == (wlo, whi) and wlo > 0 and whi > 0
+
+
+def test_stochastic_rounding_against_nearest_and_in_the_step():
+    """Never further than one grid step from the nearest-even code; with the same seed the same codes;
+    statistics (min / max, and with them the range update) do not depend on the rounding mode."""
+    g = np.random.default_rng(4)
+    c = g.integers(-20000, 20000, (64, 48)).astype(np.int32)
+    a_scale = np.float32(1e-4)
+    r1, r2 = oracle.Range.new(0.9, True), oracle.Range.new(0.9, True)
+    o1 = oracle.in_hindsight_step(c, a_scale, r1)
+    o2 = oracle.in_hindsight_step(c, a_scale, r2, seed=11)          # first iteration: dynamic, nearest-even on both
+    assert np.array_equal(o1["codes"], o2["codes"])
+    c2 = (c * 0.9).astype(np.int32)
+    o1 = oracle.in_hindsight_step(c2, a_scale, r1)
+    o2 = oracle.in_hindsight_step(c2, a_scale, r2, seed=11)
+    o3 = oracle.quantize_static(c2, a_scale, oracle.Range.new(0.9, True) if False else r2, seed=11)
+    d = o2["codes"].astype(int) - o1["codes"].astype(int)
+    assert np.abs(d).max() == 1 and (d != 0).mean() > 0.2
+    assert (o1["acc_min"], o1["acc_max"]) == (o2["acc_min"], o2["acc_max"])
+    assert (r1.qmin, r1.qmax, r1.scale) == (r2.qmin, r2.qmax, r2.scale)
+    assert not np.array_equal(o2["codes"], oracle.quantize_static(c2, a_scale, r2, seed=12)["codes"])
+
+
 def test_workload_shapes_match_the_configurations():
     import workloads as wl
     L = wl.c2_layer()
