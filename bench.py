@@ -80,6 +80,12 @@ class Layer:
     def dgrad(self):
         self.hq.hq_gemm_dgrad(self.p, self.dY, self.gq, self.Wd, self.wq, self.wdsum, self.gr, self.dX, self.dxq, self.gst)
 
+    def dgrad_sr(self):
+        """The input gradient with stochastic rounding (what the paper uses for gradients, Sec. 5)."""
+        self.sr_step = getattr(self, "sr_step", 0) + 1
+        self.hq.hq_gemm_dgrad_sr(self.p, self.dY, self.gq, self.Wd, self.wq, self.wdsum, self.gr,
+                                 (0x9e3779b97f4a7c15 * self.sr_step) % 2 ** 64, self.dX, self.dxq, self.gst)
+
     def wgrad(self):
         self.hq.hq_gemm_wgrad(self.p, self.X, self.xq, self.dY, self.gq, self.dW, None, self.ws, self.ws_w)
 
@@ -351,6 +357,9 @@ def main():
             "dgrad_fused_ms": time_calls(torch, lay.dgrad, reps), "dgrad_dynamic_ms": time_calls(torch, lay.dyn_dgrad, reps),
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb},
             "measured_hbm_bytes_per_step": stored_traffic("step")}
+        # the same input-gradient GEMM with stochastic rounding in the epilogue (general kernel)
+        out["stochastic_rounding"] = {"dgrad_sr_ms": time_calls(torch, lay.dgrad_sr, reps),
+                                      "dgrad_nearest_even_ms": out["fused_vs_dynamic"]["dgrad_fused_ms"]}
         lay.upd_y(); lay.upd_g()
         # activations that grow 5 % per iteration (the range lags; eq. (2)-(3) settle at
         # (1 - eta) / (1.05 - eta) = 2/3 of the tensor's width)

@@ -144,6 +144,21 @@ int hq_gemm_dgrad(const hq_problem *p /* host */,
                   const int8_t *Wd, const hq_qparams *wq, const int32_t *wdsum,
                   const hq_range *gr, int8_t *dX, hq_qparams *dxq, hq_stats *st, void *stream);
 
+/* hq_gemm_dgrad with STOCHASTIC ROUNDING in the epilogue: the paper quantizes the activation
+ * gradient this way in all its experiments (Sec. 5, experimental setup, and the gradient-
+ * quantization paragraph; after Gupta et al. 2015).  The scaled accumulator x = fp32(c) * m is
+ * rounded up with probability x - floor(x): up iff that fraction exceeds u = r / 2^24, r being the
+ * top 24 of 32 random bits drawn for the element from a counter-based generator keyed on
+ * (linear index of the element in dX, seed).  The result therefore depends on the seed and the
+ * tensor only, not on the kernel's tiling; callers derive `seed` (host value) from their base
+ * seed, the tensor and the iteration.  Clamping, clip counts, statistics and all other arguments
+ * as hq_gemm_dgrad.  HQ_DEPTHWISE is not supported (HQ_E_BADSHAPE).                            */
+int hq_gemm_dgrad_sr(const hq_problem *p /* host */,
+                     const int8_t *dY, const hq_qparams *gq,
+                     const int8_t *Wd, const hq_qparams *wq, const int32_t *wdsum,
+                     const hq_range *gr, uint64_t seed,
+                     int8_t *dX, hq_qparams *dxq, hq_stats *st, void *stream);
+
 /* Weight gradient G_W = X~^T . G~_Y, kept in FP32 (Sec. 3.1): no quantizer, no range state.
  *   X, xq / dY, gq   both operands may carry a non-zero zero point
  *   dW       fp32, shaped like W: (xq->scale * gq->scale) * float(integer sum)

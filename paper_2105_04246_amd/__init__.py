@@ -46,7 +46,7 @@ class HqError(RuntimeError):
 
 
 _lib = None
-EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_wgrad", "hq_range_update",
+EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_range_update",
            "hq_range_update_batch",
            "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_probe_mfma_rate",
            "hq_error_string")
@@ -67,6 +67,7 @@ def lib():
         L.hq_workspace_bytes.argtypes = [C.c_int32, PP]
         L.hq_gemm_fwd.argtypes = [PP] + [vp] * 10
         L.hq_gemm_dgrad.argtypes = [PP] + [vp] * 10
+        L.hq_gemm_dgrad_sr.argtypes = [PP] + [vp] * 6 + [C.c_uint64] + [vp] * 4
         L.hq_gemm_wgrad.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.hq_range_update.argtypes = [vp, vp, vp]
         L.hq_range_update_batch.argtypes = [vp, vp, C.c_int32, vp]
@@ -114,6 +115,11 @@ def hq_gemm_fwd(p, X, xq, W, wq, wsum, yr, Y, yq, st, stream=None):
 def hq_gemm_dgrad(p, dY, gq, Wd, wq, wdsum, gr, dX, dxq, st, stream=None):
     _check("hq_gemm_dgrad", lib().hq_gemm_dgrad(C.byref(p), _ptr(dY), _ptr(gq), _ptr(Wd), _ptr(wq), _ptr(wdsum),
                                                 _ptr(gr), _ptr(dX), _ptr(dxq), _ptr(st), _stream(stream)))
+
+
+def hq_gemm_dgrad_sr(p, dY, gq, Wd, wq, wdsum, gr, seed, dX, dxq, st, stream=None):
+    _check("hq_gemm_dgrad_sr", lib().hq_gemm_dgrad_sr(C.byref(p), _ptr(dY), _ptr(gq), _ptr(Wd), _ptr(wq), _ptr(wdsum),
+                                                    _ptr(gr), int(seed), _ptr(dX), _ptr(dxq), _ptr(st), _stream(stream)))
 
 
 def hq_gemm_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, ws_bytes, stream=None):

@@ -226,7 +226,7 @@ size_t hq_workspace_bytes(int32_t entry, const hq_problem *p)
 
 static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                        const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out,
-                       int32_t *out32, hq_qparams *outq, hq_stats *st, void *stream)
+                       int32_t *out32, hq_qparams *outq, hq_stats *st, void *stream, const uint64_t *sr_seed = nullptr)
 {
     int rc = check_problem(p);
     if (rc != HQ_OK) return rc;
@@ -234,6 +234,11 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
     if (misaligned(A, 16) || misaligned(Bw, 16) || misaligned(bsum, 16) || misaligned(out, 16) ||
         misaligned(out32, 16) || misaligned(st, 8) || misaligned(range, 4) || misaligned(aq, 4) ||
         misaligned(bq, 4) || misaligned(outq, 4)) return HQ_E_BADARG;
+    if (sr_seed) {
+        // stochastic rounding lives in the general kernel's epilogue only
+        if (p->kind == HQ_DEPTHWISE) return HQ_E_BADSHAPE;
+        return hq_launch_gemm(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
+    }
     if (p->kind == HQ_DEPTHWISE)
         return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     rc = hq_try_launch_direct(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
@@ -255,6 +260,13 @@ int hq_gemm_dgrad(const hq_problem *p, const int8_t *dY, const hq_qparams *gq, c
                   const int32_t *wdsum, const hq_range *gr, int8_t *dX, hq_qparams *dxq, hq_stats *st, void *stream)
 {
     return gemm_common(p, 1, dY, gq, Wd, wq, wdsum, gr, dX, nullptr, dxq, st, stream);
+}
+
+int hq_gemm_dgrad_sr(const hq_problem *p, const int8_t *dY, const hq_qparams *gq, const int8_t *Wd, const hq_qparams *wq,
+                     const int32_t *wdsum, const hq_range *gr, uint64_t seed, int8_t *dX, hq_qparams *dxq, hq_stats *st,
+                     void *stream)
+{
+    return gemm_common(p, 1, dY, gq, Wd, wq, wdsum, gr, dX, nullptr, dxq, st, stream, &seed);
 }
 
 int hq_gemm_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY, const hq_qparams *gq,

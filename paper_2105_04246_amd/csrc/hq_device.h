@@ -133,6 +133,73 @@ __device__ inline void hq_requant_group(const int *c, const HqEpilogue &ep, int 
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Stochastic rounding (the paper quantizes gradients with it, Sec. 5 experimental setup, after
+// Gupta et al. 2015): the scaled accumulator x rounds up with probability x - floor(x).  Each
+// output element draws its 24 random bits from a counter-based generator keyed on the element's
+// linear index in its tensor and a 64-bit seed, so the result does not depend on how the launch
+// is tiled.  The generator: the low index word through the finalizer of MurmurHash3, with the
+// first key word added and the high index word (times an odd constant) plus the second key
+// word folded in between its two rounds, closed by a multiply with the golden-ratio constant
+// and a xor-shift.
+// ---------------------------------------------------------------------------------------
+struct HqSr { unsigned k0, k1; };          // low and high half of the seed
+
+__device__ inline unsigned hq_sr_bits(unsigned idx_lo, unsigned hi_term, unsigned k0)
+{
+    unsigned h = idx_lo;                   // hi_term = idx_hi * 0x85ebca77 + k1
+    h ^= h >> 16; h *= 0x85ebca6bu; h += k0;
+    h ^= hi_term;
+    h ^= h >> 13; h *= 0xc2b2ae35u; h ^= h >> 16;
+    h *= 0x9e3779b1u; h ^= h >> 15;
+    return h;
+}
+
+// As hq_requant_group, with stochastic rounding; idx0 is the tensor index of c[0], the N values
+// are consecutive elements.
+template <int N, bool FULL_GRID>
+__device__ inline void hq_requant_group_sr(const int *c, const HqEpilogue &ep, const HqSr &sr, size_t idx0, int &mn,
+                                           int &mx, unsigned &w_lo, unsigned &w_hi, int *words)
+{
+    int gmn = c[0], gmx = c[0];
+#pragma unroll
+    for (int e = 1; e + 1 < N; e += 2) { gmn = min(gmn, min(c[e], c[e + 1])); gmx = max(gmx, max(c[e], c[e + 1])); }
+    gmn = min(gmn, c[N - 1]); gmx = max(gmx, c[N - 1]);
+    mn = min(mn, gmn); mx = max(mx, gmx);
+    const unsigned lo0 = (unsigned)idx0, hi0 = (unsigned)(idx0 >> 32);
+    const unsigned term0 = hi0 * 0x85ebca77u + sr.k1, term1 = (hi0 + 1u) * 0x85ebca77u + sr.k1;
+    float f[N];
+#pragma unroll
+    for (int e = 0; e < N; e++) {
+        const unsigned lo = lo0 + (unsigned)e;
+        const unsigned bits = hq_sr_bits(lo, lo < lo0 ? term1 : term0, sr.k0);       // carry into the high word
+        const float x = __fmul_rn((float)c[e], ep.mult), fl = floorf(x);
+        const float u = __fmul_rn((float)(bits >> 8), 1.0f / 16777216.0f);
+        f[e] = __fsub_rn(x, fl) > u ? __fadd_rn(fl, 1.0f) : fl;
+    }
+    // the rounded value lies in [floor(x), floor(x) + 1]: the group's extremes decide whether any can clip
+    if (__any(__fadd_rn(floorf(__fmul_rn((float)gmx, ep.mult)), 1.0f) > ep.fhi || floorf(__fmul_rn((float)gmn, ep.mult)) < ep.flo)) {
+        float nh = 0.0f, nl = 0.0f;
+#pragma unroll
+        for (int e = 0; e < N; e++) {
+            nh += __builtin_amdgcn_fmed3f(f[e] - ep.fhi, 0.0f, 1.0f);
+            nl += __builtin_amdgcn_fmed3f(ep.flo - f[e], 0.0f, 1.0f);
+        }
+        w_hi += (unsigned)nh; w_lo += (unsigned)nl;
+    }
+#pragma unroll
+    for (int g = 0; g < N / 4; g++) {
+        unsigned w = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            float v = f[4 * g + e];
+            if (!FULL_GRID) v = __builtin_amdgcn_fmed3f(v, ep.flo, ep.fhi);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(v + ep.zoff, e, w);
+        }
+        words[g] = (int)(w ^ 0x80808080u);
+    }
+}
+
 // min / max alone (pass 1 of the dynamic baseline keeps the 32-bit values)
 template <int N> __device__ inline void hq_minmax_group(const int *c, int &mn, int &mx)
 {

@@ -58,16 +58,20 @@ struct GemmArgs {
     int Bn;                        // images (class form)
     int ncls;                      // class form: stride * stride classes, 0 otherwise
     int cls_tile0[17];             // first row tile of each class (prefix sums), [ncls] = m_tiles
+    HqSr sr;                       // MODE 2: seed of the stochastic rounding
 };
 
 __device__ inline int sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
 // BKB: bytes of reduction per stage.  STRIDED: input gradient of a strided layer (gather with
 // exact-division test); otherwise the stencil form.  ALIGNED: Cs % 16 == 0 (16-byte loads, one tap per chunk).
-template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
+// MODE 0: 32-bit outputs (pass 1 of the dynamic baseline); 1: requantize, round to nearest even; 2: requantize,
+// stochastic rounding.
+template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, int MODE>
 __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 : 2)) void hq_gemm_kernel(const GemmArgs a)
 {
     static_assert(WGM * WGN == HQ_THREADS / 64, "four wavefronts");
+    constexpr bool FUSED = MODE != 0, SR = MODE == 2;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wavefront tile
     constexpr int MT = WTM / 32, NT = WTN / 32;         // 32x32 MFMA tiles per wavefront
     constexpr int CPS = BKB / 16;                       // 16-byte chunks per row and stage
@@ -410,7 +414,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
                     }
                 } else if (nb + 16 <= a.N) {
                     int w[4];
-                    hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
+                    if (SR) hq_requant_group_sr<16, FULL>(c, ep, a.sr, o, mn, mx, nlo, nhi, w);
+                    else    hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
                     if (wide_store) {
                         const v4i v = {w[0], w[1], w[2], w[3]};
                         *reinterpret_cast<v4i *>(a.out8 + o) = v;
@@ -423,7 +428,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
                     for (int g = 0; g < 4; g++) {
                         if (nb + 4 * g >= a.N) continue;
                         int w;
-                        hq_requant_group<4, FULL>(c + 4 * g, ep, mn, mx, nlo, nhi, &w);
+                        if (SR) hq_requant_group_sr<4, FULL>(c + 4 * g, ep, a.sr, o + 4 * g, mn, mx, nlo, nhi, &w);
+                        else    hq_requant_group<4, FULL>(c + 4 * g, ep, mn, mx, nlo, nhi, &w);
                         *reinterpret_cast<int *>(a.out8 + o + 4 * g) = w;
                     }
                 }
@@ -440,7 +446,7 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, bool FUSED>
+template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED, int MODE>
 int launch3(GemmArgs &a, hipStream_t s)
 {
     a.m_tiles = (a.M + BM - 1) / BM;
@@ -459,7 +465,7 @@ int launch3(GemmArgs &a, hipStream_t s)
         a.m_tiles = t;
     }
     const size_t lds = 2 * (size_t)(BM + BN) * (ALIGNED ? BKB : BKB + 16) + 4 * BN + 64;
-    auto kern = hq_gemm_kernel<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, FUSED>;
+    auto kern = hq_gemm_kernel<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, MODE>;
     static bool configured = false;
     if (!configured) {
         if (lds > 48 * 1024 &&
@@ -472,19 +478,26 @@ int launch3(GemmArgs &a, hipStream_t s)
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }
 
+// mode: 0 / 1 / 2 as the kernel's MODE.  Stochastic rounding is built for the two tile shapes with 64-byte
+// stages only (the launcher below routes it there).
+template <int BM, int BN, int WGM, int WGN, int BKB, bool STRIDED, bool ALIGNED>
+int launch2m(GemmArgs &a, int mode, hipStream_t s)
+{
+    if (mode == 0) return launch3<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, 0>(a, s);
+    if (mode == 1) return launch3<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, 1>(a, s);
+    if constexpr (BKB == 64 && BN >= 64) return launch3<BM, BN, WGM, WGN, BKB, STRIDED, ALIGNED, 2>(a, s);
+    return HQ_E_BADSHAPE;
+}
+
 template <int BM, int BN, int WGM, int WGN, int BKB>
-int launch2(GemmArgs &a, bool strided, bool aligned, bool fused, hipStream_t s)
+int launch2(GemmArgs &a, bool strided, bool aligned, int mode, hipStream_t s)
 {
     if (strided) {
-        if (aligned) return fused ? launch3<BM, BN, WGM, WGN, BKB, true, true, true>(a, s)
-                                  : launch3<BM, BN, WGM, WGN, BKB, true, true, false>(a, s);
-        return fused ? launch3<BM, BN, WGM, WGN, BKB, true, false, true>(a, s)
-                     : launch3<BM, BN, WGM, WGN, BKB, true, false, false>(a, s);
+        if (aligned) return launch2m<BM, BN, WGM, WGN, BKB, true, true>(a, mode, s);
+        return launch2m<BM, BN, WGM, WGN, BKB, true, false>(a, mode, s);
     }
-    if (aligned) return fused ? launch3<BM, BN, WGM, WGN, BKB, false, true, true>(a, s)
-                              : launch3<BM, BN, WGM, WGN, BKB, false, true, false>(a, s);
-    return fused ? launch3<BM, BN, WGM, WGN, BKB, false, false, true>(a, s)
-                 : launch3<BM, BN, WGM, WGN, BKB, false, false, false>(a, s);
+    if (aligned) return launch2m<BM, BN, WGM, WGN, BKB, false, true>(a, mode, s);
+    return launch2m<BM, BN, WGM, WGN, BKB, false, false>(a, mode, s);
 }
 
 } // namespace
@@ -492,7 +505,7 @@ int launch2(GemmArgs &a, bool strided, bool aligned, bool fused, hipStream_t s)
 // Host-side entry used by hq_api.hip.  `dgrad` selects the operation; `out32` the dynamic pass 1.
 int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                    const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
-                   int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
+                   int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream, const uint64_t *sr_seed)
 {
     const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
     GemmArgs a;
@@ -514,7 +527,10 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
         }
     }
     // (the class form of the strided input gradient keeps at most 16 classes: larger strides take the 4-byte path)
-    const bool aligned = (a.Cs % 16) == 0 && !(strided && a.stride > 4), fused = out32 == nullptr;
+    const bool aligned = (a.Cs % 16) == 0 && !(strided && a.stride > 4);
+    if (sr_seed && out32) return HQ_E_BADARG;
+    const int mode = out32 ? 0 : sr_seed ? 2 : 1;
+    if (sr_seed) { a.sr.k0 = (unsigned)*sr_seed; a.sr.k1 = (unsigned)(*sr_seed >> 32); } else { a.sr.k0 = a.sr.k1 = 0; }
     a.kcols = a.taps * a.Cs;
     a.cpt = aligned ? a.Cs / 16 : 1;
     a.nchunks = aligned ? a.taps * a.cpt : (a.kcols + 15) / 16;
@@ -527,9 +543,9 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
         // workgroups on every compute unit, 64-byte stages (half the LDS, four resident workgroups)
         // hide more latency instead
         const long tiles = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-        if (a.nchunks >= 16 && !(aligned && tiles >= 3 * 256)) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, fused, stream);
-        return launch2<128, 128, 2, 2, 64>(a, strided, aligned, fused, stream);
+        if (mode != 2 && a.nchunks >= 16 && !(aligned && tiles >= 3 * 256)) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, mode, stream);
+        return launch2<128, 128, 2, 2, 64>(a, strided, aligned, mode, stream);
     }
-    if (a.N > 32) return launch2<256, 64, 4, 1, 64>(a, strided, aligned, fused, stream);
-    return launch2<256, 32, 4, 1, 64>(a, strided, aligned, fused, stream);
+    if (a.N > 32 || mode == 2) return launch2<256, 64, 4, 1, 64>(a, strided, aligned, mode, stream);
+    return launch2<256, 32, 4, 1, 64>(a, strided, aligned, mode, stream);
 }

@@ -3,9 +3,10 @@
 #include <hip/hip_runtime.h>
 #include "../../include/hq.h"
 
+// sr_seed: NULL = round to nearest even; otherwise (host pointer) the seed of stochastic rounding.
 int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                    const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
-                   int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+                   int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream, const uint64_t *sr_seed = nullptr);
 
 // Fast path for layers whose weights fit in LDS; HQ_E_BADSHAPE means "not covered, use hq_launch_gemm".
 int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,

@@ -59,15 +59,19 @@ def read_qparams(q):
     return hq.from_device(q, hq.QPARAMS)[0]
 
 
-def gpu_quantized_op(L, op, A, Wdev, r, st, mode="fused", dyn_mode=hq.HQ_DYN_CURRENT):
-    """op in {'fwd','dgrad'}; mode 'fused' (in-hindsight static) or 'dynamic'.
+def gpu_quantized_op(L, op, A, Wdev, r, st, mode="fused", dyn_mode=hq.HQ_DYN_CURRENT, seed=None):
+    """op in {'fwd','dgrad'}; mode 'fused' (in-hindsight static; with a seed: stochastic rounding,
+    dgrad only) or 'dynamic'.
     Returns (codes ndarray, qparams record).  Range state / stats stay on the device."""
     p = hq_problem(L)
     shape = wl.out_shape(L) if op == "fwd" else wl.in_shape(L)
     out = torch.empty(shape, dtype=torch.int8, device="cuda")
     outq = hq.new_qparams(0.0, 0)
     Bw, bsum = (Wdev.W, Wdev.wsum) if op == "fwd" else (Wdev.Wd, Wdev.wdsum)
-    if mode == "fused":
+    if mode == "fused" and seed is not None:
+        assert op == "dgrad"
+        hq.hq_gemm_dgrad_sr(p, A.codes, A.qp, Bw, Wdev.qp, bsum, r, seed, out, outq, st)
+    elif mode == "fused":
         f = hq.hq_gemm_fwd if op == "fwd" else hq.hq_gemm_dgrad
         f(p, A.codes, A.qp, Bw, Wdev.qp, bsum, r, out, outq, st)
     else:
@@ -125,14 +129,15 @@ class TensorTrack:
         self.r, self.st = state if state is not None else (hq.new_range(eta, symmetric), hq.new_stats(1))
         self.ref = oracle.Range.new(eta, symmetric)
 
-    def step(self, L, op, A_q, W_q, A_dev, W_dev, check=True, update=True):
+    def step(self, L, op, A_q, W_q, A_dev, W_dev, check=True, update=True, seed=None):
         """Runs iteration t on both sides (dynamic init at t=0, fused afterwards), compares
         codes, quantizer, statistics and the updated range.  Returns (gpu codes, oracle dict)."""
         a_scale = oracle.acc_scale(A_q.scale, W_q.scale)
         c = oracle_acc(L, op, A_q, W_q)
         first = not self.ref.initialized
-        ref = oracle.in_hindsight_step(c, a_scale, self.ref)
-        codes, qp = gpu_quantized_op(L, op, A_dev, W_dev, self.r, self.st, "dynamic" if first else "fused")
+        ref = oracle.in_hindsight_step(c, a_scale, self.ref, seed)
+        codes, qp = gpu_quantized_op(L, op, A_dev, W_dev, self.r, self.st, "dynamic" if first else "fused",
+                                     seed=None if first else seed)
         st = read_stats(self.st)
         if update:
             hq.hq_range_update(self.r, self.st)

@@ -332,6 +332,49 @@ def test_repeat_runs_are_bit_identical(H, hq):
 
 
 # ---------------------------------------------------------------------------------------
+# Stochastic rounding of the input gradient (the paper's gradient quantizer, Sec. 5)
+# ---------------------------------------------------------------------------------------
+SR_SHAPES = [wl.conv("sr_c64", 2, 20, 64, 64, 3),                 # 256 x 64 tiles
+             wl.conv("sr_c128", 2, 14, 128, 128, 3),              # 128 x 128 tiles
+             wl.conv("sr_s2", 2, 12, 32, 48, 3, stride=2),        # strided classes
+             wl.conv("sr_c24", 1, 9, 24, 40, 3),                  # 4-byte reduction path, ragged column groups
+             wl.conv("sr_n8", 3, 7, 16, 8, 1, pad=0),             # fewer than 16 output columns... of dX: C = 16
+             wl.linear("sr_lin", 300, 72, 80),
+             wl.LayerShape("sr_c5x5_s3", wl.CONV, 2, 17, 17, 16, 5, 5, 3, 2, 32)]
+
+
+@pytest.mark.parametrize("L", SR_SHAPES, ids=[l.name for l in SR_SHAPES])
+def test_stochastic_rounding_dgrad(H, hq, L):
+    """Codes, clip counts and statistics bit for bit against the oracle with the same seed per
+    iteration; the seed changes the codes, the tiling does not enter (the oracle has none)."""
+    for g_asym in (False, True):
+        g_track = H.TensorTrack(0.9, symmetric=not g_asym)
+        Wdev, W0 = None, None
+        for t in range(3):
+            X, W, dY = rand_layer_inputs(L, 500 + t, g_asym=g_asym)
+            if Wdev is None:
+                W0, Wdev = W, H.DevWeights(L, W)
+            dYd = H.DevTensor(dY)
+            g_track.step(L, "dgrad", dY, W0, dYd, Wdev, seed=0x9e3779b97f4a7c15 * (t + 1) % 2**64)
+        # same tensor, same range, two seeds: different codes, never more than one step apart
+        a, _ = H.gpu_quantized_op(L, "dgrad", dYd, Wdev, g_track.r, g_track.st, seed=1)
+        b, _ = H.gpu_quantized_op(L, "dgrad", dYd, Wdev, g_track.r, g_track.st, seed=2)
+        hq.hq_stats_reset(g_track.st)
+        assert not np.array_equal(a, b) and np.abs(a.astype(int) - b.astype(int)).max() <= 1
+
+
+def test_stochastic_rounding_rejects_depthwise(H, hq):
+    L = wl.depthwise("sr_dw", 1, 8, 16)
+    X, W, dY = rand_layer_inputs(L, 3)
+    Wdev, dYd = H.DevWeights(L, W), H.DevTensor(dY)
+    r, st = hq.new_range(0.9, True), hq.new_stats()
+    out = torch.empty(wl.in_shape(L), dtype=torch.int8, device="cuda")
+    with pytest.raises(hq.HqError) as e:
+        hq.hq_gemm_dgrad_sr(H.hq_problem(L), dYd.codes, dYd.qp, Wdev.Wd, Wdev.qp, Wdev.wdsum, r, 1, out, hq.new_qparams(0, 0), st)
+    assert e.value.code == hq.HQ_E_BADSHAPE
+
+
+# ---------------------------------------------------------------------------------------
 # Degenerate tensors and ranges
 # ---------------------------------------------------------------------------------------
 def _const_tensor(shape, code, scale, zp):
