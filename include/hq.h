@@ -152,7 +152,7 @@ int hq_gemm_dgrad(const hq_problem *p /* host */,
  * (linear index of the element in dX, seed).  The result therefore depends on the seed and the
  * tensor only, not on the kernel's tiling; callers derive `seed` (host value) from their base
  * seed, the tensor and the iteration.  Clamping, clip counts, statistics and all other arguments
- * as hq_gemm_dgrad.  HQ_DEPTHWISE is not supported (HQ_E_BADSHAPE).                            */
+ * as hq_gemm_dgrad.  Runs in the general GEMM kernel and, for HQ_DEPTHWISE, the general stencil.  */
 int hq_gemm_dgrad_sr(const hq_problem *p /* host */,
                      const int8_t *dY, const hq_qparams *gq,
                      const int8_t *Wd, const hq_qparams *wq, const int32_t *wdsum,

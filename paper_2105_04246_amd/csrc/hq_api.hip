@@ -235,8 +235,9 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
         misaligned(out32, 16) || misaligned(st, 8) || misaligned(range, 4) || misaligned(aq, 4) ||
         misaligned(bq, 4) || misaligned(outq, 4)) return HQ_E_BADARG;
     if (sr_seed) {
-        // stochastic rounding lives in the general kernel's epilogue only
-        if (p->kind == HQ_DEPTHWISE) return HQ_E_BADSHAPE;
+        // stochastic rounding lives in the epilogues of the two general kernels only
+        if (p->kind == HQ_DEPTHWISE)
+            return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
         return hq_launch_gemm(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
     }
     if (p->kind == HQ_DEPTHWISE)

@@ -19,6 +19,8 @@ struct DwArgs {
     hq_stats *st;
     int M, C;                      // output pixels, channels
     int R, S, Hs, Ws, Ho, Wo, stride, pad, dgrad;
+    int sr_on;                     // 1: stochastic rounding with the seed below
+    HqSr sr;
 };
 
 __device__ inline int sbyte(int v, int k) { return (v << (24 - 8 * k)) >> 24; }
@@ -74,7 +76,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_kernel(const DwArgs a
         }
         if (fused) {
 #pragma unroll
-            for (int e = 0; e < 4; e++) q[e] = hq_requant(q[e], rq, nlo, nhi);
+            for (int e = 0; e < 4; e++)
+                q[e] = a.sr_on ? hq_requant_sr(q[e], rq, a.sr, (size_t)m * a.C + c + e, nlo, nhi) : hq_requant(q[e], rq, nlo, nhi);
             *reinterpret_cast<unsigned *>(a.out8 + (size_t)m * a.C + c) = hq_pack4(q[0], q[1], q[2], q[3]);
         } else {
             v4i v = {q[0], q[1], q[2], q[3]};
@@ -484,16 +487,19 @@ size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
 int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
                         const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
-                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
+                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream, const uint64_t *sr_seed)
 {
     const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
+    if (sr_seed && out32) return HQ_E_BADARG;
     DwArgs a;
+    a.sr_on = sr_seed ? 1 : 0;
+    a.sr.k0 = sr_seed ? (unsigned)*sr_seed : 0u; a.sr.k1 = sr_seed ? (unsigned)(*sr_seed >> 32) : 0u;
     a.A = A; a.Wt = Wt; a.wsum = wsum; a.aq = aq; a.bq = bq; a.range = range;
     a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
     a.C = p->C; a.R = p->R; a.S = p->S; a.stride = p->stride; a.pad = p->pad; a.dgrad = dgrad;
     if (!dgrad) { a.M = p->B * OH * OW; a.Hs = p->H; a.Ws = p->W; a.Ho = OH; a.Wo = OW; }
     else        { a.M = p->B * p->H * p->W; a.Hs = OH; a.Ws = OW; a.Ho = p->H; a.Wo = p->W; }
-    if (p->R == 3 && p->S == 3 && p->stride == 1 && p->pad == 1 && p->B <= 65535) {
+    if (!sr_seed && p->R == 3 && p->S == 3 && p->stride == 1 && p->pad == 1 && p->B <= 65535) {
         Dw3Args d;
         d.A = A; d.Wt = Wt; d.wsum = wsum; d.aq = aq; d.bq = bq; d.range = range;
         d.out8 = out8; d.out32 = out32; d.outq = outq; d.st = st;

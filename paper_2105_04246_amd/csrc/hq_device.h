@@ -155,6 +155,19 @@ __device__ inline unsigned hq_sr_bits(unsigned idx_lo, unsigned hi_term, unsigne
     return h;
 }
 
+// One value (the depthwise stencil's epilogue): as hq_requant, with stochastic rounding.
+__device__ inline int hq_requant_sr(int c, const HqRequant &q, const HqSr &sr, size_t idx, unsigned &nlo, unsigned &nhi)
+{
+    const unsigned bits = hq_sr_bits((unsigned)idx, (unsigned)(idx >> 32) * 0x85ebca77u + sr.k1, sr.k0);
+    const float x = __fmul_rn((float)c, q.mult), fl = floorf(x);
+    const float u = __fmul_rn((float)(bits >> 8), 1.0f / 16777216.0f);
+    float r = __fsub_rn(x, fl) > u ? __fadd_rn(fl, 1.0f) : fl;
+    nlo += (r < q.flo) ? 1u : 0u;
+    nhi += (r > q.fhi) ? 1u : 0u;
+    r = fminf(fmaxf(r, q.flo), q.fhi);
+    return (int)r + q.z;
+}
+
 // As hq_requant_group, with stochastic rounding; idx0 is the tensor index of c[0], the N values
 // are consecutive elements.
 template <int N, bool FULL_GRID>

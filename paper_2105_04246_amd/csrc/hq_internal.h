@@ -24,9 +24,10 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
                         const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
                         int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
 
+// sr_seed as for hq_launch_gemm (stochastic rounding runs in the general stencil kernel).
 int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
                         const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
-                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream);
+                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream, const uint64_t *sr_seed = nullptr);
 
 size_t hq_wgrad_workspace_bytes(const hq_problem *p);
 

@@ -340,7 +340,8 @@ SR_SHAPES = [wl.conv("sr_c64", 2, 20, 64, 64, 3),                 # 256 x 64 til
              wl.conv("sr_c24", 1, 9, 24, 40, 3),                  # 4-byte reduction path, ragged column groups
              wl.conv("sr_n8", 3, 7, 16, 8, 1, pad=0),             # fewer than 16 output columns... of dX: C = 16
              wl.linear("sr_lin", 300, 72, 80),
-             wl.LayerShape("sr_c5x5_s3", wl.CONV, 2, 17, 17, 16, 5, 5, 3, 2, 32)]
+             wl.LayerShape("sr_c5x5_s3", wl.CONV, 2, 17, 17, 16, 5, 5, 3, 2, 32),
+             wl.depthwise("sr_dw", 2, 13, 48), wl.depthwise("sr_dw_s2", 2, 12, 32, stride=2)]
 
 
 @pytest.mark.parametrize("L", SR_SHAPES, ids=[l.name for l in SR_SHAPES])
@@ -361,17 +362,6 @@ def test_stochastic_rounding_dgrad(H, hq, L):
         b, _ = H.gpu_quantized_op(L, "dgrad", dYd, Wdev, g_track.r, g_track.st, seed=2)
         hq.hq_stats_reset(g_track.st)
         assert not np.array_equal(a, b) and np.abs(a.astype(int) - b.astype(int)).max() <= 1
-
-
-def test_stochastic_rounding_rejects_depthwise(H, hq):
-    L = wl.depthwise("sr_dw", 1, 8, 16)
-    X, W, dY = rand_layer_inputs(L, 3)
-    Wdev, dYd = H.DevWeights(L, W), H.DevTensor(dY)
-    r, st = hq.new_range(0.9, True), hq.new_stats()
-    out = torch.empty(wl.in_shape(L), dtype=torch.int8, device="cuda")
-    with pytest.raises(hq.HqError) as e:
-        hq.hq_gemm_dgrad_sr(H.hq_problem(L), dYd.codes, dYd.qp, Wdev.Wd, Wdev.qp, Wdev.wdsum, r, 1, out, hq.new_qparams(0, 0), st)
-    assert e.value.code == hq.HQ_E_BADSHAPE
 
 
 # ---------------------------------------------------------------------------------------
