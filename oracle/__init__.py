@@ -89,6 +89,7 @@ def lib():
         L.hqo_sr_bits.restype = C.c_uint32
         L.hqo_range_update.argtypes = [C.POINTER(Range), C.c_int32, C.c_int32, C.c_float]
         L.hqo_wgrad_scale.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, f32p]
+        L.hqo_quantize_weights.argtypes = [f32p, C.c_int64, i8p, f32p]
         for f in ("hqo_fwd", "hqo_fwd_rows", "hqo_dgrad", "hqo_dgrad_rows", "hqo_wgrad"):
             getattr(L, f).restype = C.c_int
         _lib = L
@@ -202,6 +203,16 @@ def range_update(r, acc_min, acc_max, acc_scale):
     """eq. (2)-(3) in place on ``r``; the first call sets q^0."""
     lib().hqo_range_update(C.byref(r), int(acc_min), int(acc_max), float(acc_scale))
     return r
+
+
+def quantize_weights(w):
+    """Q_W with the current min-max of the tensor (Sec. 3.1; Sec. 5): returns (codes, scale);
+    symmetric grid -127..127, zero point 0."""
+    w = np.ascontiguousarray(w, np.float32)
+    out = np.empty(w.shape, np.int8)
+    s = C.c_float()
+    lib().hqo_quantize_weights(_p(w, C.c_float), w.size, _p(out, C.c_int8), C.byref(s))
+    return out, np.float32(s.value)
 
 
 def wgrad_scale(c, sx, sg):

@@ -354,6 +354,24 @@ void hqo_range_update(hqo_range *r, int32_t acc_min, int32_t acc_max, float acc_
     hqo_qparams(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi, &r->scale, &r->zero_point);
 }
 
+/* Q_W (Sec. 3.1): the weight quantizer's range does not depend on the batch; the paper always
+ * uses the current min-max of the weight tensor (Sec. 5, experimental setup).  Symmetric 8-bit
+ * grid -127..127: s = max|w| / 127 (1 for an all-zero tensor), code = clamp(rne(w / s)), every
+ * fp32 operation rounded once.                                                              */
+void hqo_quantize_weights(const float *w, int64_t n, int8_t *out, float *scale)
+{
+    float amax = 0.0f;
+    for (int64_t i = 0; i < n; i++) { float a = fabsf(w[i]); if (a > amax) amax = a; }
+    float s = amax > 0.0f ? amax / 127.0f : 1.0f;
+    for (int64_t i = 0; i < n; i++) {
+        float r = rintf(w[i] / s);
+        if (r < -127.0f) r = -127.0f;
+        if (r > 127.0f) r = 127.0f;
+        out[i] = (int8_t)(int)r;
+    }
+    *scale = s;
+}
+
 /* Weight gradient kept in FP32 (Sec. 3.1): one multiply by s_x * s_g.         */
 void hqo_wgrad_scale(const int32_t *c, int64_t n, float sx, float sg, float *dW)
 {

@@ -498,6 +498,28 @@ def test_stochastic_rounding_against_nearest_and_in_the_step():
     assert not np.array_equal(o2["codes"], oracle.quantize_static(c2, a_scale, r2, seed=12)["codes"])
 
 
+def test_weight_quantizer_current_min_max():
+    """Q_W (Sec. 3.1, Sec. 5): hand values, the extreme maps to +-127, an all-zero tensor keeps
+    scale 1, codes are within half a step of the weight, monotone, and a fixed point of
+    quantize(dequantize(.))."""
+    codes, s = oracle.quantize_weights(np.array([0.0, 1.27, -1.27, 0.635, 0.005, -0.0151, 0.64], np.float32))
+    assert s == f32(1.27) / f32(127) and codes.tolist() == [0, 127, -127, 64, 0, -2, 64]
+    codes, s = oracle.quantize_weights(np.zeros(5, np.float32))
+    assert s == f32(1.0) and not codes.any()
+    g = np.random.default_rng(8)
+    w = (g.standard_normal(20000) * 0.05).astype(np.float32)
+    codes, s = oracle.quantize_weights(w)
+    assert s == np.abs(w).max() / f32(127) and np.abs(codes).max() == 127 and codes.min() >= -127
+    assert np.abs(w.astype(np.float64) - float(s) * codes) .max() <= 0.5 * float(s) * (1 + 1e-6)
+    order = np.argsort(w, kind="stable")
+    assert (np.diff(codes[order].astype(int)) >= 0).all()
+    again, s2 = oracle.quantize_weights((f32(s) * codes.astype(np.float32)).astype(np.float32))
+    assert np.array_equal(again, codes) and abs(float(s2) - float(s)) <= 1e-6 * float(s)
+    # ties go to the even code: 0.5 and 1.5 steps of a tensor whose scale is exactly 1/64
+    codes, s = oracle.quantize_weights(np.array([127 / 64, 0.5 / 64, 1.5 / 64, 2.5 / 64, -0.5 / 64, -1.5 / 64], np.float32))
+    assert s == f32(1 / 64) and codes.tolist() == [127, 0, 2, 2, 0, -2]
+
+
 def test_workload_shapes_match_the_configurations():
     import workloads as wl
     L = wl.c2_layer()
