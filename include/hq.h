@@ -219,6 +219,14 @@ int hq_stats_fold(hq_stats *st, int32_t n, void *stream);
 int hq_weight_prepare(const hq_problem *p /* host */, const int8_t *W,
                       int8_t *Wd, int32_t *wsum, int32_t *wdsum, void *stream);
 
+/* Q_W, the weight quantizer (Sec. 3.1: its range does not depend on the batch; Sec. 5: "the weights
+ * are always quantized with the current min-max method"): symmetric 8-bit quantization of an
+ * FP32 tensor with its own range, s = max|w| / 127 (1 for an all-zero tensor),
+ * code = clamp(rne(w / s), -127, 127), each fp32 operation rounded once.  Element-wise: Wf and
+ * Wq [n] in any layout (follow with hq_weight_prepare for the dgrad layout and the sums).
+ * wq receives {s, 0}.  Finite inputs are assumed.                                             */
+int hq_weight_quantize(const float *Wf, size_t n, int8_t *Wq, hq_qparams *wq, void *stream);
+
 /* Measurement aid, not part of the method: launches a kernel in which every wavefront issues
  * iters * 8 int8 MFMAs (32x32x32, operands and accumulators in registers, no memory traffic
  * except one 4-byte store per lane to sink [blocks * 256] at the end).  Timed by the caller, it

@@ -48,7 +48,7 @@ class HqError(RuntimeError):
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_range_update",
            "hq_range_update_batch",
-           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_probe_mfma_rate",
+           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_probe_mfma_rate",
            "hq_error_string")
 
 
@@ -76,6 +76,7 @@ def lib():
         L.hq_stats_fold.argtypes = [vp, C.c_int32, vp]
         L.hq_weight_prepare.argtypes = [PP, vp, vp, vp, vp, vp]
         L.hq_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, vp, vp]
+        L.hq_weight_quantize.argtypes = [vp, C.c_size_t, vp, vp, vp]
         for f in EXPORTS[1:-1]:
             getattr(L, f).restype = C.c_int
         _lib = L
@@ -152,6 +153,10 @@ def hq_stats_fold(st, n=1, stream=None):
 def hq_weight_prepare(p, W, Wd, wsum, wdsum, stream=None):
     _check("hq_weight_prepare", lib().hq_weight_prepare(C.byref(p), _ptr(W), _ptr(Wd), _ptr(wsum), _ptr(wdsum),
                                                         _stream(stream)))
+
+
+def hq_weight_quantize(Wf, n, Wq, wq, stream=None):
+    _check("hq_weight_quantize", lib().hq_weight_quantize(_ptr(Wf), n, _ptr(Wq), _ptr(wq), _stream(stream)))
 
 
 def hq_probe_mfma_rate(blocks, iters, sink, stream=None):

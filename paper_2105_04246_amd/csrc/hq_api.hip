@@ -174,6 +174,42 @@ size_t out_elems(const hq_problem *p, bool dgrad)
     return dgrad ? (size_t)p->B * p->H * p->W * p->C : (size_t)p->B * OH * OW * p->Cout;
 }
 
+// Q_W: |w| maximum of an FP32 tensor into *bits (non-negative floats order like their bit patterns).
+__global__ __launch_bounds__(HQ_THREADS) void weight_absmax_kernel(const float *__restrict__ w, size_t n, unsigned *bits)
+{
+    __shared__ unsigned red[HQ_THREADS / 64];
+    unsigned m = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        m = max(m, __float_as_uint(fabsf(w[i])));
+#pragma unroll
+    for (int k = 32; k >= 1; k >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, k));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < HQ_THREADS / 64; k++) m = max(m, red[k]);
+        if (m) atomicMax(bits, m);
+    }
+}
+
+__global__ void weight_scale_init_kernel(hq_qparams *wq) { wq->zero_point = 0; }      // the maximum is gathered in this field
+
+__global__ void weight_scale_kernel(hq_qparams *wq)
+{
+    const float amax = __uint_as_float((unsigned)wq->zero_point);
+    wq->scale = amax > 0.0f ? __fdiv_rn(amax, 127.0f) : 1.0f;
+    wq->zero_point = 0;
+}
+
+__global__ __launch_bounds__(HQ_THREADS) void weight_quantize_kernel(const float *__restrict__ w, size_t n,
+                                                                     const hq_qparams *wq, int8_t *__restrict__ out)
+{
+    const float s = wq->scale;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const float r = fminf(fmaxf(rintf(__fdiv_rn(w[i], s)), -127.0f), 127.0f);
+        out[i] = (int8_t)(int)r;
+    }
+}
+
 // Register-only int8 MFMA loop: eight independent accumulator chains per wavefront, so that the
 // matrix pipeline never waits on a dependent result.
 __global__ __launch_bounds__(HQ_THREADS) void mfma_rate_kernel(int iters, int32_t *sink)
@@ -360,6 +396,20 @@ int hq_weight_prepare(const hq_problem *p, const int8_t *W, int8_t *Wd, int32_t 
     if (wsum) hipLaunchKernelGGL(weight_rowsum_kernel, dim3((p->Cout + 3) / 4), dim3(256), 0, s, W, p->Cout, taps * p->C, wsum);
     if (wdsum) colsum(p->Cout, wdsum);
     if (Wd) hipLaunchKernelGGL(weight_relayout_kernel, dim3(1024), dim3(256), 0, s, W, p->Cout, taps, p->C, Wd);
+    return launch_status();
+}
+
+int hq_weight_quantize(const float *Wf, size_t n, int8_t *Wq, hq_qparams *wq, void *stream)
+{
+    if (!Wf || !Wq || !wq || n == 0 || misaligned(Wf, 4) || misaligned(wq, 4)) return HQ_E_BADARG;
+    hipStream_t s = as_stream(stream);
+    size_t blocks = (n + HQ_THREADS - 1) / HQ_THREADS;
+    if (blocks > 256u * 16u) blocks = 256u * 16u;
+    hipLaunchKernelGGL(weight_scale_init_kernel, dim3(1), dim3(1), 0, s, wq);
+    hipLaunchKernelGGL(weight_absmax_kernel, dim3((unsigned)blocks), dim3(HQ_THREADS), 0, s, Wf, n,
+                       reinterpret_cast<unsigned *>(&wq->zero_point));
+    hipLaunchKernelGGL(weight_scale_kernel, dim3(1), dim3(1), 0, s, wq);
+    hipLaunchKernelGGL(weight_quantize_kernel, dim3((unsigned)blocks), dim3(HQ_THREADS), 0, s, Wf, n, wq, Wq);
     return launch_status();
 }
 

@@ -85,6 +85,7 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.hq_gemm_fwd(ctypes.byref(good), *([nul] * 10)) == hq.HQ_E_BADARG
     assert L.hq_range_update(nul, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_probe_mfma_rate(4, 4, nul, nul) == hq.HQ_E_BADARG
+    assert L.hq_weight_quantize(nul, 16, nul, nul, nul) == hq.HQ_E_BADARG
     # sizes past the documented maxima (31-bit pixel and weight counts, 32-bit byte offsets) are refused
     for huge in (hq.problem(hq.HQ_CONV2D, 1 << 20, 64, 64, 16, 3, 3, 1, 1, 16),          # B*H*W = 2^32
                  hq.problem(hq.HQ_CONV2D, 1 << 16, 64, 64, 64, 1, 1, 1, 0, 4),           # B*H*W*C = 2^34 bytes

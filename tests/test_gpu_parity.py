@@ -203,6 +203,23 @@ def test_weight_prepare_layouts_and_sums(H, hq):
     assert np.array_equal(Wd.Wd.cpu().numpy().reshape(L.C, L.R, L.S, L.Cout), W.codes.transpose(3, 1, 2, 0))
 
 
+@pytest.mark.parametrize("n", [1, 3, 36864, 147456 + 5, 2359296])
+def test_weight_quantizer(H, hq, n):
+    """Q_W with the tensor's current min-max (Sec. 3.1, Sec. 5): codes and scale bit for bit."""
+    g = np.random.default_rng(n)
+    for w in ((g.standard_normal(n) * 0.05).astype(np.float32), np.zeros(n, np.float32),
+              (g.standard_normal(n) * 1e-3 + 0.7).astype(np.float32)):
+        want, s = oracle.quantize_weights(w)
+        Wf = H.dev(w)
+        Wq = torch.empty(n, dtype=torch.int8, device="cuda")
+        wq = hq.new_qparams(123.0, 7)
+        hq.hq_weight_quantize(Wf, n, Wq, wq)
+        torch.cuda.synchronize()
+        q = H.read_qparams(wq)
+        assert np.float32(q["scale"]) == s and int(q["zero_point"]) == 0
+        assert np.array_equal(Wq.cpu().numpy(), want)
+
+
 def test_asymmetric_gradients_and_symmetric_inputs(H, hq):
     """Zero points on the gradient side (the paper quantizes gradients asymmetrically in its
     ablations, Sec. 5.1) and none on the input side."""
