@@ -145,11 +145,10 @@ class DeviceLayer(Layer):
         Layer.__init__(self, hq, torch, wl, L, as_q(xc, sx, -128), as_q(wc, sw, 0), as_q(gc, sg, 0), state)
 
 
-def c5_step(hq, torch, wl, reps=3):
-    """One quantized training step over the ResNet-18-shaped stack at batch 256: 21 forward,
-    20 dgrad (none for the stem) and 21 wgrad launches with in-hindsight ranges, against the same
+def stack_step(hq, torch, wl, specs, label, reps=3):
+    """One quantized training step over a stack of layers at batch 256: a forward and a wgrad launch
+    per layer and a dgrad launch for all but the first, with in-hindsight ranges, against the same
     step with the dynamic two-pass path."""
-    specs = wl.resnet18_layers(B=256)
     # all range states of the step in one array ([activations of every layer], [gradients of every
     # layer]) and their statistics in another: one update launch after each sweep
     n = len(specs)
@@ -178,7 +177,7 @@ def c5_step(hq, torch, wl, reps=3):
     ops = sum(2 * wl.macs(L) * (3 if i > 0 else 2) for i, L in enumerate(specs))
     fb = sum(wl.fused_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
     db = sum(wl.dynamic_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
-    return {"workload": "ResNet-18-shaped stack, batch 256 @224x224: 21 fwd + 20 dgrad + 21 wgrad", "ops": ops,
+    return {"workload": "%s: %d fwd + %d dgrad + %d wgrad" % (label, n, n - 1, n), "ops": ops,
             "fused_ms_per_step": f_ms, "dynamic_ms_per_step": d_ms, "fused_tops": ops / (f_ms * 1e-3) / 1e12,
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb}}
 
@@ -394,7 +393,9 @@ def main():
             del ly
             torch.cuda.empty_cache()
         out["other_layers"] = extra
-        out["resnet18_step"] = c5_step(hq, torch, wl)
+        out["resnet18_step"] = stack_step(hq, torch, wl, wl.resnet18_layers(B=256), "ResNet-18-shaped stack, batch 256 @224x224")
+        torch.cuda.empty_cache()
+        out["vgg16_step"] = stack_step(hq, torch, wl, wl.vgg16_layers(B=256), "VGG16-shaped stack, batch 256 @64x64")
         torch.cuda.empty_cache()
 
     if args.calibrate_copy:

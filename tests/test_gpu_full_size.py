@@ -106,6 +106,29 @@ def test_c5_resnet18_stack_small_batch(H, hq):
         assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale)), L.name
 
 
+def test_vgg16_stack_small_batch(H, hq):
+    """Every layer of the VGG16-shaped stack (13 3x3 convs at 64 ... 4 pixels, three linear layers)
+    at batch 2: dynamic init + one in-hindsight iteration of fwd and dgrad (no dgrad for the first
+    layer), wgrad once; whole tensors against the oracle."""
+    layers = wl.vgg16_layers(B=2)
+    assert len(layers) == 16 and layers[13].C == 2048
+    for idx, L in enumerate(layers):
+        yt, gt = H.TensorTrack(0.9, False), H.TensorTrack(0.9, True)
+        Wdev = None
+        for t in range(2):
+            X, W, dY = wl.layer_inputs(L, 6, t, idx, image_input=(idx == 0))
+            if Wdev is None:
+                W0, Wdev = W, H.DevWeights(L, W)
+            Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+            yt.step(L, "fwd", X, W0, Xd, Wdev)
+            if idx > 0:
+                gt.step(L, "dgrad", dY, W0, dYd, Wdev)
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref), L.name
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale)), L.name
+
+
 @pytest.mark.parametrize("which", ["stem_7x7", "s2_conv0", "s3_short", "s4_conv2", "fc"])
 def test_c5_full_batch_sampled(H, hq, which):
     """Batch 256 (the size the step is quoted on): forward and dgrad of representative layers with

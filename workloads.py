@@ -212,6 +212,22 @@ def resnet18_layers(B=256, image=224):
     return layers
 
 
+def vgg16_layers(B=256, image=64, classes=200):
+    """VGG16-shaped stack (13 3x3 convs in five blocks with 2x2 pooling between them, three
+    linear layers) on 64x64 images with 200 classes, the size of the Tiny ImageNet runs; the
+    first layer's input carries 4 channels like the ResNet stem's."""
+    layers, cin, s = [], 4, image
+    for block, (cout, n) in enumerate(((64, 2), (128, 2), (256, 3), (512, 3), (512, 3))):
+        for i in range(n):
+            layers.append(conv("b%d_conv%d" % (block + 1, i), B, s, cin, cout, 3))
+            cin = cout
+        s //= 2
+    layers.append(linear("fc1", B, cin * s * s, 4096))
+    layers.append(linear("fc2", B, 4096, 4096))
+    layers.append(linear("fc3", B, 4096, classes))
+    return layers
+
+
 def layer_inputs(L, config, t, index, image_input=False, grad_b=1e-3):
     """Independent synthetic operands for one layer of a stack."""
     g = rng(config, t, 100 * index)
