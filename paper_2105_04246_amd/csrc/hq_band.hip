@@ -16,16 +16,20 @@
 //     filled with the zero-point code), staged once, as they lie in memory.  im2col never
 //     exists: a lane forms the address of "its" pixel under tap (r,s) when it reads the MFMA
 //     fragment, so an input byte crosses L2->LDS once per tile, not once per tap.  The next
-//     patch of a group is requested at the start of its MFMA phase (into registers) and written
-//     to LDS at the start of its epilogue phase, when nobody reads that patch.
+//     patch of a group is requested during its MFMA phase (into registers, a few rows between
+//     taps) and written to LDS at the start of its epilogue phase, when nobody reads that patch.
+//   * A band whose last tile is one wavefront's worth of pixels does not spend half steps on it:
+//     the second group, idle in half step 0, multiplies and requantizes it there from a third
+//     patch buffer.
 //   * v_mfma_i32_32x32x32_i8 with the weights as first operand: a lane then holds one output
 //     pixel and, because weight rows sit in LDS in permuted order, 16 CONSECUTIVE output
 //     channels, so the epilogue stores 16 codes (or 16 accumulators) per lane at once.
-//   * Epilogue per accumulator: subtract z_a * bsum[n]; fold into min / max; requantize with
-//     one fp32 multiply, round-half-even, clamp and pack (v_cvt_pk_u8_f32 saturates, which is
-//     the clamp on the full 8-bit grid).  Clipped values are counted exactly, but only in
-//     16-value groups whose own min / max cross integer thresholds found once per kernel by
-//     bisection on the fp32 requantization formula (it is monotone in the accumulator).
+//   * The accumulators start from -z_a * bsum[n] (the first MFMA's addend, held in registers), so
+//     they come out zero-point corrected.  Epilogue per accumulator: fold into min / max;
+//     requantize with one fp32 multiply, round-half-even, clamp and pack (v_cvt_pk_u8_f32
+//     saturates, which is the clamp on the full 8-bit grid).  Clipped values are counted
+//     exactly, but only in 16-value groups whose own min / max requantize outside the grid
+//     (requantization is monotone in the accumulator).
 #include "hq_device.h"
 #include <type_traits>
 #include "hq_internal.h"
