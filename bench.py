@@ -216,6 +216,30 @@ def range_tracking(hq, torch, lay, op, scales, report):
     return rows
 
 
+def tensor_quantizer(hq, torch, wl):
+    """Element-wise quantizer of an FP32 tensor the size of the headline layer's output (a
+    normalisation / activation output): the in-hindsight single pass against the dynamic two-pass
+    one, each as GB/s of its own algorithmic traffic (5 and 9 bytes per element)."""
+    n = wl.nelem(wl.out_shape(wl.c2_layer()))
+    x = torch.from_numpy(wl.real_activation(wl.rng(2, 0, 77), n)).cuda()
+    q = torch.empty(n, dtype=torch.int8, device="cuda")
+    r, st, qp = hq.new_range(0.9, False), hq.new_stats(1), hq.new_qparams(1.0, 0)
+    hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_CURRENT, x, n, r, q, qp, st)
+    hq.hq_range_update(r, st)
+
+    def static():
+        hq.hq_tensor_quantize(x, n, r, q, qp, st)
+        hq.hq_range_update(r, st)
+
+    def dynamic():
+        hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_CURRENT, x, n, r, q, qp, st)
+        hq.hq_range_update(r, st)
+
+    s_ms, d_ms = time_calls(torch, static, 20), time_calls(torch, dynamic, 20)
+    return {"elements": n, "in_hindsight_ms": s_ms, "dynamic_ms": d_ms, "speedup": d_ms / s_ms,
+            "in_hindsight_alg_GBs": 5 * n / (s_ms * 1e-3) / 1e9, "dynamic_alg_GBs": 9 * n / (d_ms * 1e-3) / 1e9}
+
+
 def time_calls(torch, fn, reps, warmup=2):
     """Average milliseconds of fn() over `reps` back-to-back launches, HIP events on the launch stream."""
     for _ in range(warmup):
@@ -396,6 +420,8 @@ def main():
         out["resnet18_step"] = stack_step(hq, torch, wl, wl.resnet18_layers(B=256), "ResNet-18-shaped stack, batch 256 @224x224")
         torch.cuda.empty_cache()
         out["vgg16_step"] = stack_step(hq, torch, wl, wl.vgg16_layers(B=256), "VGG16-shaped stack, batch 256 @64x64")
+        torch.cuda.empty_cache()
+        out["real_tensor_quantizer"] = tensor_quantizer(hq, torch, wl)
         torch.cuda.empty_cache()
 
     if args.calibrate_copy:

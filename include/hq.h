@@ -84,7 +84,7 @@ typedef struct {
 typedef struct {
     int32_t  acc_min, acc_max;
     float    acc_scale;
-    uint32_t reserved;
+    uint32_t fp32_keys;       /* 0: accumulator units (the GEMMs); 1: see hq_tensor_quantize */
     uint64_t clip_lo, clip_hi, count;
     uint8_t  pad[88];
     hq_stats_part part[HQ_STATS_PARTS];
@@ -219,13 +219,39 @@ int hq_stats_fold(hq_stats *st, int32_t n, void *stream);
 int hq_weight_prepare(const hq_problem *p /* host */, const int8_t *W,
                       int8_t *Wd, int32_t *wsum, int32_t *wdsum, void *stream);
 
-/* Q_W, the weight quantizer (Sec. 3.1: its range does not depend on the batch; Sec. 5: "the weights
- * are always quantized with the current min-max method"): symmetric 8-bit quantization of an
+/* Q_W, the weight quantizer (Sec. 3.1: its range does not depend on the batch; Sec. 5.2: weights
+ * take the min-max of the tensor as it is now): symmetric 8-bit quantization of an
  * FP32 tensor with its own range, s = max|w| / 127 (1 for an all-zero tensor),
  * code = clamp(rne(w / s), -127, 127), each fp32 operation rounded once.  Element-wise: Wf and
  * Wq [n] in any layout (follow with hq_weight_prepare for the dgrad layout and the sums).
  * wq receives {s, 0}.  Finite inputs are assumed.                                             */
 int hq_weight_quantize(const float *Wf, size_t n, int8_t *Wq, hq_qparams *wq, void *stream);
+
+/* In-hindsight quantization of a real-valued tensor that no GEMM of this library produced (the
+ * output of a normalisation or activation layer, a loss gradient), so that a chain of layers runs
+ * without the host: static quantization (Sec. 3.2) with the quantizer r->qp that eq. (2)-(3)
+ * pre-computed, one pass over X (4 bytes read, 1 byte written per element).  A real value is
+ * treated as an accumulator output of unit 1: code = clamp(rne(x * m), qlo - z, qhi - z) + z
+ * with m = 1 / s, each fp32 operation rounded once, as in the fused epilogue of the GEMMs.
+ *   X [n] fp32 and Q [n] codes, 16-byte aligned, any layout (element-wise); n may be 0
+ *   q_out  receives r->qp (travels with Q)
+ *   st     minimum and maximum of X, the clip counts and the element count are merged into it; the
+ *          minimum and maximum are held as order-preserving integer keys of the fp32 values and
+ *          st->fp32_keys is set to 1, which hq_range_update reads; a record serves either real-valued
+ *          tensors or GEMM outputs between two updates, not both
+ * While r is not initialized its quantizer is {1, 0}: take hq_tensor_quantize_dynamic for the
+ * first batch (Sec. 4.1).  Finite inputs are assumed.                                          */
+int hq_tensor_quantize(const float *X, size_t n, const hq_range *r, int8_t *Q, hq_qparams *q_out,
+                       hq_stats *st, void *stream);
+
+/* The dynamic counterpart (eq. (1)): a first pass reads X for its minimum and maximum, a
+ * one-wavefront kernel derives the quantizer, a second pass reads X again and writes the codes
+ * (8 bytes read, 1 byte written per element).  mode, r, st as for hq_gemm_dynamic: HQ_DYN_CURRENT
+ * quantizes with this tensor's own range and sets q^0 if r is not initialized; HQ_DYN_RUNNING
+ * moves r by eq. (2)-(3) with this tensor first and quantizes with the result.  st is left
+ * filled, so hq_range_update can follow.  With n == 0, q_out receives r->qp and r is untouched. */
+int hq_tensor_quantize_dynamic(int32_t mode, const float *X, size_t n, hq_range *r, int8_t *Q,
+                               hq_qparams *q_out, hq_stats *st, void *stream);
 
 /* Measurement aid, not part of the method: launches a kernel in which every wavefront issues
  * iters * 8 int8 MFMAs (32x32x32, operands and accumulators in registers, no memory traffic

@@ -58,10 +58,13 @@ class Range(C.Structure):
                 ("initialized", C.c_int32), ("scale", C.c_float), ("zero_point", C.c_int32)]
 
     @staticmethod
-    def new(eta=0.9, symmetric=False):
+    def new(eta=0.9, symmetric=False, bits=8):
+        """b-bit grid held in 8-bit storage: -2^(b-1)..2^(b-1)-1, symmetric without its lowest code."""
+        assert 2 <= bits <= 8
+        top = 2 ** (bits - 1) - 1
         if symmetric:
-            return Range(0.0, 0.0, eta, -127, 127, 1, 0, 1.0, 0)
-        return Range(0.0, 0.0, eta, -128, 127, 0, 0, 1.0, 0)
+            return Range(0.0, 0.0, eta, -top, top, 1, 0, 1.0, 0)
+        return Range(0.0, 0.0, eta, -top - 1, top, 0, 0, 1.0, 0)
 
 
 def lib():
@@ -90,6 +93,9 @@ def lib():
         L.hqo_range_update.argtypes = [C.POINTER(Range), C.c_int32, C.c_int32, C.c_float]
         L.hqo_wgrad_scale.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, f32p]
         L.hqo_quantize_weights.argtypes = [f32p, C.c_int64, i8p, f32p]
+        L.hqo_range_update_real.argtypes = [C.POINTER(Range), C.c_float, C.c_float]
+        L.hqo_quantize_tensor.argtypes = [f32p, C.c_int64, C.c_float, C.c_int, C.c_int, C.c_int, i8p,
+                                          C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), f32p, f32p]
         for f in ("hqo_fwd", "hqo_fwd_rows", "hqo_dgrad", "hqo_dgrad_rows", "hqo_wgrad"):
             getattr(L, f).restype = C.c_int
         _lib = L
@@ -203,6 +209,50 @@ def range_update(r, acc_min, acc_max, acc_scale):
     """eq. (2)-(3) in place on ``r``; the first call sets q^0."""
     lib().hqo_range_update(C.byref(r), int(acc_min), int(acc_max), float(acc_scale))
     return r
+
+
+def range_update_real(r, gmin, gmax):
+    """eq. (2)-(3) in place on ``r`` from a tensor's minimum and maximum in real units."""
+    lib().hqo_range_update_real(C.byref(r), float(np.float32(gmin)), float(np.float32(gmax)))
+    return r
+
+
+def quantize_tensor(x, scale, zero_point, qlo, qhi):
+    """Static quantization of a real-valued tensor with a given quantizer (Sec. 3.2).
+    Returns dict(codes, clip_lo, clip_hi, min, max, count)."""
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty(x.shape, np.int8)
+    lo, hi = C.c_uint64(), C.c_uint64()
+    mn, mx = C.c_float(), C.c_float()
+    lib().hqo_quantize_tensor(_p(x, C.c_float), x.size, float(scale), int(zero_point), int(qlo), int(qhi),
+                              _p(out, C.c_int8), C.byref(lo), C.byref(hi), C.byref(mn), C.byref(mx))
+    return dict(codes=out, clip_lo=lo.value, clip_hi=hi.value, min=np.float32(mn.value), max=np.float32(mx.value),
+                count=x.size)
+
+
+def tensor_step(x, r, mode="hindsight"):
+    """One iteration for a real-valued tensor with range state ``r``.
+    "hindsight": Sec. 4.1 -- the first batch is quantized with its own min-max, which becomes q^0;
+    later batches with the pre-computed q^t; the tensor's min-max then moves the range (eq. (2)-(3)).
+    "current": eq. (1), every batch with its own min-max (r only takes q^0 and the updates).
+    "running": the range is first moved by eq. (2)-(3) with this tensor, then used (Sec. 4.1)."""
+    x = np.ascontiguousarray(x, np.float32)
+    gmin, gmax = x.min(), x.max()
+    if mode == "running":
+        range_update_real(r, gmin, gmax)
+        out = quantize_tensor(x, r.scale, r.zero_point, r.qlo, r.qhi)
+        out.update(scale=np.float32(r.scale), zero_point=r.zero_point)
+        return out
+    if mode == "current" or not r.initialized:
+        if not r.initialized:
+            range_update_real(r, gmin, gmax)                           # sets q^0
+        s, z = qparams(gmin, gmax, r.symmetric, r.qlo, r.qhi)
+    else:
+        s, z = np.float32(r.scale), r.zero_point
+    out = quantize_tensor(x, s, z, r.qlo, r.qhi)
+    out.update(scale=np.float32(s), zero_point=int(z))
+    range_update_real(r, gmin, gmax)                                   # q^{t+1}
+    return out
 
 
 def quantize_weights(w):

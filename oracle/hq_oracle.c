@@ -337,11 +337,10 @@ void hqo_requant_sr(const int32_t *c, int64_t n, float acc_scale, float s_y, int
     *clip_lo = nlo; *clip_hi = nhi;
 }
 
-/* In-hindsight min-max, eq. (2)-(3); first call sets q^0 (Sec. 4.1).         */
-void hqo_range_update(hqo_range *r, int32_t acc_min, int32_t acc_max, float acc_scale)
+/* In-hindsight min-max, eq. (2)-(3), from the minimum and maximum of the tensor in real units;
+ * first call sets q^0 (Sec. 4.1).                                             */
+void hqo_range_update_real(hqo_range *r, float gmin, float gmax)
 {
-    float gmin = acc_scale * (float)acc_min;
-    float gmax = acc_scale * (float)acc_max;
     if (!r->initialized) {
         r->qmin = gmin; r->qmax = gmax; r->initialized = 1;
     } else {
@@ -352,6 +351,32 @@ void hqo_range_update(hqo_range *r, int32_t acc_min, int32_t acc_max, float acc_
         r->qmax = a + b;
     }
     hqo_qparams(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi, &r->scale, &r->zero_point);
+}
+
+/* The same from accumulator statistics: one accumulator unit is worth acc_scale.  */
+void hqo_range_update(hqo_range *r, int32_t acc_min, int32_t acc_max, float acc_scale)
+{
+    hqo_range_update_real(r, acc_scale * (float)acc_min, acc_scale * (float)acc_max);
+}
+
+/* Static quantization (Sec. 3.2) of a real-valued tensor with a given quantizer (s, z): the
+ * arithmetic of hqo_requant with the real value in the accumulator's place and unit 1, so
+ * m = 1 / s.  Also returns the tensor's minimum and maximum, which eq. (2)-(3) consume.  */
+void hqo_quantize_tensor(const float *x, int64_t n, float s, int z, int qlo, int qhi,
+                         int8_t *out, uint64_t *clip_lo, uint64_t *clip_hi, float *xmin, float *xmax)
+{
+    float m = 1.0f / s;
+    float flo = (float)(qlo - z), fhi = (float)(qhi - z);
+    uint64_t nlo = 0, nhi = 0;
+    for (int64_t i = 0; i < n; i++) {
+        float r = rintf(x[i] * m);
+        if (r < flo) { r = flo; nlo++; }
+        if (r > fhi) { r = fhi; nhi++; }
+        out[i] = (int8_t)((int)r + z);
+        if (i == 0 || x[i] < *xmin) *xmin = x[i];
+        if (i == 0 || x[i] > *xmax) *xmax = x[i];
+    }
+    *clip_lo = nlo; *clip_hi = nhi;
 }
 
 /* Q_W (Sec. 3.1): the weight quantizer's range does not depend on the batch; the paper always

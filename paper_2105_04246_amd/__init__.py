@@ -24,7 +24,7 @@ RANGE = np.dtype([("qmin", "<f4"), ("qmax", "<f4"), ("eta", "<f4"), ("qlo", "<i4
 STATS_PARTS = 64
 STATS_PART = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("clip_lo", "<u8"), ("clip_hi", "<u8"),
                        ("pad", "u1", (104,))])
-STATS = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("acc_scale", "<f4"), ("reserved", "<u4"),
+STATS = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("acc_scale", "<f4"), ("fp32_keys", "<u4"),
                   ("clip_lo", "<u8"), ("clip_hi", "<u8"), ("count", "<u8"), ("pad", "u1", (88,)),
                   ("part", STATS_PART, (STATS_PARTS,))])
 assert QPARAMS.itemsize == 8 and RANGE.itemsize == 36 and STATS_PART.itemsize == 128
@@ -48,7 +48,8 @@ class HqError(RuntimeError):
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_range_update",
            "hq_range_update_batch",
-           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_probe_mfma_rate",
+           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_dynamic",
+           "hq_probe_mfma_rate",
            "hq_error_string")
 
 
@@ -77,6 +78,8 @@ def lib():
         L.hq_weight_prepare.argtypes = [PP, vp, vp, vp, vp, vp]
         L.hq_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, vp, vp]
         L.hq_weight_quantize.argtypes = [vp, C.c_size_t, vp, vp, vp]
+        L.hq_tensor_quantize.argtypes = [vp, C.c_size_t, vp, vp, vp, vp, vp]
+        L.hq_tensor_quantize_dynamic.argtypes = [C.c_int32, vp, C.c_size_t, vp, vp, vp, vp, vp]
         for f in EXPORTS[1:-1]:
             getattr(L, f).restype = C.c_int
         _lib = L
@@ -159,6 +162,16 @@ def hq_weight_quantize(Wf, n, Wq, wq, stream=None):
     _check("hq_weight_quantize", lib().hq_weight_quantize(_ptr(Wf), n, _ptr(Wq), _ptr(wq), _stream(stream)))
 
 
+def hq_tensor_quantize(X, n, r, Q, q_out, st, stream=None):
+    _check("hq_tensor_quantize", lib().hq_tensor_quantize(_ptr(X), n, _ptr(r), _ptr(Q), _ptr(q_out), _ptr(st),
+                                                          _stream(stream)))
+
+
+def hq_tensor_quantize_dynamic(mode, X, n, r, Q, q_out, st, stream=None):
+    _check("hq_tensor_quantize_dynamic", lib().hq_tensor_quantize_dynamic(mode, _ptr(X), n, _ptr(r), _ptr(Q),
+                                                                          _ptr(q_out), _ptr(st), _stream(stream)))
+
+
 def hq_probe_mfma_rate(blocks, iters, sink, stream=None):
     """Launches the register-only MFMA loop; returns the int8 operations it issues."""
     _check("hq_probe_mfma_rate", lib().hq_probe_mfma_rate(blocks, iters, _ptr(sink), _stream(stream)))
@@ -191,11 +204,15 @@ def new_qparams(scale, zero_point, device="cuda"):
     return to_device(rec, device)
 
 
-def new_range(eta=0.9, symmetric=False, device="cuda"):
-    """Uninitialised range state on the 8-bit grid (asymmetric -128..127, symmetric -127..127)."""
+def new_range(eta=0.9, symmetric=False, device="cuda", bits=8):
+    """Uninitialised range state on a b-bit grid in 8-bit storage (8 bits: asymmetric -128..127,
+    symmetric -127..127; fewer bits: -2^(b-1)..2^(b-1)-1, symmetric without the lowest code)."""
+    if not 2 <= bits <= 8:
+        raise ValueError("bits must be 2..8")
+    top = 2 ** (bits - 1) - 1
     rec = np.zeros((), RANGE)
     rec["eta"], rec["symmetric"] = eta, int(symmetric)
-    rec["qlo"], rec["qhi"] = (-127, 127) if symmetric else (-128, 127)
+    rec["qlo"], rec["qhi"] = (-top, top) if symmetric else (-top - 1, top)
     rec["scale"] = 1.0
     return to_device(rec, device)
 

@@ -10,21 +10,6 @@ inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP; }
 
-// ---------------------------------------------------------------------------------------
-// eq. (2)-(3): q <- (1 - eta) * g + eta * q, each product and the sum rounded once.
-// ---------------------------------------------------------------------------------------
-__device__ inline void ema_update(hq_range *r, float gmin, float gmax)
-{
-    if (!r->initialized) {
-        r->qmin = gmin; r->qmax = gmax; r->initialized = 1;
-    } else {
-        const float w = __fsub_rn(1.0f, r->eta);
-        r->qmin = __fadd_rn(__fmul_rn(w, gmin), __fmul_rn(r->eta, r->qmin));
-        r->qmax = __fadd_rn(__fmul_rn(w, gmax), __fmul_rn(r->eta, r->qmax));
-    }
-    r->qp = hq_qparams_from_range(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi);
-}
-
 // Empties a record; called by the 64 lanes of one wavefront (lane = partial record).
 __device__ inline void stats_clear_wave(hq_stats *st)
 {
@@ -32,7 +17,7 @@ __device__ inline void stats_clear_wave(hq_stats *st)
     hq_stats_part *p = &st->part[lane];
     p->acc_min = INT_MAX; p->acc_max = INT_MIN; p->clip_lo = 0; p->clip_hi = 0;
     if (lane == 0) {
-        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
+        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->fp32_keys = 0;
         st->clip_lo = 0; st->clip_hi = 0; st->count = 0;
     }
 }
@@ -43,14 +28,16 @@ __global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats 
     // every load of the kernel is issued before anything waits: one memory round trip
     hq_range rr = *r;
     const float acc_scale = st->acc_scale;
+    const unsigned fp32_keys = st->fp32_keys;
     const unsigned long long count = st->count;
     const HqStatsFolded f = hq_stats_fold_wave(st);
     if (threadIdx.x == 0) {
         if (count != 0) {
-            ema_update(&rr, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
+            if (fp32_keys) hq_ema_update(&rr, hq_key_float(f.acc_min), hq_key_float(f.acc_max));
+            else hq_ema_update(&rr, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
             *r = rr;
         }
-        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->reserved = 0;
+        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->fp32_keys = 0;
         st->clip_lo = 0; st->clip_hi = 0; st->count = 0;           // the partial records are already empty
     }
 }
@@ -67,10 +54,10 @@ __global__ __launch_bounds__(64) void dynamic_mid_kernel(int mode, hq_range *r, 
     const float gmin = __fmul_rn(st->acc_scale, (float)f.acc_min);
     const float gmax = __fmul_rn(st->acc_scale, (float)f.acc_max);
     if (mode == HQ_DYN_RUNNING) {
-        ema_update(r, gmin, gmax);                 // running min-max: this tensor moves the range first
+        hq_ema_update(r, gmin, gmax);                 // running min-max: this tensor moves the range first
         *outq = r->qp;
     } else {
-        if (!r->initialized) ema_update(r, gmin, gmax);          // q^0 = min-max of the first batch
+        if (!r->initialized) hq_ema_update(r, gmin, gmax);          // q^0 = min-max of the first batch
         *outq = hq_qparams_from_range(gmin, gmax, r->symmetric, r->qlo, r->qhi);   // eq. (1)
     }
 }

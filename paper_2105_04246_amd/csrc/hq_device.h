@@ -40,6 +40,31 @@ __device__ inline hq_qparams hq_qparams_from_range(float qmin, float qmax, int s
     return q;
 }
 
+// Order-preserving map between fp32 values and signed 32-bit keys (its own inverse on the bit
+// pattern): integer min / max and their atomics then order real values.  Used by the statistics
+// of real-valued tensors; -0 is made +0 first so that equal values have equal keys.
+__device__ inline int hq_float_key(float x)
+{
+    const int b = __float_as_int(x + 0.0f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ inline float hq_key_float(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+
+// ---------------------------------------------------------------------------------------
+// eq. (2)-(3): q <- (1 - eta) * g + eta * q, each product and the sum rounded once.
+// ---------------------------------------------------------------------------------------
+__device__ inline void hq_ema_update(hq_range *r, float gmin, float gmax)
+{
+    if (!r->initialized) {
+        r->qmin = gmin; r->qmax = gmax; r->initialized = 1;
+    } else {
+        const float w = __fsub_rn(1.0f, r->eta);
+        r->qmin = __fadd_rn(__fmul_rn(w, gmin), __fmul_rn(r->eta, r->qmin));
+        r->qmax = __fadd_rn(__fmul_rn(w, gmax), __fmul_rn(r->eta, r->qmax));
+    }
+    r->qp = hq_qparams_from_range(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi);
+}
+
 // Everything the epilogue needs to turn a zero-point-corrected accumulator into a code.
 struct HqRequant {
     float mult;        // (s_a * s_b) / s_out

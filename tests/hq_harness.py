@@ -124,10 +124,10 @@ def assert_range_close(gpu_r, ref_r, rel=1e-6):
 class TensorTrack:
     """One quantized output tensor followed over iterations on both sides: device range
     state + stats, and the oracle's Range."""
-    def __init__(self, eta=0.9, symmetric=False, state=None):
+    def __init__(self, eta=0.9, symmetric=False, state=None, bits=8):
         """state: (range record, statistics record) views into caller-owned arrays, for the batched update."""
-        self.r, self.st = state if state is not None else (hq.new_range(eta, symmetric), hq.new_stats(1))
-        self.ref = oracle.Range.new(eta, symmetric)
+        self.r, self.st = state if state is not None else (hq.new_range(eta, symmetric, bits=bits), hq.new_stats(1))
+        self.ref = oracle.Range.new(eta, symmetric, bits)
 
     def step(self, L, op, A_q, W_q, A_dev, W_dev, check=True, update=True, seed=None):
         """Runs iteration t on both sides (dynamic init at t=0, fused afterwards), compares

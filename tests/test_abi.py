@@ -59,7 +59,7 @@ def test_struct_views_match_header_sizes():
 
     class ST(ctypes.Structure):
         _fields_ = [("acc_min", ctypes.c_int32), ("acc_max", ctypes.c_int32), ("acc_scale", ctypes.c_float),
-                    ("reserved", ctypes.c_uint32), ("clip_lo", ctypes.c_uint64), ("clip_hi", ctypes.c_uint64),
+                    ("fp32_keys", ctypes.c_uint32), ("clip_lo", ctypes.c_uint64), ("clip_hi", ctypes.c_uint64),
                     ("count", ctypes.c_uint64), ("pad", ctypes.c_uint8 * 88), ("part", PT * 64)]
 
     assert ctypes.sizeof(QP) == hq.QPARAMS.itemsize
@@ -86,6 +86,10 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.hq_range_update(nul, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_probe_mfma_rate(4, 4, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_weight_quantize(nul, 16, nul, nul, nul) == hq.HQ_E_BADARG
+    assert L.hq_tensor_quantize(nul, 16, nul, nul, nul, nul, nul) == hq.HQ_E_BADARG
+    assert L.hq_tensor_quantize_dynamic(0, nul, 16, nul, nul, nul, nul, nul) == hq.HQ_E_BADARG
+    assert L.hq_tensor_quantize_dynamic(7, nul, 0, ctypes.c_void_p(128), nul, ctypes.c_void_p(128),
+                                        ctypes.c_void_p(128), nul) == hq.HQ_E_BADARG      # bad mode, caught before any launch
     # sizes past the documented maxima (31-bit pixel and weight counts, 32-bit byte offsets) are refused
     for huge in (hq.problem(hq.HQ_CONV2D, 1 << 20, 64, 64, 16, 3, 3, 1, 1, 16),          # B*H*W = 2^32
                  hq.problem(hq.HQ_CONV2D, 1 << 16, 64, 64, 64, 1, 1, 1, 0, 4),           # B*H*W*C = 2^34 bytes

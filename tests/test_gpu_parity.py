@@ -381,6 +381,107 @@ def test_stochastic_rounding_dgrad(H, hq, L):
         assert not np.array_equal(a, b) and np.abs(a.astype(int) - b.astype(int)).max() <= 1
 
 
+def _real_batch(kind, n, t, seed):
+    g = np.random.default_rng([seed, t, n])
+    if kind == "act":
+        return wl.real_activation(g, n, gain=1.05 ** t)
+    return wl.real_gradient(g, n, 1e-3 * 0.8 ** t)
+
+
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 4096 * 3 + 5, 1_000_003])
+@pytest.mark.parametrize("kind", ["act", "grad"])
+def test_real_tensor_in_hindsight_quantizer(H, hq, n, kind):
+    """Element-wise quantizer of FP32 tensors over four iterations (dynamic for the first batch, then
+    in hindsight): codes, quantizer, clip counts, minimum / maximum bit for bit; range state after
+    each update within 1e-6."""
+    sym = kind == "grad"
+    r, st = hq.new_range(0.9, sym), hq.new_stats(1)
+    ref = oracle.Range.new(0.9, sym)
+    Q = torch.empty(max(n, 1), dtype=torch.int8, device="cuda")
+    qp = hq.new_qparams(0.0, 99)
+    for t in range(4):
+        x = _real_batch(kind, n, t, 31)
+        xd = torch.from_numpy(x).cuda()
+        if n == 0:
+            hq.hq_tensor_quantize(xd, 0, r, Q, qp, st)
+            assert int(H.read_stats(st)["count"]) == 0
+            hq.hq_range_update(r, st)
+            assert int(H.read_range(r)["initialized"]) == 0
+            hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_CURRENT, xd, 0, r, Q, qp, st)
+            got = H.read_qparams(qp)
+            assert float(got["scale"]) == 1.0 and int(got["zero_point"]) == 0
+            continue
+        want = oracle.tensor_step(x, ref, "hindsight")
+        if t == 0:
+            hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_CURRENT, xd, n, r, Q, qp, st)
+        else:
+            hq.hq_tensor_quantize(xd, n, r, Q, qp, st)
+        got_st, got_qp = H.read_stats(st), H.read_qparams(qp)
+        hq.hq_range_update(r, st)
+        codes = Q[:n].cpu().numpy()
+        assert np.float32(got_qp["scale"]) == want["scale"] and int(got_qp["zero_point"]) == want["zero_point"]
+        assert np.array_equal(codes, want["codes"]), int((codes != want["codes"]).sum())
+        assert int(got_st["fp32_keys"]) == 1 and int(got_st["count"]) == n
+        assert (int(got_st["clip_lo"]), int(got_st["clip_hi"])) == (want["clip_lo"], want["clip_hi"])
+        key = lambda k: np.array([k ^ ((k >> 31) & 0x7fffffff)], np.int32).view(np.float32)[0]
+        assert key(int(got_st["acc_min"])) == want["min"] and key(int(got_st["acc_max"])) == want["max"]
+        H.assert_range_close(H.read_range(r), ref)
+        assert int(H.read_stats(st)["count"]) == 0 and int(H.read_stats(st)["fp32_keys"]) == 0
+        if t >= 2 and n > 1000 and kind == "act":
+            assert want["clip_hi"] > 0                      # growing activations: the past range clips
+
+
+@pytest.mark.parametrize("mode", ["current", "running"])
+def test_real_tensor_dynamic_quantizers(H, hq, mode):
+    """eq. (1) and the running variant on FP32 tensors, asymmetric and symmetric, 4- and 8-bit grids."""
+    n = 70_001
+    for sym, bits in [(False, 8), (True, 8), (False, 4), (True, 4)]:
+        r, st = hq.new_range(0.9, sym, bits=bits), hq.new_stats(1)
+        ref = oracle.Range.new(0.9, sym, bits)
+        Q = torch.empty(n, dtype=torch.int8, device="cuda")
+        qp = hq.new_qparams(0.0, 99)
+        for t in range(3):
+            x = _real_batch("grad" if sym else "act", n, t, 57)
+            if not sym:
+                x -= np.float32(0.3)                       # a range that does not start at zero
+            want = oracle.tensor_step(x, ref, mode)
+            hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_RUNNING if mode == "running" else hq.HQ_DYN_CURRENT,
+                                          torch.from_numpy(x).cuda(), n, r, Q, qp, st)
+            got_st, got_qp = H.read_stats(st), H.read_qparams(qp)
+            if mode == "current":
+                hq.hq_range_update(r, st)
+            else:
+                hq.hq_stats_reset(st)
+            assert np.float32(got_qp["scale"]) == want["scale"] and int(got_qp["zero_point"]) == want["zero_point"]
+            assert np.array_equal(Q.cpu().numpy(), want["codes"])
+            assert (int(got_st["clip_lo"]), int(got_st["clip_hi"])) == (want["clip_lo"], want["clip_hi"])
+            H.assert_range_close(H.read_range(r), ref)
+
+
+NARROW = [wl.conv("nb_band", 2, 20, 64, 64, 3), wl.conv("nb_gemm", 2, 9, 24, 40, 3),
+          wl.conv("nb_bandw", 1, 12, 128, 128, 3), wl.conv("nb_first", 2, 23, 4, 48, 7, stride=2),
+          wl.depthwise("nb_dw", 2, 13, 48), wl.linear("nb_lin", 300, 72, 80)]
+
+
+@pytest.mark.parametrize("bits", [2, 4, 6])
+@pytest.mark.parametrize("L", NARROW, ids=[l.name for l in NARROW])
+def test_output_grids_narrower_than_eight_bits(H, hq, L, bits):
+    """The range state carries its grid (qlo, qhi): a b-bit output grid in 8-bit storage goes
+    through every kernel's epilogue unchanged, bit for bit, with the clip counts of that grid;
+    the last iteration rounds the gradient stochastically."""
+    y_track, g_track = H.TensorTrack(0.9, False, bits=bits), H.TensorTrack(0.9, True, bits=bits)
+    Wdev = None
+    for t in range(3):
+        X, W, dY = rand_layer_inputs(L, 7000 + 10 * bits + t)
+        if Wdev is None:
+            W0, Wdev = W, H.DevWeights(L, W)
+        Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+        y, _ = y_track.step(L, "fwd", X, W0, Xd, Wdev)
+        g, _ = g_track.step(L, "dgrad", dY, W0, dYd, Wdev, seed=77 if t == 2 else None)
+        top = 2 ** (bits - 1) - 1
+        assert y.min() >= -top - 1 and y.max() <= top and g.min() >= -top and g.max() <= top
+
+
 # ---------------------------------------------------------------------------------------
 # Degenerate tensors and ranges
 # ---------------------------------------------------------------------------------------

@@ -218,8 +218,10 @@ def test_qparams_hand_values():
 
 def test_quantize_dequantize_idempotent_monotone_in_grid():
     g = np.random.default_rng(4)
-    for sym in (0, 1):
-        qlo, qhi = (-127, 127) if sym else (-128, 127)
+    for sym, bits in [(0, 8), (1, 8), (0, 6), (1, 6), (0, 4), (1, 4), (0, 2), (1, 2)]:
+        r0 = oracle.Range.new(0.9, bool(sym), bits)
+        qlo, qhi = r0.qlo, r0.qhi
+        assert qhi == 2 ** (bits - 1) - 1 and qlo == (-qhi if sym else -qhi - 1)      # b-bit grid
         for _ in range(20):
             lo, hi = -abs(g.normal()) * 10 ** g.uniform(-3, 3), abs(g.normal()) * 10 ** g.uniform(-3, 3)
             s, z = oracle.qparams(lo, hi, sym, qlo, qhi)
@@ -518,6 +520,87 @@ def test_weight_quantizer_current_min_max():
     # ties go to the even code: 0.5 and 1.5 steps of a tensor whose scale is exactly 1/64
     codes, s = oracle.quantize_weights(np.array([127 / 64, 0.5 / 64, 1.5 / 64, 2.5 / 64, -0.5 / 64, -1.5 / 64], np.float32))
     assert s == f32(1 / 64) and codes.tolist() == [127, 0, 2, 2, 0, -2]
+
+
+def test_real_tensor_quantizer_hand_values_bounds_and_statistics():
+    """Static quantization of a real-valued tensor (Sec. 3.2): hand values with ties, clip counts,
+    exact minimum / maximum, the half-step error bound inside the range (fp64 brute force), and
+    agreement with the accumulator path for integer-valued inputs."""
+    # scale 1/4, zero point -3, full asymmetric grid: x = k/4 -> code k - 3; ties to the even integer
+    x = np.array([0.0, 0.25, -0.25, 0.125, 0.375, -0.125, -0.375, 32.5, 32.75, 33.0, -31.25, -31.5, 1e6, -1e6], np.float32)
+    o = oracle.quantize_tensor(x, 0.25, -3, -128, 127)
+    assert o["codes"].tolist() == [-3, -2, -4, -3, -1, -3, -5, 127, 127, 127, -128, -128, 127, -128]
+    assert (o["clip_lo"], o["clip_hi"]) == (2, 3)          # 32.5 -> code 127 exactly: inside; 32.75, 33, 1e6 above; -31.5, -1e6 below
+    assert o["min"] == f32(-1e6) and o["max"] == f32(1e6) and o["count"] == x.size
+    g = np.random.default_rng(21)
+    for sym in (0, 1):
+        x = (g.standard_normal(30000) * 3).astype(np.float32)
+        lo, hi = np.percentile(x, 1), np.percentile(x, 99)
+        qlo, qhi = (-127, 127) if sym else (-128, 127)
+        s, z = oracle.qparams(lo, hi, sym, qlo, qhi)
+        o = oracle.quantize_tensor(x, s, z, qlo, qhi)
+        assert o["min"] == x.min() and o["max"] == x.max()
+        ideal = x.astype(np.float64) / float(s) + z             # unrounded code in fp64
+        inside = (ideal > qlo + 1e-3) & (ideal < qhi - 1e-3)
+        assert np.abs(o["codes"][inside] - ideal[inside]).max() <= 0.5 + 1e-4
+        assert np.all(o["codes"][ideal >= qhi] == qhi) and np.all(o["codes"][ideal <= qlo] == qlo)
+        # clipped = rounded code outside the grid: ideal beyond the edge by more than half a step
+        margin = 1e-3
+        assert int((ideal < qlo - 0.5 - margin).sum()) <= o["clip_lo"] <= int((ideal < qlo - 0.5 + margin).sum())
+        assert int((ideal > qhi + 0.5 + margin).sum()) <= o["clip_hi"] <= int((ideal > qhi + 0.5 - margin).sum())
+        assert o["clip_lo"] > 50 and o["clip_hi"] > 50
+        # integer-valued reals of unit 1 are accumulators of scale 1
+        c = g.integers(-5000, 5000, 4000).astype(np.int32)
+        codes, nlo, nhi = oracle.requant(c, 1.0, f32(37.5), z, qlo, qhi)
+        o = oracle.quantize_tensor(c.astype(np.float32), f32(37.5), z, qlo, qhi)
+        assert np.array_equal(o["codes"], codes) and (o["clip_lo"], o["clip_hi"]) == (nlo, nhi)
+
+
+def test_real_tensor_step_follows_the_three_estimators():
+    """Sec. 4.1 / eq. (1)-(3) on real-valued tensors: which range quantizes batch t under each
+    estimator, checked against the recursion evaluated in fp64 by hand."""
+    eta = 0.9
+    mins = [-1.0, -2.0, -0.5, -4.0, -1.5]
+    maxs = [3.0, 1.0, 6.0, 2.0, 2.5]
+    g = np.random.default_rng(5)
+    batches = []
+    for lo, hi in zip(mins, maxs):
+        x = g.uniform(lo, hi, 1000).astype(np.float32)
+        x[0], x[1] = lo, hi
+        batches.append(x)
+    grid = 255.0
+    # in hindsight: batch 0 with its own range; batch t with the average of batches < t
+    r = oracle.Range.new(eta, False)
+    qmin = qmax = None
+    for t, x in enumerate(batches):
+        o = oracle.tensor_step(x, r, "hindsight")
+        if t == 0:
+            used = (mins[0], maxs[0]); qmin, qmax = mins[0], maxs[0]
+        else:
+            used = (qmin, qmax)
+        assert abs(float(o["scale"]) - (used[1] - used[0]) / grid) <= 1e-6 * (used[1] - used[0]) / grid
+        qmin, qmax = (1 - eta) * mins[t] + eta * qmin, (1 - eta) * maxs[t] + eta * qmax
+        assert abs(r.qmin - qmin) <= 1e-6 * abs(qmin) and abs(r.qmax - qmax) <= 1e-6 * abs(qmax)
+        if t > 0 and (mins[t] < used[0] or maxs[t] > used[1]):
+            assert o["clip_lo"] + o["clip_hi"] > 0                 # the estimate of the past does not cover this batch
+    # current min-max: always the batch's own range, so nothing clips
+    r = oracle.Range.new(eta, False)
+    for t, x in enumerate(batches):
+        o = oracle.tensor_step(x, r, "current")
+        assert abs(float(o["scale"]) - (maxs[t] - mins[t]) / grid) <= 1e-6 and o["clip_lo"] + o["clip_hi"] == 0
+    assert abs(r.qmin - qmin) <= 1e-6 * abs(qmin)                   # the state still follows eq. (2)-(3)
+    # running min-max: batch t with the average that already includes batch t
+    r = oracle.Range.new(eta, False)
+    qmin, qmax = mins[0], maxs[0]
+    for t, x in enumerate(batches):
+        o = oracle.tensor_step(x, r, "running")
+        if t > 0:
+            qmin, qmax = (1 - eta) * mins[t] + eta * qmin, (1 - eta) * maxs[t] + eta * qmax
+        assert abs(float(o["scale"]) - (qmax - qmin) / grid) <= 1e-6 * (qmax - qmin) / grid
+    # symmetric gradients: scale from the larger magnitude
+    r = oracle.Range.new(eta, True)
+    o = oracle.tensor_step(np.array([-3.0, 1.0, 0.5], np.float32), r, "hindsight")
+    assert o["scale"] == f32(3.0) / f32(127) and o["zero_point"] == 0 and o["codes"].tolist() == [-127, 42, 21]
 
 
 def test_workload_shapes_match_the_configurations():

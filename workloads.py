@@ -128,6 +128,23 @@ def laplace_gradient(g, shape, b, outlier_frac=0.0, outlier_gain=20.0):
     return to_symmetric_codes(x, max(float(np.abs(x).max()), 1e-30) / 127.0)
 
 
+def real_activation(g, n, gain=1.0, shift=0.0):
+    """FP32 tensor as a normalisation layer followed by ReLU hands it on: gain * max(N(0,1) + shift, 0)."""
+    x = g.standard_normal(n, dtype=np.float32)
+    x += np.float32(shift)
+    np.maximum(x, 0, out=x)
+    x *= np.float32(gain)
+    return x
+
+
+def real_gradient(g, n, b, outlier_frac=0.01, outlier_gain=20.0):
+    """FP32 activation gradient: Laplace(0, b) with a fraction of outliers."""
+    x = g.laplace(0.0, b, size=n).astype(np.float32)
+    mask = g.random(n, dtype=np.float32) < outlier_frac
+    x[mask] *= np.float32(outlier_gain)
+    return x
+
+
 # ---------------------------------------------------------------------------
 # the five configurations
 # ---------------------------------------------------------------------------
