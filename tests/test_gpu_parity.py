@@ -458,6 +458,94 @@ def test_real_tensor_dynamic_quantizers(H, hq, mode):
             H.assert_range_close(H.read_range(r), ref)
 
 
+def test_two_layer_chain_runs_on_the_device_without_the_host(H, hq):
+    """FP32 image -> Q_X -> conv -> conv -> (FP32 loss gradient -> Q_G) -> dgrad -> dgrad, both
+    weight gradients, FP32 master weights through Q_W: every quantizer parameter is handed from
+    call to call as a device pointer, all six range states are updated by one launch, and nothing
+    is read back before the iteration's end.  Three iterations (the first dynamic), every tensor
+    compared with the oracle doing the same chain."""
+    L1, L2 = wl.conv("chain1", 3, 18, 16, 64, 3), wl.conv("chain2", 3, 18, 64, 64, 3)
+    p1, p2 = H.hq_problem(L1), H.hq_problem(L2)
+    o1, o2 = H.oracle_problem(L1), H.oracle_problem(L2)
+    g = np.random.default_rng(99)
+    Wf = [(g.standard_normal(wl.w_shape(L)) * np.sqrt(2.0 / (9 * L.C))).astype(np.float32) for L in (L1, L2)]
+    # device state: ranges 0..5 = x0, y1, y2, g2 (loss gradient), g1, g0
+    sym = [False, False, False, True, True, True]
+    R, ST = hq.new_ranges(sym), hq.new_stats(6)
+    rp = lambda i: R.data_ptr() + i * hq.RANGE.itemsize
+    sp = lambda i: ST.data_ptr() + i * hq.STATS.itemsize
+    refs = [oracle.Range.new(0.9, f) for f in sym]
+    i8 = lambda shape: torch.empty(shape, dtype=torch.int8, device="cuda")
+    qps = [hq.new_qparams(0.0, 0) for _ in range(6)]
+    wq = [hq.new_qparams(0.0, 0) for _ in range(2)]
+    Wq = [i8(w.shape) for w in Wf]
+    Wd = [i8(w.size) for w in Wf]
+    wsum = [torch.empty(L.Cout, dtype=torch.int32, device="cuda") for L in (L1, L2)]
+    wdsum = [torch.empty(L.C, dtype=torch.int32, device="cuda") for L in (L1, L2)]
+    ws_n = max(hq.hq_workspace_bytes(e, p) for e in (hq.HQ_ENTRY_WGRAD, hq.HQ_ENTRY_DYNAMIC_FWD, hq.HQ_ENTRY_DYNAMIC_DGRAD)
+               for p in (p1, p2))
+    ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
+    x0q, y1, y2 = i8(wl.in_shape(L1)), i8(wl.out_shape(L1)), i8(wl.out_shape(L2))
+    g2, g1, g0 = i8(wl.out_shape(L2)), i8(wl.in_shape(L2)), i8(wl.in_shape(L1))
+    dW = [torch.empty(w.shape, dtype=torch.float32, device="cuda") for w in Wf]
+    dWa = [torch.empty(w.shape, dtype=torch.int32, device="cuda") for w in Wf]
+    for t in range(3):
+        x0 = (g.standard_normal(wl.in_shape(L1)) * 1.1 ** t).astype(np.float32)
+        gl = wl.real_gradient(g, wl.nelem(wl.out_shape(L2)), 1e-3 * 0.7 ** t).reshape(wl.out_shape(L2))
+        for w in Wf:
+            w *= np.float32(0.97)                                   # the master weights move
+        # ---- device: one stream, no synchronisation inside the iteration
+        x0d, gld = torch.from_numpy(x0).cuda(), torch.from_numpy(gl).cuda()
+        for k, p in enumerate((p1, p2)):
+            hq.hq_weight_quantize(torch.from_numpy(Wf[k]).cuda(), Wf[k].size, Wq[k], wq[k])
+            hq.hq_weight_prepare(p, Wq[k], Wd[k], wsum[k], wdsum[k])
+        if t == 0:
+            dyn = hq.HQ_DYN_CURRENT
+            hq.hq_tensor_quantize_dynamic(dyn, x0d, x0.size, rp(0), x0q, qps[0], sp(0))
+            hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_FWD, dyn, p1, x0q, qps[0], Wq[0], wq[0], wsum[0], rp(1), y1, qps[1], sp(1), ws, ws_n)
+            hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_FWD, dyn, p2, y1, qps[1], Wq[1], wq[1], wsum[1], rp(2), y2, qps[2], sp(2), ws, ws_n)
+            hq.hq_tensor_quantize_dynamic(dyn, gld, gl.size, rp(3), g2, qps[3], sp(3))
+            hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_DGRAD, dyn, p2, g2, qps[3], Wd[1], wq[1], wdsum[1], rp(4), g1, qps[4], sp(4), ws, ws_n)
+            hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_DGRAD, dyn, p1, g1, qps[4], Wd[0], wq[0], wdsum[0], rp(5), g0, qps[5], sp(5), ws, ws_n)
+        else:
+            hq.hq_tensor_quantize(x0d, x0.size, rp(0), x0q, qps[0], sp(0))
+            hq.hq_gemm_fwd(p1, x0q, qps[0], Wq[0], wq[0], wsum[0], rp(1), y1, qps[1], sp(1))
+            hq.hq_gemm_fwd(p2, y1, qps[1], Wq[1], wq[1], wsum[1], rp(2), y2, qps[2], sp(2))
+            hq.hq_tensor_quantize(gld, gl.size, rp(3), g2, qps[3], sp(3))
+            hq.hq_gemm_dgrad(p2, g2, qps[3], Wd[1], wq[1], wdsum[1], rp(4), g1, qps[4], sp(4))
+            hq.hq_gemm_dgrad(p1, g1, qps[4], Wd[0], wq[0], wdsum[0], rp(5), g0, qps[5], sp(5))
+        hq.hq_gemm_wgrad(p2, y1, qps[1], g2, qps[3], dW[1], dWa[1], ws, ws_n)
+        hq.hq_gemm_wgrad(p1, x0q, qps[0], g1, qps[4], dW[0], dWa[0], ws, ws_n)
+        hq.hq_range_update_batch(R, ST, 6)
+        torch.cuda.synchronize()
+        # ---- oracle: the same chain
+        wc = [oracle.quantize_weights(w) for w in Wf]
+        ox0 = oracle.tensor_step(x0, refs[0])
+        oy1 = oracle.in_hindsight_step(oracle.fwd(o1, ox0["codes"], ox0["zero_point"], wc[0][0]),
+                                       oracle.acc_scale(ox0["scale"], wc[0][1]), refs[1])
+        oy2 = oracle.in_hindsight_step(oracle.fwd(o2, oy1["codes"], oy1["zero_point"], wc[1][0]),
+                                       oracle.acc_scale(oy1["scale"], wc[1][1]), refs[2])
+        og2 = oracle.tensor_step(gl, refs[3])
+        og1 = oracle.in_hindsight_step(oracle.dgrad(o2, og2["codes"], og2["zero_point"], wc[1][0]),
+                                       oracle.acc_scale(og2["scale"], wc[1][1]), refs[4])
+        og0 = oracle.in_hindsight_step(oracle.dgrad(o1, og1["codes"], og1["zero_point"], wc[0][0]),
+                                       oracle.acc_scale(og1["scale"], wc[0][1]), refs[5])
+        odw2 = oracle.wgrad(o2, oy1["codes"], oy1["zero_point"], og2["codes"], og2["zero_point"])
+        odw1 = oracle.wgrad(o1, ox0["codes"], ox0["zero_point"], og1["codes"], og1["zero_point"])
+        for name, dev_t, want in (("x0", x0q, ox0), ("y1", y1, oy1), ("y2", y2, oy2), ("g2", g2, og2), ("g1", g1, og1), ("g0", g0, og0)):
+            got = dev_t.cpu().numpy()
+            assert np.array_equal(got, want["codes"].reshape(got.shape)), (t, name, int((got != want["codes"].reshape(got.shape)).sum()))
+        for k, want in enumerate((ox0, oy1, oy2, og2, og1, og0)):
+            q = H.read_qparams(qps[k])
+            assert np.float32(q["scale"]) == want["scale"] and int(q["zero_point"]) == want["zero_point"], (t, k)
+        assert np.array_equal(dWa[1].cpu().numpy(), odw2) and np.array_equal(dWa[0].cpu().numpy(), odw1)
+        assert np.array_equal(dW[1].cpu().numpy(), oracle.wgrad_scale(odw2, oy1["scale"], og2["scale"]))
+        assert np.array_equal(dW[0].cpu().numpy(), oracle.wgrad_scale(odw1, ox0["scale"], og1["scale"]))
+        rr = hq.from_device(R, hq.RANGE)
+        for k in range(6):
+            H.assert_range_close(rr[k], refs[k])
+
+
 NARROW = [wl.conv("nb_band", 2, 20, 64, 64, 3), wl.conv("nb_gemm", 2, 9, 24, 40, 3),
           wl.conv("nb_bandw", 1, 12, 128, 128, 3), wl.conv("nb_first", 2, 23, 4, 48, 7, stride=2),
           wl.depthwise("nb_dw", 2, 13, 48), wl.linear("nb_lin", 300, 72, 80)]
