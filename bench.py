@@ -173,12 +173,15 @@ def stack_step(hq, torch, wl, specs, label, reps=3):
     fused = lambda: sweep(lambda ly: ly.fwd(), lambda ly: ly.dgrad())
     dynamic = lambda: sweep(lambda ly: ly.dyn_fwd(), lambda ly: ly.dyn_dgrad())
 
+    fused_sr = lambda: sweep(lambda ly: ly.fwd(), lambda ly: ly.dgrad_sr())       # the paper's gradient rounding (Sec. 5)
     f_ms, d_ms = time_calls(torch, fused, reps, 1), time_calls(torch, dynamic, reps, 1)
+    sr_ms = time_calls(torch, fused_sr, reps, 1)
     ops = sum(2 * wl.macs(L) * (3 if i > 0 else 2) for i, L in enumerate(specs))
     fb = sum(wl.fused_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
     db = sum(wl.dynamic_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
     return {"workload": "%s: %d fwd + %d dgrad + %d wgrad" % (label, n, n - 1, n), "ops": ops,
             "fused_ms_per_step": f_ms, "dynamic_ms_per_step": d_ms, "fused_tops": ops / (f_ms * 1e-3) / 1e12,
+            "fused_ms_per_step_stochastic_dgrad": sr_ms,
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb}}
 
 
@@ -380,7 +383,7 @@ def main():
             "dgrad_fused_ms": time_calls(torch, lay.dgrad, reps), "dgrad_dynamic_ms": time_calls(torch, lay.dyn_dgrad, reps),
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb},
             "measured_hbm_bytes_per_step": stored_traffic("step")}
-        # the same input-gradient GEMM with stochastic rounding in the epilogue (general kernel)
+        # the same input-gradient GEMM with stochastic rounding in the epilogue
         out["stochastic_rounding"] = {"dgrad_sr_ms": time_calls(torch, lay.dgrad_sr, reps),
                                       "dgrad_nearest_even_ms": out["fused_vs_dynamic"]["dgrad_fused_ms"]}
         lay.upd_y(); lay.upd_g()

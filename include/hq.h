@@ -152,7 +152,8 @@ int hq_gemm_dgrad(const hq_problem *p /* host */,
  * (linear index of the element in dX, seed).  The result therefore depends on the seed and the
  * tensor only, not on the kernel's tiling; callers derive `seed` (host value) from their base
  * seed, the tensor and the iteration.  Clamping, clip counts, statistics and all other arguments
- * as hq_gemm_dgrad.  Runs in the general GEMM kernel and, for HQ_DEPTHWISE, the general stencil.  */
+ * as hq_gemm_dgrad.  Same kernel selection as hq_gemm_dgrad, except that HQ_DEPTHWISE layers
+ * always take the general stencil.                                                           */
 int hq_gemm_dgrad_sr(const hq_problem *p /* host */,
                      const int8_t *dY, const hq_qparams *gq,
                      const int8_t *Wd, const hq_qparams *wq, const int32_t *wdsum,
@@ -243,6 +244,12 @@ int hq_weight_quantize(const float *Wf, size_t n, int8_t *Wq, hq_qparams *wq, vo
  * first batch (Sec. 4.1).  Finite inputs are assumed.                                          */
 int hq_tensor_quantize(const float *X, size_t n, const hq_range *r, int8_t *Q, hq_qparams *q_out,
                        hq_stats *st, void *stream);
+
+/* hq_tensor_quantize with stochastic rounding (the paper's gradient quantizer, Sec. 5.1 / 5.2):
+ * x * m rounds up with probability equal to its fractional part, the draw as in hq_gemm_dgrad_sr
+ * with the element's index in X as the counter.  Everything else as hq_tensor_quantize.       */
+int hq_tensor_quantize_sr(const float *X, size_t n, const hq_range *r, uint64_t seed, int8_t *Q,
+                          hq_qparams *q_out, hq_stats *st, void *stream);
 
 /* The dynamic counterpart (eq. (1)): a first pass reads X for its minimum and maximum, a
  * one-wavefront kernel derives the quantizer, a second pass reads X again and writes the codes

@@ -94,6 +94,8 @@ def lib():
         L.hqo_wgrad_scale.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, f32p]
         L.hqo_quantize_weights.argtypes = [f32p, C.c_int64, i8p, f32p]
         L.hqo_range_update_real.argtypes = [C.POINTER(Range), C.c_float, C.c_float]
+        L.hqo_quantize_tensor_sr.argtypes = [f32p, C.c_int64, C.c_float, C.c_int, C.c_int, C.c_int, C.c_uint64, i8p,
+                                             C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), f32p, f32p]
         L.hqo_quantize_tensor.argtypes = [f32p, C.c_int64, C.c_float, C.c_int, C.c_int, C.c_int, i8p,
                                           C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), f32p, f32p]
         for f in ("hqo_fwd", "hqo_fwd_rows", "hqo_dgrad", "hqo_dgrad_rows", "hqo_wgrad"):
@@ -217,25 +219,30 @@ def range_update_real(r, gmin, gmax):
     return r
 
 
-def quantize_tensor(x, scale, zero_point, qlo, qhi):
-    """Static quantization of a real-valued tensor with a given quantizer (Sec. 3.2).
-    Returns dict(codes, clip_lo, clip_hi, min, max, count)."""
+def quantize_tensor(x, scale, zero_point, qlo, qhi, seed=None):
+    """Static quantization of a real-valued tensor with a given quantizer (Sec. 3.2); with a
+    seed, stochastic rounding.  Returns dict(codes, clip_lo, clip_hi, min, max, count)."""
     x = np.ascontiguousarray(x, np.float32)
     out = np.empty(x.shape, np.int8)
     lo, hi = C.c_uint64(), C.c_uint64()
     mn, mx = C.c_float(), C.c_float()
-    lib().hqo_quantize_tensor(_p(x, C.c_float), x.size, float(scale), int(zero_point), int(qlo), int(qhi),
-                              _p(out, C.c_int8), C.byref(lo), C.byref(hi), C.byref(mn), C.byref(mx))
+    if seed is None:
+        lib().hqo_quantize_tensor(_p(x, C.c_float), x.size, float(scale), int(zero_point), int(qlo), int(qhi),
+                                  _p(out, C.c_int8), C.byref(lo), C.byref(hi), C.byref(mn), C.byref(mx))
+    else:
+        lib().hqo_quantize_tensor_sr(_p(x, C.c_float), x.size, float(scale), int(zero_point), int(qlo), int(qhi),
+                                     int(seed), _p(out, C.c_int8), C.byref(lo), C.byref(hi), C.byref(mn), C.byref(mx))
     return dict(codes=out, clip_lo=lo.value, clip_hi=hi.value, min=np.float32(mn.value), max=np.float32(mx.value),
                 count=x.size)
 
 
-def tensor_step(x, r, mode="hindsight"):
+def tensor_step(x, r, mode="hindsight", seed=None):
     """One iteration for a real-valued tensor with range state ``r``.
     "hindsight": Sec. 4.1 -- the first batch is quantized with its own min-max, which becomes q^0;
     later batches with the pre-computed q^t; the tensor's min-max then moves the range (eq. (2)-(3)).
     "current": eq. (1), every batch with its own min-max (r only takes q^0 and the updates).
-    "running": the range is first moved by eq. (2)-(3) with this tensor, then used (Sec. 4.1)."""
+    "running": the range is first moved by eq. (2)-(3) with this tensor, then used (Sec. 4.1).
+    A seed selects stochastic rounding on the in-hindsight (static) iterations."""
     x = np.ascontiguousarray(x, np.float32)
     gmin, gmax = x.min(), x.max()
     if mode == "running":
@@ -247,9 +254,10 @@ def tensor_step(x, r, mode="hindsight"):
         if not r.initialized:
             range_update_real(r, gmin, gmax)                           # sets q^0
         s, z = qparams(gmin, gmax, r.symmetric, r.qlo, r.qhi)
+        seed = None                                                    # the dynamic passes round to nearest
     else:
         s, z = np.float32(r.scale), r.zero_point
-    out = quantize_tensor(x, s, z, r.qlo, r.qhi)
+    out = quantize_tensor(x, s, z, r.qlo, r.qhi, seed)
     out.update(scale=np.float32(s), zero_point=int(z))
     range_update_real(r, gmin, gmax)                                   # q^{t+1}
     return out

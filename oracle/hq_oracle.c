@@ -379,6 +379,29 @@ void hqo_quantize_tensor(const float *x, int64_t n, float s, int z, int qlo, int
     *clip_lo = nlo; *clip_hi = nhi;
 }
 
+/* The same with stochastic rounding: the decision rule and the draw of hqo_requant_sr
+ * (element i of the tensor draws hqo_sr_bits(i, seed)), on y = x * m.                    */
+void hqo_quantize_tensor_sr(const float *x, int64_t n, float s, int z, int qlo, int qhi, uint64_t seed,
+                            int8_t *out, uint64_t *clip_lo, uint64_t *clip_hi, float *xmin, float *xmax)
+{
+    float m = 1.0f / s;
+    float flo = (float)(qlo - z), fhi = (float)(qhi - z);
+    uint64_t nlo = 0, nhi = 0;
+    for (int64_t i = 0; i < n; i++) {
+        float y = x[i] * m;
+        float f = floorf(y);
+        float frac = y - f;
+        float u = (float)(hqo_sr_bits((uint64_t)i, seed) >> 8) * (1.0f / 16777216.0f);
+        float r = frac > u ? f + 1.0f : f;
+        if (r < flo) { r = flo; nlo++; }
+        if (r > fhi) { r = fhi; nhi++; }
+        out[i] = (int8_t)((int)r + z);
+        if (i == 0 || x[i] < *xmin) *xmin = x[i];
+        if (i == 0 || x[i] > *xmax) *xmax = x[i];
+    }
+    *clip_lo = nlo; *clip_hi = nhi;
+}
+
 /* Q_W (Sec. 3.1): the weight quantizer's range does not depend on the batch; the paper always
  * uses the current min-max of the weight tensor (Sec. 5, experimental setup).  Symmetric 8-bit
  * grid -127..127: s = max|w| / 127 (1 for an all-zero tensor), code = clamp(rne(w / s)), every

@@ -48,7 +48,7 @@ class HqError(RuntimeError):
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_range_update",
            "hq_range_update_batch",
-           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_dynamic",
+           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_sr", "hq_tensor_quantize_dynamic",
            "hq_probe_mfma_rate",
            "hq_error_string")
 
@@ -79,6 +79,7 @@ def lib():
         L.hq_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, vp, vp]
         L.hq_weight_quantize.argtypes = [vp, C.c_size_t, vp, vp, vp]
         L.hq_tensor_quantize.argtypes = [vp, C.c_size_t, vp, vp, vp, vp, vp]
+        L.hq_tensor_quantize_sr.argtypes = [vp, C.c_size_t, vp, C.c_uint64, vp, vp, vp, vp]
         L.hq_tensor_quantize_dynamic.argtypes = [C.c_int32, vp, C.c_size_t, vp, vp, vp, vp, vp]
         for f in EXPORTS[1:-1]:
             getattr(L, f).restype = C.c_int
@@ -165,6 +166,11 @@ def hq_weight_quantize(Wf, n, Wq, wq, stream=None):
 def hq_tensor_quantize(X, n, r, Q, q_out, st, stream=None):
     _check("hq_tensor_quantize", lib().hq_tensor_quantize(_ptr(X), n, _ptr(r), _ptr(Q), _ptr(q_out), _ptr(st),
                                                           _stream(stream)))
+
+
+def hq_tensor_quantize_sr(X, n, r, seed, Q, q_out, st, stream=None):
+    _check("hq_tensor_quantize_sr", lib().hq_tensor_quantize_sr(_ptr(X), n, _ptr(r), int(seed), _ptr(Q), _ptr(q_out),
+                                                                _ptr(st), _stream(stream)))
 
 
 def hq_tensor_quantize_dynamic(mode, X, n, r, Q, q_out, st, stream=None):

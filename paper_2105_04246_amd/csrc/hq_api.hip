@@ -258,9 +258,13 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
         misaligned(out32, 16) || misaligned(st, 8) || misaligned(range, 4) || misaligned(aq, 4) ||
         misaligned(bq, 4) || misaligned(outq, 4)) return HQ_E_BADARG;
     if (sr_seed) {
-        // stochastic rounding lives in the epilogues of the two general kernels only
+        // stochastic rounding: the two 3x3 / 1x1 fast paths, else the two general kernels
         if (p->kind == HQ_DEPTHWISE)
             return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
+        rc = hq_try_launch_bandw(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
+        if (rc != HQ_E_BADSHAPE) return rc;
+        rc = hq_try_launch_band(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
+        if (rc != HQ_E_BADSHAPE) return rc;
         return hq_launch_gemm(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
     }
     if (p->kind == HQ_DEPTHWISE)

@@ -53,6 +53,8 @@ struct BandArgs {
     int rows_per_band, bands_per_image;
     unsigned magic_Wo;             // ceil(2^32 / Wo)
     unsigned long long count;      // outputs of the whole tensor
+    HqSr sr;                       // seed of stochastic rounding (epilogue mode 2)
+    int sr_on;
 };
 
 constexpr int BM = 256;            // output pixels per tile: 4 wavefronts x 2 MFMA row blocks
@@ -70,9 +72,12 @@ template <int C> __device__ inline int wswz(int i)
 // workgroups with their own copy of the weights): a workgroup runs its phases one after the other
 // and the two workgroups of a compute unit overlap freely, without a common barrier and without the
 // idle half steps at both ends.
-template <int C, int KSZ, int NT, int PR, int PJ, int NG, bool FUSED>
+// MODE: 0 = 32-bit outputs (first pass of the dynamic baseline), 1 = fused requantization with
+// round-half-even, 2 = fused with stochastic rounding (input gradients).
+template <int C, int KSZ, int NT, int PR, int PJ, int NG, int MODE>
 __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(const BandArgs a)
 {
+    constexpr bool FUSED = MODE != 0, SR = MODE == 2;
     constexpr int BAND_THREADS = 256 * NG;
     constexpr int NCH = C / 16, KS = C / 32, PP = C + 16, BN = 32 * NT, TAPS = KSZ * KSZ;
     constexpr int WROW = TAPS * C;                        // bytes per weight row in LDS
@@ -345,7 +350,8 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
                             for (int r = 0; r < 16; r++) c[r] = acc[i][j][r];
                             if (FUSED) {
                                 int w[4];
-                                hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
+                                if (SR) hq_requant_group_sr<16, FULL>(c, ep, a.sr, m * a.N + nb, mn, mx, nlo, nhi, w);
+                                else hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
                                 const v4i packed = {w[0], w[1], w[2], w[3]};
                                 *reinterpret_cast<v4i *>(a.out8 + m * a.N + nb) = packed;
                             } else {
@@ -376,29 +382,34 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
 
 constexpr size_t BAND_LDS_MAX = 160 * 1024;
 
-template <int C, int KSZ, int NT, int PR, int PJ, int NG>
-int launch_band(const BandArgs &a, int blocks, size_t lds, hipStream_t s)
+template <int C, int KSZ, int NT, int PR, int PJ, int NG, int MODE>
+int launch_band_mode(const BandArgs &a, int blocks, size_t lds, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, NG, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, NG, false>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_band_kernel<C, KSZ, NT, PR, PJ, NG, MODE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX) != hipSuccess)
             return HQ_E_HIP;
         configured = true;
     }
-    if (a.out32 == nullptr)
-        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, NG, true>), dim3(blocks), dim3(256 * NG), lds, s, a);
-    else
-        hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, NG, false>), dim3(blocks), dim3(256 * NG), lds, s, a);
+    hipLaunchKernelGGL((hq_band_kernel<C, KSZ, NT, PR, PJ, NG, MODE>), dim3(blocks), dim3(256 * NG), lds, s, a);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+}
+
+template <int C, int KSZ, int NT, int PR, int PJ, int NG>
+int launch_band(const BandArgs &a, int mode, int blocks, size_t lds, hipStream_t s)
+{
+    if (mode == 0) return launch_band_mode<C, KSZ, NT, PR, PJ, NG, 0>(a, blocks, lds, s);
+    if (mode == 1) return launch_band_mode<C, KSZ, NT, PR, PJ, NG, 1>(a, blocks, lds, s);
+    return launch_band_mode<C, KSZ, NT, PR, PJ, NG, 2>(a, blocks, lds, s);
 }
 
 template <int C, int KSZ, int NT, int PR, int PJ>
 int launch_band_ng(const BandArgs &a, int ng, int blocks, size_t lds, hipStream_t s)
 {
-    return ng == 1 ? launch_band<C, KSZ, NT, PR, PJ, 1>(a, blocks, lds, s) : launch_band<C, KSZ, NT, PR, PJ, 2>(a, blocks, lds, s);
+    const int mode = a.out32 ? 0 : a.sr_on ? 2 : 1;
+    return ng == 1 ? launch_band<C, KSZ, NT, PR, PJ, 1>(a, mode, blocks, lds, s)
+                   : launch_band<C, KSZ, NT, PR, PJ, 2>(a, mode, blocks, lds, s);
 }
 
 } // namespace
@@ -407,14 +418,17 @@ int launch_band_ng(const BandArgs &a, int ng, int blocks, size_t lds, hipStream_
 // caller then uses the general gather kernel), HQ_E_HIP on a launch error.
 int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                        const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
-                       int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
+                       int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream, const uint64_t *sr_seed)
 {
     if (p->kind != HQ_CONV2D || p->R != p->S) return HQ_E_BADSHAPE;
     if (dgrad && p->stride != 1) return HQ_E_BADSHAPE;
+    if (sr_seed && out32) return HQ_E_BADARG;
     const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
     BandArgs a;
     a.A = A; a.Bw = Bw; a.bsum = bsum; a.aq = aq; a.bq = bq; a.range = range;
     a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
+    a.sr_on = sr_seed != nullptr;
+    a.sr = sr_seed ? HqSr{(unsigned)*sr_seed, (unsigned)(*sr_seed >> 32)} : HqSr{0, 0};
     int C;
     if (!dgrad) {
         C = p->C; a.N = p->Cout; a.Hs = p->H; a.Ws = p->W; a.Ho = OH; a.Wo = OW;

@@ -44,14 +44,18 @@ struct BandwArgs {
     int patch_px;                  // nimg * PH * PW
     unsigned magic_img, magic_PW;  // ceil(2^32 / (PH * PW)), ceil(2^32 / PW)
     unsigned long long count;
+    HqSr sr;                       // seed of stochastic rounding (epilogue mode 2)
 };
 
 __device__ inline int bw_sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 __device__ inline int bw_swz(int row) { return (row >> 2) & 3; }
 
-template <bool FUSED>
+// MODE: 0 = 32-bit outputs, 1 = fused requantization with round-half-even, 2 = fused with
+// stochastic rounding (input gradients).
+template <int MODE>
 __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs a)
 {
+    constexpr bool FUSED = MODE != 0, SR = MODE == 2;
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     const int patch_bytes = (a.patch_px * BW_CK + 1023) & ~1023;       // whole wavefront loads
     int8_t *Wl = smem;                                     // [2 buffers][2 steps][128][64]
@@ -253,7 +257,8 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
                     const size_t o = m * a.N + nb;
                     if (FUSED) {
                         int w[4];
-                        hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
+                        if (SR) hq_requant_group_sr<16, FULL>(c, ep, a.sr, o, mn, mx, nlo, nhi, w);
+                        else hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
                         const v4i v = {w[0], w[1], w[2], w[3]};
                         *reinterpret_cast<v4i *>(a.out8 + o) = v;
                     } else {
@@ -284,8 +289,9 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
 // input gradient of such a layer with the roles of C and Cout swapped.  HQ_E_BADSHAPE: not covered.
 int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                         const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
-                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
+                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream, const uint64_t *sr_seed)
 {
+    if (sr_seed && out32) return HQ_E_BADARG;
     if (p->kind != HQ_CONV2D || p->R != 3 || p->S != 3 || p->stride != 1 || p->pad != 1) return HQ_E_BADSHAPE;
     const int C = dgrad ? p->Cout : p->C, N = dgrad ? p->C : p->Cout;
     if (C % 64 != 0 || C < 128 || N % 16 != 0 || N < 128) return HQ_E_BADSHAPE;
@@ -311,21 +317,25 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
     a.magic_img = hq_magic32((unsigned)(a.PH * a.PW));
     a.magic_PW = hq_magic32((unsigned)a.PW);
     a.count = (unsigned long long)p->B * p->H * p->W * N;
+    a.sr = sr_seed ? HqSr{(unsigned)*sr_seed, (unsigned)(*sr_seed >> 32)} : HqSr{0, 0};
     const size_t patch_bytes = ((size_t)a.patch_px * BW_CK + 1023) & ~(size_t)1023;
     const size_t lds = 4 * BW_BN * BW_CK + 2 * patch_bytes + 4 * BW_BN + 64;
     if (lds > 158 * 1024) return HQ_E_BADSHAPE;            // (two workgroups per compute unit up to 78 KiB)
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<true>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<false>),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(hq_bandw_kernel<2>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return HQ_E_HIP;
         configured = true;
     }
     long items = (long)a.ntiles * a.nchunks;
     const int blocks = (int)(items < 512 ? items : 512);
-    if (out32 == nullptr) hipLaunchKernelGGL(hq_bandw_kernel<true>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);
-    else                  hipLaunchKernelGGL(hq_bandw_kernel<false>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);
+    if (out32 != nullptr) hipLaunchKernelGGL(hq_bandw_kernel<0>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);
+    else if (sr_seed)     hipLaunchKernelGGL(hq_bandw_kernel<2>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);
+    else                  hipLaunchKernelGGL(hq_bandw_kernel<1>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }

@@ -14,21 +14,30 @@ constexpr int TQ_GROUP = 16;        // elements per thread and trip: four 16-byt
 
 // QUANT: write codes and count the clipped ones; MINMAX: gather the tensor's minimum and maximum
 // as order-preserving keys.  The in-hindsight pass does both, the dynamic passes one each.
-template <bool QUANT, bool MINMAX>
+// SR: stochastic rounding, the draw keyed on the element's index in the tensor and the seed.
+template <bool QUANT, bool MINMAX, bool SR>
 __global__ __launch_bounds__(HQ_THREADS) void tensor_pass_kernel(const float *__restrict__ x, size_t n,
                                                                  const hq_range *r, const hq_qparams *qp,
                                                                  int8_t *__restrict__ out, hq_qparams *q_out,
-                                                                 hq_stats *st)
+                                                                 hq_stats *st, HqSr sr)
 {
     __shared__ int red[4 * (HQ_THREADS / 64)];
     HqRequant rq = {};
     if (QUANT) rq = hq_make_requant(1.0f, *qp, r->qlo, r->qhi);       // a real value is an accumulator of unit 1
     int mn = INT_MAX, mx = INT_MIN;
     unsigned nlo = 0, nhi = 0;
-    auto one = [&](float v) __attribute__((always_inline)) -> int {
+    auto one = [&](float v, size_t idx) __attribute__((always_inline)) -> int {
         if (MINMAX) { const int k = hq_float_key(v); mn = min(mn, k); mx = max(mx, k); }
         if (!QUANT) return 0;
-        float q = rintf(__fmul_rn(v, rq.mult));
+        float q;
+        if (SR) {
+            const unsigned bits = hq_sr_bits((unsigned)idx, (unsigned)(idx >> 32) * 0x85ebca77u + sr.k1, sr.k0);
+            const float y = __fmul_rn(v, rq.mult), fl = floorf(y);
+            const float u = __fmul_rn((float)(bits >> 8), 1.0f / 16777216.0f);
+            q = __fsub_rn(y, fl) > u ? __fadd_rn(fl, 1.0f) : fl;
+        } else {
+            q = rintf(__fmul_rn(v, rq.mult));
+        }
         nlo += (q < rq.flo) ? 1u : 0u;
         nhi += (q > rq.fhi) ? 1u : 0u;
         q = fminf(fmaxf(q, rq.flo), rq.fhi);
@@ -43,14 +52,15 @@ __global__ __launch_bounds__(HQ_THREADS) void tensor_pass_kernel(const float *__
         v4i packed;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
-            const int c0 = one(v[k][0]), c1 = one(v[k][1]), c2 = one(v[k][2]), c3 = one(v[k][3]);
+            const size_t i0 = g * TQ_GROUP + 4 * k;
+            const int c0 = one(v[k][0], i0), c1 = one(v[k][1], i0 + 1), c2 = one(v[k][2], i0 + 2), c3 = one(v[k][3], i0 + 3);
             packed[k] = (int)hq_pack4(c0, c1, c2, c3);
         }
         if (QUANT) reinterpret_cast<v4i *>(out)[g] = packed;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         for (size_t i = groups * TQ_GROUP; i < n; i++) {               // fewer than 16 elements
-            const int c = one(x[i]);
+            const int c = one(x[i], i);
             if (QUANT) out[i] = (int8_t)c;
         }
         if (MINMAX) {
@@ -100,8 +110,19 @@ int hq_tensor_quantize(const float *X, size_t n, const hq_range *r, int8_t *Q, h
 {
     if (!r || !q_out || !st || (n && (!X || !Q))) return HQ_E_BADARG;
     if (misaligned(X, 16) || misaligned(Q, 16) || misaligned(st, 128)) return HQ_E_BADARG;
-    hipLaunchKernelGGL((tensor_pass_kernel<true, true>), dim3(pass_blocks(n)), dim3(HQ_THREADS), 0,
-                       reinterpret_cast<hipStream_t>(stream), X, n, r, &r->qp, Q, q_out, st);
+    hipLaunchKernelGGL((tensor_pass_kernel<true, true, false>), dim3(pass_blocks(n)), dim3(HQ_THREADS), 0,
+                       reinterpret_cast<hipStream_t>(stream), X, n, r, &r->qp, Q, q_out, st, HqSr{0, 0});
+    return launch_status();
+}
+
+int hq_tensor_quantize_sr(const float *X, size_t n, const hq_range *r, uint64_t seed, int8_t *Q,
+                          hq_qparams *q_out, hq_stats *st, void *stream)
+{
+    if (!r || !q_out || !st || (n && (!X || !Q))) return HQ_E_BADARG;
+    if (misaligned(X, 16) || misaligned(Q, 16) || misaligned(st, 128)) return HQ_E_BADARG;
+    hipLaunchKernelGGL((tensor_pass_kernel<true, true, true>), dim3(pass_blocks(n)), dim3(HQ_THREADS), 0,
+                       reinterpret_cast<hipStream_t>(stream), X, n, r, &r->qp, Q, q_out, st,
+                       HqSr{(unsigned)seed, (unsigned)(seed >> 32)});
     return launch_status();
 }
 
@@ -113,11 +134,11 @@ int hq_tensor_quantize_dynamic(int32_t mode, const float *X, size_t n, hq_range 
     if (misaligned(X, 16) || misaligned(Q, 16) || misaligned(st, 128)) return HQ_E_BADARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const unsigned blocks = pass_blocks(n);
-    hipLaunchKernelGGL((tensor_pass_kernel<false, true>), dim3(blocks), dim3(HQ_THREADS), 0, s, X, n, r,
-                       (const hq_qparams *)nullptr, (int8_t *)nullptr, (hq_qparams *)nullptr, st);
+    hipLaunchKernelGGL((tensor_pass_kernel<false, true, false>), dim3(blocks), dim3(HQ_THREADS), 0, s, X, n, r,
+                       (const hq_qparams *)nullptr, (int8_t *)nullptr, (hq_qparams *)nullptr, st, HqSr{0, 0});
     hipLaunchKernelGGL(tensor_mid_kernel, dim3(1), dim3(64), 0, s, (int)mode, r, st, q_out);
-    hipLaunchKernelGGL((tensor_pass_kernel<true, false>), dim3(blocks), dim3(HQ_THREADS), 0, s, X, n, r,
-                       (const hq_qparams *)q_out, Q, q_out, st);
+    hipLaunchKernelGGL((tensor_pass_kernel<true, false, false>), dim3(blocks), dim3(HQ_THREADS), 0, s, X, n, r,
+                       (const hq_qparams *)q_out, Q, q_out, st, HqSr{0, 0});
     return launch_status();
 }
 

@@ -35,6 +35,7 @@ def test_c2_full_size_three_iterations(H, hq):
     dYd = H.DevTensor(dY)
     for _ in range(2):
         gtrack.step(L, "dgrad", dY, W, dYd, Wdev)
+    gtrack.step(L, "dgrad", dY, W, dYd, Wdev, seed=0x243f6a8885a308d3)        # stochastic rounding, whole tensor
     dW, dWa = H.gpu_wgrad(L, H.DevTensor(X), dYd)
     ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
     assert np.array_equal(dWa, ref) and np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))

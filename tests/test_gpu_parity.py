@@ -351,8 +351,16 @@ def test_repeat_runs_are_bit_identical(H, hq):
 # ---------------------------------------------------------------------------------------
 # Stochastic rounding of the input gradient (the paper's gradient quantizer, Sec. 5)
 # ---------------------------------------------------------------------------------------
-SR_SHAPES = [wl.conv("sr_c64", 2, 20, 64, 64, 3),                 # 256 x 64 tiles
-             wl.conv("sr_c128", 2, 14, 128, 128, 3),              # 128 x 128 tiles
+SR_SHAPES = [wl.conv("sr_c64", 2, 20, 64, 64, 3),                 # weights-resident kernel, one-row bands
+             wl.conv("sr_band_tiles", 128, 36, 64, 64, 3),        # ... two tiles per band, the second ragged
+             wl.conv("sr_band_n48", 2, 17, 48, 64, 3),            # ... ragged column tile (dX has 48 channels)
+             wl.conv("sr_band_1x1", 2, 20, 192, 32, 1),           # ... 1x1, three column chunks (reduction over 32)
+             wl.conv("sr_band_1x1_c192", 2, 20, 32, 192, 1),      # ... 1x1, reduction over 192
+             wl.conv("sr_n64", 2, 20, 64, 48, 3),                 # general kernel, 256 x 64 tiles
+             wl.conv("sr_c128", 2, 14, 128, 128, 3),              # streamed-weights kernel
+             wl.conv("sr_bandw_rows", 2, 30, 128, 192, 3),        # ... tiles of rows, last one short; dX has 128 channels
+             wl.conv("sr_bandw_imgs", 3, 10, 192, 128, 3),        # ... tiles of whole images, ragged channel chunk
+             wl.conv("sr_c128_s2", 2, 14, 128, 128, 3, stride=2), # general kernel, 128 x 128 tiles
              wl.conv("sr_s2", 2, 12, 32, 48, 3, stride=2),        # strided classes
              wl.conv("sr_c24", 1, 9, 24, 40, 3),                  # 4-byte reduction path, ragged column groups
              wl.conv("sr_n8", 3, 7, 16, 8, 1, pad=0),             # fewer than 16 output columns... of dX: C = 16
@@ -411,9 +419,12 @@ def test_real_tensor_in_hindsight_quantizer(H, hq, n, kind):
             got = H.read_qparams(qp)
             assert float(got["scale"]) == 1.0 and int(got["zero_point"]) == 0
             continue
-        want = oracle.tensor_step(x, ref, "hindsight")
+        seed = (0x9e3779b97f4a7c15 * (t + 1)) % 2 ** 64 if kind == "grad" and t >= 2 else None   # gradients: the last two rounded stochastically
+        want = oracle.tensor_step(x, ref, "hindsight", seed)
         if t == 0:
             hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_CURRENT, xd, n, r, Q, qp, st)
+        elif seed is not None:
+            hq.hq_tensor_quantize_sr(xd, n, r, seed, Q, qp, st)
         else:
             hq.hq_tensor_quantize(xd, n, r, Q, qp, st)
         got_st, got_qp = H.read_stats(st), H.read_qparams(qp)

@@ -556,6 +556,34 @@ def test_real_tensor_quantizer_hand_values_bounds_and_statistics():
         assert np.array_equal(o["codes"], codes) and (o["clip_lo"], o["clip_hi"]) == (nlo, nhi)
 
 
+def test_real_tensor_stochastic_rounding_is_floor_or_ceil_and_unbiased():
+    """Stochastic rounding of a real-valued tensor: every code is floor or ceil of x/s (fp64 brute
+    force), the mean over many elements of one value approaches it, whole numbers never move, the
+    decision of element i is the one its own draw gives, and the seed matters."""
+    s, z = f32(0.25), 5
+    x = np.full(200000, 0.3, np.float32)                 # x/s = 1.2
+    o = oracle.quantize_tensor(x, s, z, -128, 127, seed=3)
+    vals = o["codes"].astype(int) - z
+    assert set(np.unique(vals)) == {1, 2} and abs(vals.mean() - 1.2) < 0.005
+    assert o["min"] == f32(0.3) and o["max"] == f32(0.3) and o["clip_lo"] + o["clip_hi"] == 0
+    for i in (0, 1, 77, 199999):                         # up iff fraction > u_i
+        u = (oracle.sr_bits(i, 3) >> 8) / 2.0 ** 24
+        frac = float(f32(0.3) * (f32(1.0) / s)) - 1.0
+        assert vals[i] == (2 if frac > u else 1)
+    g = np.random.default_rng(6)
+    x = (g.standard_normal(50000) * 2).astype(np.float32)
+    o = oracle.quantize_tensor(x, s, z, -128, 127, seed=9)
+    ideal = x.astype(np.float64) / 0.25
+    d = (o["codes"].astype(int) - z) - ideal
+    assert d.min() > -1 - 1e-5 and d.max() < 1 + 1e-5 and abs(d.mean()) < 0.01
+    assert not np.array_equal(o["codes"], oracle.quantize_tensor(x, s, z, -128, 127, seed=10)["codes"])
+    whole = np.arange(-20, 20).astype(np.float32) * s
+    assert np.array_equal(oracle.quantize_tensor(whole, s, z, -128, 127, seed=1)["codes"], np.arange(-20, 20) + z)
+    # clip counts follow the rounded value: far outside always clips
+    o = oracle.quantize_tensor(np.array([100.0, -100.0, 0.0], np.float32), s, z, -128, 127, seed=1)
+    assert o["codes"].tolist() == [127, -128, 5] and (o["clip_lo"], o["clip_hi"]) == (1, 1)
+
+
 def test_real_tensor_step_follows_the_three_estimators():
     """Sec. 4.1 / eq. (1)-(3) on real-valued tensors: which range quantizes batch t under each
     estimator, checked against the recursion evaluated in fp64 by hand."""
