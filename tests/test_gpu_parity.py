@@ -185,7 +185,8 @@ def test_random_shapes_all_ops(H, hq, L):
             W0, Wdev = W, H.DevWeights(L, W)
         Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
         y_track.step(L, "fwd", X, W0, Xd, Wdev)
-        g_track.step(L, "dgrad", dY, W0, dYd, Wdev)
+        # the fused iteration of every other shape rounds the input gradient stochastically
+        g_track.step(L, "dgrad", dY, W0, dYd, Wdev, seed=0xabcdef12345 + L.B if t == 1 and len(L.name) % 2 else None)
         dW, dWa = H.gpu_wgrad(L, Xd, dYd)
         ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
         assert np.array_equal(dWa, ref)
