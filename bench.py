@@ -338,6 +338,14 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / K
     dom_ms = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+    # what a pair of events with nothing between them reads on the same busy stream (after the timed
+    # region): the part of dom_ms that is the events' own, reported next to it and not subtracted
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    for a, b in pairs:
+        calls[0][1]()
+        a.record(); b.record()
+    torch.cuda.synchronize()
+    pair_ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
 
     ops_gemm = 2 * wl.macs(L)
     step_ops = 3 * ops_gemm
@@ -356,7 +364,7 @@ def main():
     roofline = {"kernel": names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": achieved / PEAK_INT8_TOPS, "peak_measured": peak_measured,
                 "frac_of_measured": achieved / peak_measured, "traffic": stored_traffic(dom),
-                "algorithmic_bytes": wl.fused_bytes(L, dom), "avg_launch_ms": dom_ms,
+                "algorithmic_bytes": wl.fused_bytes(L, dom), "avg_launch_ms": dom_ms, "empty_event_pair_ms": pair_ms,
                 "launches_timed": "every %dth of the %d timed steps" % (EV, K),
                 "hbm_frac_of_8TBs": wl.fused_bytes(L, dom) / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
 
