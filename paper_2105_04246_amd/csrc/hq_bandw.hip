@@ -333,6 +333,9 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
         configured = true;
     }
     long items = (long)a.ntiles * a.nchunks;
+    // Too few tiles for the chip under a reduction long enough to matter (4 x 4 images with 512 channels):
+    // the gather kernel's 64 x 64 tiles spread the same work over four times as many workgroups.
+    if (items < 192 && (unsigned long long)a.count * 9ull * (unsigned)C >= (1ull << 32)) return HQ_E_BADSHAPE;
     const int blocks = (int)(items < 512 ? items : 512);
     if (out32 != nullptr) hipLaunchKernelGGL(hq_bandw_kernel<0>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);
     else if (sr_seed)     hipLaunchKernelGGL(hq_bandw_kernel<2>, dim3(blocks), dim3(HQ_THREADS), lds, stream, a);

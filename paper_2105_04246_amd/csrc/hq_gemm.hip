@@ -543,6 +543,10 @@ int hq_launch_gemm(const hq_problem *p, int dgrad, const int8_t *A, const hq_qpa
         // workgroups on every compute unit, 64-byte stages (half the LDS, four resident workgroups)
         // hide more latency instead
         const long tiles = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+        // not even one 128 x 128 tile per compute unit (small images or batches under a long reduction,
+        // fully connected layers): 64 x 64 tiles, four times as many workgroups
+        if (aligned && !strided && mode != 2 && a.nchunks >= 16 && tiles < 256)
+            return launch2m<64, 64, 2, 2, 128, false, true>(a, mode, stream);
         if (mode != 2 && a.nchunks >= 16 && !(aligned && tiles >= 3 * 256)) return launch2<128, 128, 2, 2, 128>(a, strided, aligned, mode, stream);
         return launch2<128, 128, 2, 2, 64>(a, strided, aligned, mode, stream);
     }

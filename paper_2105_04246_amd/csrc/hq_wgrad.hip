@@ -36,6 +36,7 @@ struct WgradArgs {
     int ctiles;                    // tiles along C inside one tap
     int xt, yt, splits;            // tile columns (taps * ctiles), tile rows, pixel splits
     int g16, x16;                  // rows of G / X are 16-byte aligned (N % 16 == 0 / C % 16 == 0)
+    int direct;                    // splits == 1: every sum has one writer, plain stores into acc (not zeroed)
 };
 
 __device__ inline v4i load16(const int8_t *p, int nbytes, bool aligned16)
@@ -252,7 +253,10 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const int n = n0 + wn * WTN + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (n < a.N && acc[i][j][r] != 0) atomicAdd(a.acc + (size_t)n * krow + (size_t)tap * a.C + c, acc[i][j][r]);
+                if (n >= a.N) continue;
+                int32_t *dst = a.acc + (size_t)n * krow + (size_t)tap * a.C + c;
+                if (a.direct) *dst = acc[i][j][r];
+                else if (acc[i][j][r] != 0) atomicAdd(dst, acc[i][j][r]);
             }
         }
     if (do_gsum) {
@@ -756,10 +760,6 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
         return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
     }
 
-    const size_t ws_words = sums_bytes / 4;
-    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
-                       dim3(256), 0, stream, a.acc, ws_words);
-
     const bool big = a.N > 64 && a.C > 64, packed = a.C < 16;
     const int TN = big ? 128 : 64, TK = packed ? 256 : big ? 128 : 64;
     a.ctiles = (a.C + TK - 1) / TK;
@@ -776,6 +776,12 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     a.m_per_split = stages_per * MB;
     splits = (stages_total + stages_per - 1) / stages_per;
     a.xt = xt; a.yt = yt; a.splits = splits;
+    // one split: the tiles partition [N][K], so the sums are stored, not added, and only the column sums start at zero
+    a.direct = splits == 1 && !packed;
+    int32_t *zero_from = a.direct ? a.gsum : a.acc;
+    const size_t ws_words = (a.direct ? sums_bytes - acc_bytes : sums_bytes) / 4;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
+                       dim3(256), 0, stream, zero_from, ws_words);
     dim3 grid((unsigned)(xt * yt * splits));
     if (packed)   hipLaunchKernelGGL((hq_wgrad_kernel<64, 256, true>), grid, dim3(HQ_THREADS), 0, stream, a);
     else if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128, false>), grid, dim3(HQ_THREADS), 0, stream, a);

@@ -79,6 +79,10 @@ SMALL = [
     wl.conv("band_early_tail", 128, 24, 64, 64, 3),  # bands of 288 pixels: the 32-pixel last tile is taken in the first half step
     wl.LayerShape("c2x1_s3", wl.CONV, 1, 2, 10, 4, 2, 1, 3, 0, 36),   # filter of width 1 and height 2 (division by 1 in the tap arithmetic)
     wl.LayerShape("c1x3_w1", wl.CONV, 2, 9, 1, 16, 1, 1, 1, 0, 32),   # images one pixel wide
+    wl.conv("gemm128_conv", 5, 58, 144, 136, 3),     # general kernel with 128 x 128 tiles (264 of them), ragged in both directions
+    wl.linear("gemm128_lin", 20000, 256, 200),       # ... linear layer, 314 tiles
+    wl.conv("gemm64_small_images", 40, 4, 512, 256, 3),   # 4 x 4 images under a long reduction: 64 x 64 tiles
+    wl.linear("wgrad_one_split", 96, 2048, 2048),    # weight gradient with one writer per sum (256 tiles, no pixel splits)
 ]
 
 
