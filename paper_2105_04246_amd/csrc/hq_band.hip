@@ -439,7 +439,7 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
     }
     const int KSZ = p->R;
     int NT, PJ;
-    if (C == 64 && KSZ == 3) { NT = 2; PJ = 1; }
+    if (C == 64 && KSZ == 3) { NT = 2; PJ = ((a.Wo - 1) * a.stride + KSZ) * 4 > 256 ? 2 : 1; }   // patch rows of up to 64 / 128 pixels
     else if (C == 32 && KSZ == 1) { NT = 2; PJ = 1; }
     else if (C == 192 && KSZ == 1) { NT = 1; PJ = 3; }
     else return HQ_E_BADSHAPE;
@@ -483,6 +483,10 @@ int hq_try_launch_band(const hq_problem *p, int dgrad, const int8_t *A, const hq
     a.magic_Wo = hq_magic32((unsigned)a.Wo);
     a.count = (unsigned long long)p->B * a.Ho * a.Wo * a.N;
     const int blocks = p->B * a.bands_per_image;
+    if (C == 64 && PJ == 2) {
+        if (prmax <= 6) return launch_band_ng<64, 3, 2, 6, 2>(a, ng, blocks, lds, stream);
+        return HQ_E_BADSHAPE;
+    }
     if (C == 64) {
         if (prmax <= 8) return launch_band_ng<64, 3, 2, 8, 1>(a, ng, blocks, lds, stream);
         if (prmax <= 12) return launch_band_ng<64, 3, 2, 12, 1>(a, ng, blocks, lds, stream);

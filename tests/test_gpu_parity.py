@@ -82,6 +82,8 @@ SMALL = [
     wl.conv("gemm128_conv", 5, 58, 144, 136, 3),     # general kernel with 128 x 128 tiles (264 of them), ragged in both directions
     wl.linear("gemm128_lin", 20000, 256, 200),       # ... linear layer, 314 tiles
     wl.conv("gemm64_small_images", 40, 4, 512, 256, 3),   # 4 x 4 images under a long reduction: 64 x 64 tiles
+    wl.conv("band_w64", 2, 64, 64, 64, 3),           # weights-resident kernel, patch rows of more than 64 pixels (two chunks per thread)
+    wl.LayerShape("band_w126", wl.CONV, 1, 9, 126, 64, 3, 3, 1, 1, 48),   # ... the widest rows it takes, ragged tiles and columns
     wl.linear("wgrad_one_split", 96, 2048, 2048),    # weight gradient with one writer per sum (256 tiles, no pixel splits)
 ]
 
