@@ -175,7 +175,21 @@ def random_fast_path_shapes(n, seed):
     return shapes
 
 
-RANDOM = random_shapes(40, 20260) + random_shapes(50, 7) + random_fast_path_shapes(48, 11)
+def random_wide_band_shapes(n, seed):
+    """3x3 layers with 64 input channels on images 58 .. 132 pixels wide: around the two patch-row widths
+    of the weights-resident kernel (64 and 126 output pixels at stride 1) and past them (gather kernel)."""
+    g = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < n:
+        L = wl.LayerShape("wide%d" % len(shapes), wl.CONV, int(g.choice([1, 2, 3])), int(g.integers(3, 14)), int(g.integers(58, 133)),
+                          64, 3, 3, int(g.choice([1, 1, 2])), int(g.integers(0, 3)), 16 * int(g.integers(1, 6)))
+        OH, OW = (L.H + 2 * L.pad - 3) // L.stride + 1, (L.W + 2 * L.pad - 3) // L.stride + 1
+        if OH >= 1 and OW >= 1:
+            shapes.append(L)
+    return shapes
+
+
+RANDOM = random_shapes(40, 20260) + random_shapes(50, 7) + random_fast_path_shapes(48, 11) + random_wide_band_shapes(12, 5)
 
 
 @pytest.mark.parametrize("L", RANDOM, ids=["%s_b%d_%dx%d_c%d_%dx%d_s%d_p%d_n%d" % (l.name, l.B, l.H, l.W, l.C, l.R, l.S, l.stride, l.pad, l.Cout)
