@@ -62,7 +62,7 @@ __global__ __launch_bounds__(64) void dynamic_mid_kernel(int mode, hq_range *r, 
     }
 }
 
-// Dynamic baseline, pass 2: load the 32-bit outputs back (eq. (5), "load acc output"),
+// Dynamic baseline, pass 2: load the 32-bit outputs back (the accumulator-load term of eq. (5)),
 // quantize, store codes.  16 outputs per thread: 64 B in, 16 B out.
 __global__ __launch_bounds__(HQ_THREADS) void dynamic_pass2_kernel(const int32_t *__restrict__ c, size_t n,
                                                                    const hq_stats *st, const hq_range *r,

@@ -28,7 +28,7 @@
 // the epilogue removes the zero point, folds min / max / clip counts into the tensor's
 // statistics (Sec. 4, step 2) and stores codes quantized with the range fixed before the
 // launch (Sec. 4, step 1).  With `out32` set, the kernel is pass 1 of the dynamic baseline:
-// it stores the corrected 32-bit outputs (eq. (5), "save acc output") and gathers min / max.
+// it stores the corrected 32-bit outputs (the accumulator-save term of eq. (5)) and gathers min / max.
 #include "hq_device.h"
 #include <type_traits>
 
