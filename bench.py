@@ -176,12 +176,21 @@ def stack_step(hq, torch, wl, specs, label, reps=3):
     fused_sr = lambda: sweep(lambda ly: ly.fwd(), lambda ly: ly.dgrad_sr())       # the paper's gradient rounding (Sec. 5)
     f_ms, d_ms = time_calls(torch, fused, reps, 1), time_calls(torch, dynamic, reps, 1)
     sr_ms = time_calls(torch, fused_sr, reps, 1)
+    # every layer's three launches on their own (three repetitions each, back to back)
+    per_layer = []
+    for i, (L, ly) in enumerate(zip(specs, layers)):
+        gop = 2 * wl.macs(L) / 1e9
+        row = {"layer": L.name, "gop": gop, "fwd_ms": time_calls(torch, ly.fwd, 3, 1),
+               "dgrad_ms": time_calls(torch, ly.dgrad, 3, 1) if i > 0 else None, "wgrad_ms": time_calls(torch, ly.wgrad, 3, 1)}
+        row["fwd_tops"] = gop / row["fwd_ms"]
+        per_layer.append(row)
+    hq.hq_stats_reset(stats, 2 * n)
     ops = sum(2 * wl.macs(L) * (3 if i > 0 else 2) for i, L in enumerate(specs))
     fb = sum(wl.fused_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
     db = sum(wl.dynamic_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
     return {"workload": "%s: %d fwd + %d dgrad + %d wgrad" % (label, n, n - 1, n), "ops": ops,
             "fused_ms_per_step": f_ms, "dynamic_ms_per_step": d_ms, "fused_tops": ops / (f_ms * 1e-3) / 1e12,
-            "fused_ms_per_step_stochastic_dgrad": sr_ms,
+            "fused_ms_per_step_stochastic_dgrad": sr_ms, "per_layer": per_layer,
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb}}
 
 
