@@ -578,6 +578,77 @@ def test_two_layer_chain_runs_on_the_device_without_the_host(H, hq):
             H.assert_range_close(rr[k], refs[k])
 
 
+@pytest.mark.parametrize("L", [wl.conv("graph_band", 4, 20, 64, 64, 3), wl.conv("graph_gemm", 2, 9, 24, 40, 3),
+                               wl.depthwise("graph_dw", 2, 13, 48)], ids=lambda l: l.name)
+def test_side_stream_and_graph_replay(H, hq, L):
+    """The library only launches kernels on the stream it is handed (no allocation, no memset, no
+    synchronisation), so a layer step can run on a side stream and be captured into a graph.  Three
+    eager steps on the default stream give the expected sequence (the range state moves every step);
+    the same step captured once on a side stream and replayed three times, with other work and
+    synchronisations between the replays, must reproduce it bit for bit."""
+    X, W, dY = rand_layer_inputs(L, 4242)
+    Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
+    p = H.hq_problem(L)
+    R, ST = hq.new_ranges([False, True]), hq.new_stats(2)
+    rs, ss = hq.RANGE.itemsize, hq.STATS.itemsize
+    Y = torch.empty(wl.out_shape(L), dtype=torch.int8, device="cuda")
+    dX = torch.empty(wl.in_shape(L), dtype=torch.int8, device="cuda")
+    dW = torch.empty(wl.w_shape(L), dtype=torch.float32, device="cuda")
+    yq, dxq = hq.new_qparams(0, 0), hq.new_qparams(0, 0)
+    nws = max(hq.hq_workspace_bytes(e, p) for e in (hq.HQ_ENTRY_WGRAD, hq.HQ_ENTRY_DYNAMIC_FWD, hq.HQ_ENTRY_DYNAMIC_DGRAD))
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    # initialise both ranges dynamically, then keep that state as the common starting point
+    hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_FWD, hq.HQ_DYN_CURRENT, p, Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, R[:rs], Y, yq, ST[:ss], ws, nws)
+    hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_DGRAD, hq.HQ_DYN_CURRENT, p, dYd.codes, dYd.qp, Wdev.Wd, Wdev.qp, Wdev.wdsum, R[rs:], dX, dxq,
+                       ST[ss:], ws, nws)
+    hq.hq_range_update_batch(R, ST, 2)
+    torch.cuda.synchronize()
+    R0 = R.clone()
+
+    def step():
+        hq.hq_gemm_fwd(p, Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, R[:rs], Y, yq, ST[:ss])
+        hq.hq_gemm_dgrad(p, dYd.codes, dYd.qp, Wdev.Wd, Wdev.qp, Wdev.wdsum, R[rs:], dX, dxq, ST[ss:])
+        hq.hq_gemm_wgrad(p, Xd.codes, Xd.qp, dYd.codes, dYd.qp, dW, None, ws, nws)
+        hq.hq_range_update_batch(R, ST, 2)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (Y, dX, dW, R, yq, dxq)]
+
+    eager = []
+    for _ in range(3):
+        # the data scale drifts so that consecutive steps differ
+        Xd.qp.copy_(hq.new_qparams(float(X.scale) * (1.3 ** len(eager)), X.zero_point))
+        step()
+        eager.append(snapshot())
+    assert not torch.equal(eager[0][0], eager[2][0])
+    # side stream, eager
+    R.copy_(R0)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        Xd.qp.copy_(hq.new_qparams(float(X.scale), X.zero_point))
+        step()
+    side.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(snapshot(), eager[0]))
+    # captured once, replayed three times
+    R.copy_(R0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    R.copy_(R0)                                           # capturing does not run the step; make sure of the start state anyway
+    hq.hq_stats_reset(ST, 2)
+    for k in range(3):
+        Xd.qp.copy_(hq.new_qparams(float(X.scale) * (1.3 ** k), X.zero_point))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        assert all(torch.equal(a, b) for a, b in zip(got, eager[k])), "replay %d differs from the eager step" % k
+        junk = torch.randn(1 << 16, device="cuda").sum()      # unrelated eager work between replays
+        torch.cuda.synchronize()
+
+
 NARROW = [wl.conv("nb_band", 2, 20, 64, 64, 3), wl.conv("nb_gemm", 2, 9, 24, 40, 3),
           wl.conv("nb_bandw", 1, 12, 128, 128, 3), wl.conv("nb_first", 2, 23, 4, 48, 7, stride=2),
           wl.depthwise("nb_dw", 2, 13, 48), wl.linear("nb_lin", 300, 72, 80)]
