@@ -91,8 +91,11 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
 
     // tile of this workgroup: ids are dealt round-robin to the 8 XCDs; give each XCD a
     // contiguous run of tiles (channel blocks of one pixel block next to each other)
+    // (not in the class form of a strided input gradient: its classes are runs of row tiles with
+    // different numbers of taps, down to none, and a contiguous run per XCD would leave the heavy
+    // classes to one or two XCDs)
     int tile = blockIdx.x;
-    {
+    if (!(STRIDED && ALIGNED)) {
         const int total = a.m_tiles * a.n_tiles, per = total / 8;
         if (per > 0 && tile < per * 8) tile = (tile & 7) * per + (tile >> 3);
     }
@@ -120,6 +123,48 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
         if (ns == 0) ns = 1;                       // no taps at all: nchunks == 0, nothing is decoded
     }
     const int m0 = tile_m * BM;
+
+    if (CLASSED && nchunks == 0) {
+        // A class no filter tap reaches (1x1 filters with stride 2: three of the four classes): every
+        // output of the tile is real zero, its code the zero point.  Stored directly, a row's columns by
+        // neighbouring lanes, instead of going through the tile machinery.
+        const int cols = min(BN, a.N - n0);                 // multiple of 4
+        const bool wide = ((cols | a.N) & 15) == 0;         // 16-byte pieces, else 4-byte ones
+        const int ppr = wide ? cols / 16 : cols / 4;        // pieces per row (at most 32)
+        const int rpp = HQ_THREADS / ppr;                   // rows per pass of the workgroup
+        const int rl = tid / ppr, piece = tid - rl * ppr;
+        const int zcode = a.range->qp.zero_point & 0xff;    // inside the grid by construction
+        const int fillw = zcode * 0x01010101;
+        if (rl < rpp) {
+            // the row's pixel is decoded once and then stepped (rpp rows per pass)
+            int m = m0 + rl;
+            int x = m % Wc, t = m / Wc, y = t % Hc, b = t / Hc;
+            for (int row = rl; row < BM && m < Mrows; row += rpp, m += rpp) {
+                const size_t px = (size_t)(b * a.Ho + ph + a.stride * y) * a.Wo + pw + a.stride * x;
+                const size_t o = px * a.N + n0;
+                if (MODE == 0) {
+                    const v4i z4 = {0, 0, 0, 0};
+                    for (int q = 0; q < (wide ? 4 : 1); q++)
+                        *reinterpret_cast<v4i *>(a.out32 + o + (wide ? 16 * piece + 4 * q : 4 * piece)) = z4;
+                } else if (wide) {
+                    const v4i f4 = {fillw, fillw, fillw, fillw};
+                    *reinterpret_cast<v4i *>(a.out8 + o + 16 * piece) = f4;
+                } else {
+                    *reinterpret_cast<int *>(a.out8 + o + 4 * piece) = fillw;
+                }
+                x += rpp;
+                while (x >= Wc) { x -= Wc; if (++y == Hc) { y = 0; b++; } }
+            }
+        }
+        int *red0 = reinterpret_cast<int *>(smem);
+        hq_block_stats_commit(0, 0, 0, 0, a.st, red0);      // the accumulators of this tile are all 0
+        if (blockIdx.x == 0 && tid == 0) {
+            a.st->acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
+            atomicAdd((unsigned long long *)&a.st->count, (unsigned long long)a.M * (unsigned long long)a.N);
+            if (MODE != 0) *a.outq = a.range->qp;
+        }
+        return;
+    }
 
     const int za = a.aq->zero_point;
     const int fill = (za & 0xff) * 0x01010101;

@@ -84,6 +84,8 @@ SMALL = [
     wl.conv("gemm64_small_images", 40, 4, 512, 256, 3),   # 4 x 4 images under a long reduction: 64 x 64 tiles
     wl.conv("band_w64", 2, 64, 64, 64, 3),           # weights-resident kernel, patch rows of more than 64 pixels (two chunks per thread)
     wl.LayerShape("band_w126", wl.CONV, 1, 9, 126, 64, 3, 3, 1, 1, 48),   # ... the widest rows it takes, ragged tiles and columns
+    wl.conv("c1x1_s2_n24", 2, 11, 24, 32, 1, stride=2, pad=0),           # pixel classes that no tap reaches, filled in 4-byte pieces
+    wl.LayerShape("c2x2_s3", wl.CONV, 2, 14, 17, 32, 2, 2, 3, 0, 48),      # ... five of nine classes, 16-byte pieces, non-square image
     wl.linear("wgrad_one_split", 96, 2048, 2048),    # weight gradient with one writer per sum (256 tiles, no pixel splits)
 ]
 
