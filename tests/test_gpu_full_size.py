@@ -172,3 +172,30 @@ def test_c5_full_batch_sampled(H, hq, which):
         want, _, _ = oracle.requant(c, a_scale, ref.scale, ref.zero_point, ref.qlo, ref.qhi)
         assert np.array_equal(codes.reshape(nrow, -1)[rows], want)
         assert (int(s1["acc_min"]), int(s1["acc_max"]), int(s1["count"])) == (int(s0["acc_min"]), int(s0["acc_max"]), codes.size)
+
+
+def test_real_tensor_quantizer_full_size(H, hq):
+    """The element-wise quantizer on an FP32 tensor the size of config 2's output (25.7 M values), in the
+    launch shape bench.py times: dynamic first batch, in-hindsight second, stochastic third; whole
+    tensor against the oracle."""
+    n = wl.nelem(wl.out_shape(wl.c2_layer()))
+    r, st, ref = hq.new_range(0.9, False), hq.new_stats(1), oracle.Range.new(0.9, False)
+    Q = torch.empty(n, dtype=torch.int8, device="cuda")
+    qp = hq.new_qparams(0.0, 0)
+    for t in range(3):
+        x = wl.real_activation(wl.rng(2, t, 77), n, gain=1.05 ** t, shift=-0.2)
+        xd = torch.from_numpy(x).cuda()
+        seed = 0x6a09e667f3bcc908 if t == 2 else None
+        want = oracle.tensor_step(x, ref, "hindsight", seed)
+        if t == 0:
+            hq.hq_tensor_quantize_dynamic(hq.HQ_DYN_CURRENT, xd, n, r, Q, qp, st)
+        elif seed is None:
+            hq.hq_tensor_quantize(xd, n, r, Q, qp, st)
+        else:
+            hq.hq_tensor_quantize_sr(xd, n, r, seed, Q, qp, st)
+        got_st = H.read_stats(st)
+        hq.hq_range_update(r, st)
+        assert np.array_equal(Q.cpu().numpy(), want["codes"])
+        assert (int(got_st["clip_lo"]), int(got_st["clip_hi"]), int(got_st["count"])) == (want["clip_lo"], want["clip_hi"], n)
+        H.assert_range_close(H.read_range(r), ref)
+    assert want["clip_hi"] > 0
