@@ -205,6 +205,15 @@ int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p /* host */,
                     hq_range *r, int8_t *out, hq_qparams *outq, hq_stats *st,
                     void *ws, size_t ws_bytes, void *stream);
 
+/* hq_gemm_dynamic with stochastic rounding in the second pass (the dynamic estimators with the
+ * paper's gradient rounding, Sec. 5.1 / 5.2): decision rule, generator and element index as in
+ * hq_gemm_dgrad_sr.  All other arguments as hq_gemm_dynamic.                                   */
+int hq_gemm_dynamic_sr(int32_t op, int32_t mode, const hq_problem *p /* host */,
+                       const int8_t *A, const hq_qparams *aq,
+                       const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum,
+                       hq_range *r, uint64_t seed, int8_t *out, hq_qparams *outq, hq_stats *st,
+                       void *ws, size_t ws_bytes, void *stream);
+
 /* Empties n statistics records (min = INT32_MAX, max = INT32_MIN, counters 0). */
 int hq_stats_reset(hq_stats *st, int32_t n, void *stream);
 

@@ -304,13 +304,17 @@ def quantize_static(c, a_scale, r, seed=None):
                 acc_min=mn, acc_max=mx, clip_lo=lo, clip_hi=hi, count=c.size)
 
 
-def quantize_dynamic(c, a_scale, symmetric, qlo, qhi):
-    """Dynamic quantization: the range is the min-max of the tensor itself, eq. (1)."""
+def quantize_dynamic(c, a_scale, symmetric, qlo, qhi, seed=None):
+    """Dynamic quantization: the range is the min-max of the tensor itself, eq. (1); with a seed,
+    stochastic rounding."""
     mn, mx = minmax(c)
     gmin = np.float32(a_scale) * np.float32(mn)
     gmax = np.float32(a_scale) * np.float32(mx)
     s, z = qparams(gmin, gmax, symmetric, qlo, qhi)
-    codes, lo, hi = requant(c, a_scale, s, z, qlo, qhi)
+    if seed is None:
+        codes, lo, hi = requant(c, a_scale, s, z, qlo, qhi)
+    else:
+        codes, lo, hi = requant_stochastic(c, a_scale, s, z, qlo, qhi, seed)
     return dict(codes=codes, scale=s, zero_point=z, acc_min=mn, acc_max=mx,
                 clip_lo=lo, clip_hi=hi, count=c.size)
 

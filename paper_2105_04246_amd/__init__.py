@@ -48,7 +48,7 @@ class HqError(RuntimeError):
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_range_update",
            "hq_range_update_batch",
-           "hq_gemm_dynamic", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_sr", "hq_tensor_quantize_dynamic",
+           "hq_gemm_dynamic", "hq_gemm_dynamic_sr", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_sr", "hq_tensor_quantize_dynamic",
            "hq_probe_mfma_rate",
            "hq_error_string")
 
@@ -73,6 +73,7 @@ def lib():
         L.hq_range_update.argtypes = [vp, vp, vp]
         L.hq_range_update_batch.argtypes = [vp, vp, C.c_int32, vp]
         L.hq_gemm_dynamic.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 10 + [C.c_size_t, vp]
+        L.hq_gemm_dynamic_sr.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 6 + [C.c_uint64] + [vp] * 4 + [C.c_size_t, vp]
         L.hq_stats_reset.argtypes = [vp, C.c_int32, vp]
         L.hq_stats_fold.argtypes = [vp, C.c_int32, vp]
         L.hq_weight_prepare.argtypes = [PP, vp, vp, vp, vp, vp]
@@ -144,6 +145,12 @@ def hq_gemm_dynamic(op, mode, p, A, aq, Bw, bq, bsum, r, out, outq, st, ws, ws_b
     _check("hq_gemm_dynamic", lib().hq_gemm_dynamic(op, mode, C.byref(p), _ptr(A), _ptr(aq), _ptr(Bw), _ptr(bq),
                                                     _ptr(bsum), _ptr(r), _ptr(out), _ptr(outq), _ptr(st),
                                                     _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def hq_gemm_dynamic_sr(op, mode, p, A, aq, Bw, bq, bsum, r, seed, out, outq, st, ws, ws_bytes, stream=None):
+    _check("hq_gemm_dynamic_sr", lib().hq_gemm_dynamic_sr(op, mode, C.byref(p), _ptr(A), _ptr(aq), _ptr(Bw), _ptr(bq),
+                                                          _ptr(bsum), _ptr(r), int(seed), _ptr(out), _ptr(outq), _ptr(st),
+                                                          _ptr(ws), ws_bytes, _stream(stream)))
 
 
 def hq_stats_reset(st, n=1, stream=None):

@@ -64,14 +64,19 @@ __global__ __launch_bounds__(64) void dynamic_mid_kernel(int mode, hq_range *r, 
 
 // Dynamic baseline, pass 2: load the 32-bit outputs back (the accumulator-load term of eq. (5)),
 // quantize, store codes.  16 outputs per thread: 64 B in, 16 B out.
+// SR: stochastic rounding, the draw keyed on the element's index in the output tensor and the seed.
+template <bool SR>
 __global__ __launch_bounds__(HQ_THREADS) void dynamic_pass2_kernel(const int32_t *__restrict__ c, size_t n,
                                                                    const hq_stats *st, const hq_range *r,
                                                                    const hq_qparams *outq, int8_t *__restrict__ out,
-                                                                   hq_stats *st_out)
+                                                                   hq_stats *st_out, HqSr sr)
 {
     __shared__ int red[4 * (HQ_THREADS / 64)];
     const HqRequant rq = hq_make_requant(st->acc_scale, *outq, r->qlo, r->qhi);
     unsigned nlo = 0, nhi = 0;
+    auto one = [&](int v, size_t idx) __attribute__((always_inline)) -> int {
+        return SR ? hq_requant_sr(v, rq, sr, idx, nlo, nhi) : hq_requant(v, rq, nlo, nhi);
+    };
     const size_t groups = n / 16, step = (size_t)gridDim.x * blockDim.x;
     for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += step) {
         const v4i *src = reinterpret_cast<const v4i *>(c) + 4 * g;
@@ -79,14 +84,14 @@ __global__ __launch_bounds__(HQ_THREADS) void dynamic_pass2_kernel(const int32_t
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             v4i v = src[k];
-            packed[k] = (int)hq_pack4(hq_requant(v[0], rq, nlo, nhi), hq_requant(v[1], rq, nlo, nhi),
-                                      hq_requant(v[2], rq, nlo, nhi), hq_requant(v[3], rq, nlo, nhi));
+            const size_t i0 = 16 * g + 4 * k;
+            packed[k] = (int)hq_pack4(one(v[0], i0), one(v[1], i0 + 1), one(v[2], i0 + 2), one(v[3], i0 + 3));
         }
         reinterpret_cast<v4i *>(out)[g] = packed;
     }
     // tail (n % 16 elements), one thread
     if (blockIdx.x == 0 && threadIdx.x == 0)
-        for (size_t i = groups * 16; i < n; i++) out[i] = (int8_t)hq_requant(c[i], rq, nlo, nhi);
+        for (size_t i = groups * 16; i < n; i++) out[i] = (int8_t)one(c[i], i);
     hq_block_stats_commit(INT_MAX, INT_MIN, nlo, nhi, st_out, red);
 }
 
@@ -340,9 +345,9 @@ int hq_stats_fold(hq_stats *st, int32_t n, void *stream)
     return launch_status();
 }
 
-int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p, const int8_t *A, const hq_qparams *aq,
-                    const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum, hq_range *r, int8_t *out,
-                    hq_qparams *outq, hq_stats *st, void *ws, size_t ws_bytes, void *stream)
+static int dynamic_common(int32_t op, int32_t mode, const hq_problem *p, const int8_t *A, const hq_qparams *aq,
+                          const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum, hq_range *r, int8_t *out,
+                          hq_qparams *outq, hq_stats *st, void *ws, size_t ws_bytes, void *stream, const uint64_t *sr_seed)
 {
     if (op != HQ_ENTRY_DYNAMIC_FWD && op != HQ_ENTRY_DYNAMIC_DGRAD) return HQ_E_BADARG;
     if (mode != HQ_DYN_CURRENT && mode != HQ_DYN_RUNNING) return HQ_E_BADARG;
@@ -362,9 +367,27 @@ int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p, const int8_t 
     unsigned blocks = (unsigned)((groups + HQ_THREADS - 1) / HQ_THREADS);
     if (blocks < 1) blocks = 1;
     if (blocks > 256u * 16u) blocks = 256u * 16u;
-    hipLaunchKernelGGL(dynamic_pass2_kernel, dim3(blocks), dim3(HQ_THREADS), 0, as_stream(stream),
-                       c32, n, st, r, outq, out, st);
+    if (sr_seed)
+        hipLaunchKernelGGL(dynamic_pass2_kernel<true>, dim3(blocks), dim3(HQ_THREADS), 0, as_stream(stream),
+                           c32, n, st, r, outq, out, st, HqSr{(unsigned)*sr_seed, (unsigned)(*sr_seed >> 32)});
+    else
+        hipLaunchKernelGGL(dynamic_pass2_kernel<false>, dim3(blocks), dim3(HQ_THREADS), 0, as_stream(stream),
+                           c32, n, st, r, outq, out, st, HqSr{0, 0});
     return launch_status();
+}
+
+int hq_gemm_dynamic(int32_t op, int32_t mode, const hq_problem *p, const int8_t *A, const hq_qparams *aq,
+                    const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum, hq_range *r, int8_t *out,
+                    hq_qparams *outq, hq_stats *st, void *ws, size_t ws_bytes, void *stream)
+{
+    return dynamic_common(op, mode, p, A, aq, Bw, bq, bsum, r, out, outq, st, ws, ws_bytes, stream, nullptr);
+}
+
+int hq_gemm_dynamic_sr(int32_t op, int32_t mode, const hq_problem *p, const int8_t *A, const hq_qparams *aq,
+                       const int8_t *Bw, const hq_qparams *bq, const int32_t *bsum, hq_range *r, uint64_t seed,
+                       int8_t *out, hq_qparams *outq, hq_stats *st, void *ws, size_t ws_bytes, void *stream)
+{
+    return dynamic_common(op, mode, p, A, aq, Bw, bq, bsum, r, out, outq, st, ws, ws_bytes, stream, &seed);
 }
 
 int hq_weight_prepare(const hq_problem *p, const int8_t *W, int8_t *Wd, int32_t *wsum, int32_t *wdsum, void *stream)

@@ -61,7 +61,7 @@ def read_qparams(q):
 
 def gpu_quantized_op(L, op, A, Wdev, r, st, mode="fused", dyn_mode=hq.HQ_DYN_CURRENT, seed=None):
     """op in {'fwd','dgrad'}; mode 'fused' (in-hindsight static; with a seed: stochastic rounding,
-    dgrad only) or 'dynamic'.
+    dgrad only) or 'dynamic' (with a seed: stochastic rounding in its second pass).
     Returns (codes ndarray, qparams record).  Range state / stats stay on the device."""
     p = hq_problem(L)
     shape = wl.out_shape(L) if op == "fwd" else wl.in_shape(L)
@@ -78,7 +78,10 @@ def gpu_quantized_op(L, op, A, Wdev, r, st, mode="fused", dyn_mode=hq.HQ_DYN_CUR
         entry = hq.HQ_ENTRY_DYNAMIC_FWD if op == "fwd" else hq.HQ_ENTRY_DYNAMIC_DGRAD
         nbytes = hq.hq_workspace_bytes(entry, p)
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        hq.hq_gemm_dynamic(entry, dyn_mode, p, A.codes, A.qp, Bw, Wdev.qp, bsum, r, out, outq, st, ws, nbytes)
+        if seed is not None:
+            hq.hq_gemm_dynamic_sr(entry, dyn_mode, p, A.codes, A.qp, Bw, Wdev.qp, bsum, r, seed, out, outq, st, ws, nbytes)
+        else:
+            hq.hq_gemm_dynamic(entry, dyn_mode, p, A.codes, A.qp, Bw, Wdev.qp, bsum, r, out, outq, st, ws, nbytes)
     torch.cuda.synchronize()
     return out.cpu().numpy(), read_qparams(outq)
 

@@ -334,6 +334,52 @@ def test_running_min_max_mode(H, hq):
         H.assert_range_close(H.read_range(r), ref)
 
 
+@pytest.mark.parametrize("L", [wl.conv("dynsr_band", 2, 20, 64, 64, 3), wl.conv("dynsr_gemm", 2, 9, 24, 40, 3),
+                               wl.conv("dynsr_s2", 2, 12, 32, 48, 3, stride=2), wl.depthwise("dynsr_dw", 2, 13, 48),
+                               wl.linear("dynsr_lin", 37, 72, 80)], ids=lambda l: l.name)
+def test_dynamic_estimators_with_stochastic_rounding(H, hq, L):
+    """The two dynamic estimators on the input gradient with stochastic rounding in the second
+    pass: current min-max (eq. (1)) and running min-max (Sec. 4.1), three iterations each, codes,
+    quantizer, clip counts and range state against the oracle with the same seeds."""
+    for mode in ("current", "running"):
+        r, st, ref = hq.new_range(0.9, True), hq.new_stats(), oracle.Range.new(0.9, True)
+        Wdev, W0 = None, None
+        for t in range(3):
+            X, W, dY = rand_layer_inputs(L, 880 + t)
+            dY = wl.QTensor(dY.codes, np.float32(dY.scale * 0.7 ** t), dY.zero_point)      # shrinking gradients
+            if Wdev is None:
+                W0, Wdev = W, H.DevWeights(L, W)
+            seed = 0xd1b54a32d192ed03 * (t + 1) % 2 ** 64
+            codes, q = H.gpu_quantized_op(L, "dgrad", H.DevTensor(dY), Wdev, r, st, "dynamic",
+                                          hq.HQ_DYN_RUNNING if mode == "running" else hq.HQ_DYN_CURRENT, seed=seed)
+            stats = H.read_stats(st)
+            if mode == "current":
+                hq.hq_range_update(r, st)
+            else:
+                hq.hq_stats_reset(st)
+            c = H.oracle_acc(L, "dgrad", dY, W0)
+            a_scale = oracle.acc_scale(dY.scale, W0.scale)
+            mn, mx = oracle.minmax(c)
+            if mode == "running":
+                oracle.range_update(ref, mn, mx, a_scale)
+                want, lo, hi = oracle.requant_stochastic(c, a_scale, ref.scale, ref.zero_point, ref.qlo, ref.qhi, seed)
+                ws, wz = np.float32(ref.scale), ref.zero_point
+            else:
+                if not ref.initialized:
+                    oracle.range_update(ref, mn, mx, a_scale)
+                o = oracle.quantize_dynamic(c, a_scale, True, ref.qlo, ref.qhi, seed)
+                want, lo, hi, ws, wz = o["codes"], o["clip_lo"], o["clip_hi"], o["scale"], o["zero_point"]
+                oracle.range_update(ref, mn, mx, a_scale)
+            assert np.float32(q["scale"]) == ws and int(q["zero_point"]) == wz
+            assert np.array_equal(codes, want), int((codes != want).sum())
+            assert (int(stats["clip_lo"]), int(stats["clip_hi"])) == (lo, hi)
+            H.assert_range_close(H.read_range(r), ref)
+        nearest, _ = H.gpu_quantized_op(L, "dgrad", H.DevTensor(dY), Wdev, r, st, "dynamic", hq.HQ_DYN_CURRENT)
+        hq.hq_stats_reset(st)
+        if mode == "current":
+            assert not np.array_equal(nearest, codes) and np.abs(nearest.astype(int) - codes.astype(int)).max() <= 1
+
+
 def test_statistics_merge_until_consumed(H, hq):
     """Two launches into the same statistics record give the union; hq_range_update with an
     empty record leaves the range alone."""
