@@ -443,6 +443,31 @@ def main():
         torch.cuda.empty_cache()
         out["real_tensor_quantizer"] = tensor_quantizer(hq, torch, wl)
         torch.cuda.empty_cache()
+        # every launch measured above against both ceilings (single launches, back to back): the
+        # larger fraction names the bound; the depthwise stencil is bound by neither (vector ALU)
+        rl = []
+        fd = out["fused_vs_dynamic"]
+        for op in ("fwd", "dgrad"):
+            ms = fd[op + "_fused_ms"]
+            rl.append({"launch": "config 2 " + op, "ms": ms, "mfma_frac": ops_gemm / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+                       "hbm_frac": wl.fused_bytes(L, op) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+            dms = fd[op + "_dynamic_ms"]
+            rl.append({"launch": "config 2 " + op + " (dynamic two-pass)", "ms": dms,
+                       "mfma_frac": ops_gemm / (dms * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+                       "hbm_frac": wl.dynamic_bytes(L, op) / (dms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        rl.append({"launch": "config 2 wgrad", "ms": dom_ms if dom == "wgrad" else per_call["wgrad"],
+                   "mfma_frac": roofline["frac"] if dom == "wgrad" else None,
+                   "hbm_frac": roofline["hbm_frac_of_8TBs"] if dom == "wgrad" else None})
+        for name, row in extra.items():
+            for op, r in row.items():
+                rl.append({"launch": name + " " + op, "ms": r["ms"], "mfma_frac": r["tops"] / PEAK_INT8_TOPS,
+                           "hbm_frac": r["alg_GBs"] / PEAK_HBM_GBS})
+        tq = out["real_tensor_quantizer"]
+        rl.append({"launch": "FP32 tensor quantizer, in hindsight", "ms": tq["in_hindsight_ms"], "mfma_frac": None,
+                   "hbm_frac": tq["in_hindsight_alg_GBs"] / PEAK_HBM_GBS})
+        rl.append({"launch": "FP32 tensor quantizer, dynamic", "ms": tq["dynamic_ms"], "mfma_frac": None,
+                   "hbm_frac": tq["dynamic_alg_GBs"] / PEAK_HBM_GBS})
+        out["rooflines_all_launches"] = rl
 
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
