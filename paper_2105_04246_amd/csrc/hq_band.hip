@@ -18,6 +18,8 @@
 //     fragment, so an input byte crosses L2->LDS once per tile, not once per tap.  The next
 //     patch of a group is requested during its MFMA phase (into registers, a few rows between
 //     taps) and written to LDS at the start of its epilogue phase, when nobody reads that patch.
+//     A loader thread owns PJ 16-byte chunks of a patch row: one for rows of up to 64 pixels at 64
+//     channels, two for rows of up to 126 pixels, three for the 192-channel 1x1 layers.
 //   * A band whose last tile is one wavefront's worth of pixels does not spend half steps on it:
 //     the second group, idle in half step 0, multiplies and requantizes it there from a third
 //     patch buffer.

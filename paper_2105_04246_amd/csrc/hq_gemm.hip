@@ -22,7 +22,10 @@
 // (two buffers, the next stage's global loads in flight during the current stage's MFMAs),
 // rows padded by 16 bytes to keep 16-byte fragment reads free of bank conflicts.  Tiles that
 // share their A rows (same pixels, different channel blocks) get consecutive slots on the
-// same XCD, so the second reader finds the rows in that XCD's L2.
+// same XCD, so the second reader finds the rows in that XCD's L2 (except in the class form, whose
+// tiles differ in work from class to class and are dealt round-robin; a class without taps is
+// filled with the zero-point code and leaves).  Tile shapes: 128x128, 256x64, 256x32, and
+// 64x64 for launches that 128x128 tiles would leave with fewer workgroups than compute units.
 //
 // The accumulators never leave registers on the fused path (Sec. 3.2, static quantization):
 // the epilogue removes the zero point, folds min / max / clip counts into the tensor's
