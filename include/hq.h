@@ -171,6 +171,17 @@ int hq_gemm_wgrad(const hq_problem *p /* host */,
                   const int8_t *dY, const hq_qparams *gq,
                   float *dW, int32_t *dW_acc, void *ws, size_t ws_bytes, void *stream);
 
+/* hq_gemm_wgrad followed by hq_range_update_batch(r, st, n) in one call: the range updates run as
+ * n extra workgroups of the call's last launch, next to its own work, instead of in a launch of
+ * their own.  For the layer step fwd, dgrad, wgrad: the statistics must come from launches earlier
+ * on the stream (the forward and input-gradient GEMMs); the weight gradient itself reads no range.
+ * 1 <= n <= 4096; all other arguments and the result as hq_gemm_wgrad.                          */
+int hq_gemm_wgrad_update(const hq_problem *p /* host */,
+                         const int8_t *X, const hq_qparams *xq,
+                         const int8_t *dY, const hq_qparams *gq,
+                         float *dW, int32_t *dW_acc, void *ws, size_t ws_bytes,
+                         hq_range *r, hq_stats *st, int32_t n, void *stream);
+
 /* In-hindsight min-max update, eq. (2)-(3): folds the statistics of the tensor just
  * produced into the range for the next iteration and re-derives r->qp.  If r is not
  * initialized the statistics become q^0 (Sec. 4.1).  Folds the partial records first and

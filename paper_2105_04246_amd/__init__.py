@@ -46,7 +46,7 @@ class HqError(RuntimeError):
 
 
 _lib = None
-EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_range_update",
+EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_gemm_wgrad_update", "hq_range_update",
            "hq_range_update_batch",
            "hq_gemm_dynamic", "hq_gemm_dynamic_sr", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_sr", "hq_tensor_quantize_dynamic",
            "hq_probe_mfma_rate",
@@ -70,6 +70,7 @@ def lib():
         L.hq_gemm_dgrad.argtypes = [PP] + [vp] * 10
         L.hq_gemm_dgrad_sr.argtypes = [PP] + [vp] * 6 + [C.c_uint64] + [vp] * 4
         L.hq_gemm_wgrad.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.hq_gemm_wgrad_update.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp, C.c_int32, vp]
         L.hq_range_update.argtypes = [vp, vp, vp]
         L.hq_range_update_batch.argtypes = [vp, vp, C.c_int32, vp]
         L.hq_gemm_dynamic.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 10 + [C.c_size_t, vp]
@@ -131,6 +132,12 @@ def hq_gemm_dgrad_sr(p, dY, gq, Wd, wq, wdsum, gr, seed, dX, dxq, st, stream=Non
 def hq_gemm_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, ws_bytes, stream=None):
     _check("hq_gemm_wgrad", lib().hq_gemm_wgrad(C.byref(p), _ptr(X), _ptr(xq), _ptr(dY), _ptr(gq), _ptr(dW),
                                                 _ptr(dW_acc), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def hq_gemm_wgrad_update(p, X, xq, dY, gq, dW, dW_acc, ws, ws_bytes, r, st, n, stream=None):
+    _check("hq_gemm_wgrad_update", lib().hq_gemm_wgrad_update(C.byref(p), _ptr(X), _ptr(xq), _ptr(dY), _ptr(gq), _ptr(dW),
+                                                              _ptr(dW_acc), _ptr(ws), ws_bytes, _ptr(r), _ptr(st), n,
+                                                              _stream(stream)))
 
 
 def hq_range_update(r, st, stream=None):

@@ -24,22 +24,7 @@ __device__ inline void stats_clear_wave(hq_stats *st)
 
 __global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats *st)
 {
-    r += blockIdx.x; st += blockIdx.x;
-    // every load of the kernel is issued before anything waits: one memory round trip
-    hq_range rr = *r;
-    const float acc_scale = st->acc_scale;
-    const unsigned fp32_keys = st->fp32_keys;
-    const unsigned long long count = st->count;
-    const HqStatsFolded f = hq_stats_fold_wave(st);
-    if (threadIdx.x == 0) {
-        if (count != 0) {
-            if (fp32_keys) hq_ema_update(&rr, hq_key_float(f.acc_min), hq_key_float(f.acc_max));
-            else hq_ema_update(&rr, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
-            *r = rr;
-        }
-        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->fp32_keys = 0;
-        st->clip_lo = 0; st->clip_hi = 0; st->count = 0;           // the partial records are already empty
-    }
+    hq_range_update_wave(r + blockIdx.x, st + blockIdx.x);
 }
 
 __global__ __launch_bounds__(64) void stats_reset_kernel(hq_stats *st) { stats_clear_wave(st + blockIdx.x); }
@@ -315,6 +300,23 @@ int hq_gemm_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, co
     if (p->kind == HQ_DEPTHWISE)
         return hq_launch_depthwise_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream));
     return hq_launch_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream));
+}
+
+int hq_gemm_wgrad_update(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
+                         const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, size_t ws_bytes,
+                         hq_range *r, hq_stats *st, int32_t n, void *stream)
+{
+    int rc = check_problem(p);
+    if (rc != HQ_OK) return rc;
+    if (!X || !xq || !dY || !gq || !dW || !r || !st || n < 1 || n > 4096) return HQ_E_BADARG;
+    if (misaligned(X, 16) || misaligned(dY, 16) || misaligned(dW, 16) || misaligned(dW_acc, 16) ||
+        misaligned(xq, 4) || misaligned(gq, 4) || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
+    const size_t need = hq_wgrad_workspace_bytes(p);
+    if (need && (!ws || ws_bytes < need || misaligned(ws, 16))) return HQ_E_WORKSPACE;
+    const HqRideAlong ra = {r, st, n, 0};
+    if (p->kind == HQ_DEPTHWISE)
+        return hq_launch_depthwise_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream), &ra);
+    return hq_launch_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream), &ra);
 }
 
 int hq_range_update(hq_range *r, hq_stats *st, void *stream)

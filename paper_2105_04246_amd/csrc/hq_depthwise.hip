@@ -470,8 +470,9 @@ __global__ void dw_zero_kernel(int32_t *p, size_t n)
 
 __global__ void dw_wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, const int32_t *xsum,
                                          const hq_qparams *xq, const hq_qparams *gq, unsigned M, int K, int C,
-                                         float *dW, int32_t *dW_acc)
+                                         float *dW, int32_t *dW_acc, const HqRideAlong ride)
 {
+    if (hq_ride_along(ride)) return;
     const unsigned zx = (unsigned)xq->zero_point, zg = (unsigned)gq->zero_point;
     const float s = __fmul_rn(xq->scale, gq->scale);
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -525,9 +526,12 @@ int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const h
 }
 
 int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
-                              const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream)
+                              const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream,
+                              const HqRideAlong *ride)
 {
     if (p->R * p->S > DW_MAX_TAPS) return HQ_E_BADSHAPE;
+    HqRideAlong ra = {nullptr, nullptr, 0, 0};
+    if (ride) ra = *ride;
     const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
     const int taps = p->R * p->S;
     const size_t K = (size_t)taps * p->C;
@@ -559,8 +563,9 @@ int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qpa
         if (gz > p->B) gz = p->B;
         hipLaunchKernelGGL(hq_dw3x3_wgrad_kernel, dim3((unsigned)xb, (unsigned)strips, (unsigned)gz), dim3(HQ_THREADS),
                            19 * (size_t)p->C * 4, stream, d);
-        hipLaunchKernelGGL(dw_wgrad_finalize_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream,
-                           a.acc, a.gsum, a.xsum, xq, gq, (unsigned)a.M, (int)K, p->C, dW, dW_acc);
+        ra.first = (int)((K + 255) / 256);
+        hipLaunchKernelGGL(dw_wgrad_finalize_kernel, dim3((unsigned)((K + 255) / 256) + (unsigned)ra.n), dim3(256), 0, stream,
+                           a.acc, a.gsum, a.xsum, xq, gq, (unsigned)a.M, (int)K, p->C, dW, dW_acc, ra);
         return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
     }
     a.CT = p->C < 256 ? p->C : 256;
@@ -572,7 +577,8 @@ int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qpa
     const size_t lds_bytes = (size_t)(2 * taps + 1) * a.CT * 4;       // at most 19 KiB
     hipLaunchKernelGGL(hq_depthwise_wgrad_kernel, dim3((unsigned)blocks, (unsigned)ctiles), dim3(HQ_THREADS),
                        lds_bytes, stream, a);
-    hipLaunchKernelGGL(dw_wgrad_finalize_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, stream,
-                       a.acc, a.gsum, a.xsum, xq, gq, (unsigned)a.M, (int)K, p->C, dW, dW_acc);
+    ra.first = (int)((K + 255) / 256);
+    hipLaunchKernelGGL(dw_wgrad_finalize_kernel, dim3((unsigned)((K + 255) / 256) + (unsigned)ra.n), dim3(256), 0, stream,
+                       a.acc, a.gsum, a.xsum, xq, gq, (unsigned)a.M, (int)K, p->C, dW, dW_acc, ra);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }

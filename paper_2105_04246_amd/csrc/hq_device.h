@@ -345,3 +345,35 @@ __device__ inline HqStatsFolded hq_stats_fold_wave(hq_stats *st)
     if (lane == 0) { st->acc_min = f.acc_min; st->acc_max = f.acc_max; st->clip_lo = f.clip_lo; st->clip_hi = f.clip_hi; }
     return f;
 }
+
+// eq. (2)-(3) for one quantizer, by one wavefront: folds the statistics record, moves the range,
+// derives the quantizer, empties the record.  With count == 0 the range is left as it is.
+__device__ inline void hq_range_update_wave(hq_range *r, hq_stats *st)
+{
+    // every load is issued before anything waits: one memory round trip
+    hq_range rr = *r;
+    const float acc_scale = st->acc_scale;
+    const unsigned fp32_keys = st->fp32_keys;
+    const unsigned long long count = st->count;
+    const HqStatsFolded f = hq_stats_fold_wave(st);
+    if ((threadIdx.x & 63) == 0) {
+        if (count != 0) {
+            if (fp32_keys) hq_ema_update(&rr, hq_key_float(f.acc_min), hq_key_float(f.acc_max));
+            else hq_ema_update(&rr, __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
+            *r = rr;
+        }
+        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->fp32_keys = 0;
+        st->clip_lo = 0; st->clip_hi = 0; st->count = 0;           // the partial records are already empty
+    }
+}
+
+// Range updates that ride along with another launch: the workgroups past `first` of that launch
+// (one per quantizer, their first wavefront) run eq. (2)-(3) instead of the launch's own work.
+struct HqRideAlong { hq_range *r; hq_stats *st; int n; int first; };
+
+__device__ inline bool hq_ride_along(const HqRideAlong &ra)
+{
+    if (ra.n == 0 || (int)blockIdx.x < ra.first) return false;
+    if (threadIdx.x < 64) hq_range_update_wave(ra.r + (blockIdx.x - ra.first), ra.st + (blockIdx.x - ra.first));
+    return true;
+}

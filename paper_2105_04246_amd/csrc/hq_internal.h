@@ -34,8 +34,12 @@ int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const h
 
 size_t hq_wgrad_workspace_bytes(const hq_problem *p);
 
+// ride: range updates to run in the call's last launch (NULL: none); see HqRideAlong.
+struct HqRideAlong;
 int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
-                    const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream);
+                    const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream,
+                    const HqRideAlong *ride = nullptr);
 
 int hq_launch_depthwise_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
-                              const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream);
+                              const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream,
+                              const HqRideAlong *ride = nullptr);

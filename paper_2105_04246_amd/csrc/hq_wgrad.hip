@@ -566,12 +566,14 @@ __global__ void zero_kernel(int32_t *p, size_t n)
 // result fits 32 bits) and applies the one FP32 scale.
 __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, const int32_t *xsum,
                                       const hq_qparams *xq, const hq_qparams *gq, unsigned M, int N, int K,
-                                      int gsum_per_k, float *dW, int32_t *dW_acc)
+                                      int gsum_per_k, float *dW, int32_t *dW_acc, const HqRideAlong ride)
 {
+    if (hq_ride_along(ride)) return;
     const unsigned zx = (unsigned)xq->zero_point, zg = (unsigned)gq->zero_point;
     const float s = __fmul_rn(xq->scale, gq->scale);
     const size_t total = (size_t)N * K;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const unsigned nblocks = ride.n ? (unsigned)ride.first : gridDim.x;       // workgroups doing this kernel's own work
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)nblocks * blockDim.x) {
         const int n = (int)(i / K), k = (int)(i % K);
         const unsigned g = (unsigned)gsum[gsum_per_k ? k % gsum_per_k : n];
         unsigned c = (unsigned)acc[i] - zx * g - zg * (unsigned)xsum[k] + M * zx * zg;
@@ -587,8 +589,10 @@ __global__ void wgrad_finalize_kernel(const int32_t *acc, const int32_t *gsum, c
 template <int TY>
 __global__ __launch_bounds__(64 * TY) void wband_finalize_kernel(const int32_t *partial, const int32_t *sums,
                                                               const hq_qparams *xq, const hq_qparams *gq, unsigned M,
-                                                              int N, int C, int splits, float *dW, int32_t *dW_acc)
+                                                              int N, int C, int splits, float *dW, int32_t *dW_acc,
+                                                              const HqRideAlong ride)
 {
+    if (hq_ride_along(ride)) return;
     __shared__ v4i sh[TY][64];
     __shared__ int shx[TY][64], shg[TY][4];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -724,8 +728,11 @@ size_t hq_wgrad_workspace_bytes(const hq_problem *p)
 }
 
 int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
-                    const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream)
+                    const hq_qparams *gq, float *dW, int32_t *dW_acc, void *ws, hipStream_t stream,
+                    const HqRideAlong *ride)
 {
+    HqRideAlong ra = {nullptr, nullptr, 0, 0};
+    if (ride) ra = *ride;
     const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
     const size_t K = (size_t)p->R * p->S * p->C;
     WgradArgs a;
@@ -747,16 +754,17 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
         int32_t *sums = reinterpret_cast<int32_t *>(w + sums_bytes + wband_partial_bytes(pl));
         if (!launch_wgrad_band(p, pl, a, partial, sums, stream)) return HQ_E_HIP;
         const size_t quads = (size_t)a.N / 4 * K;              // multiple of 64 (C % 64 == 0)
-        const dim3 fgrid((unsigned)(quads / 64));
+        ra.first = (int)(quads / 64);
+        const dim3 fgrid((unsigned)(quads / 64) + (unsigned)ra.n);
         if (pl.splits >= 48)
             hipLaunchKernelGGL(wband_finalize_kernel<16>, fgrid, dim3(1024), 0, stream, partial, sums, xq, gq,
-                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc);
+                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc, ra);
         else if (pl.splits >= 12)
             hipLaunchKernelGGL(wband_finalize_kernel<4>, fgrid, dim3(256), 0, stream, partial, sums, xq, gq,
-                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc);
+                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc, ra);
         else
             hipLaunchKernelGGL(wband_finalize_kernel<1>, fgrid, dim3(64), 0, stream, partial, sums, xq, gq,
-                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc);
+                               (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc, ra);
         return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
     }
 
@@ -789,7 +797,8 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
 
     const size_t total = (size_t)a.N * K;
     unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
-    hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb), dim3(256), 0, stream, a.acc, a.gsum, a.xsum, xq, gq,
-                       (unsigned)a.M, a.N, (int)K, 0, dW, dW_acc);
+    ra.first = (int)fb;
+    hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb + (unsigned)ra.n), dim3(256), 0, stream, a.acc, a.gsum, a.xsum, xq, gq,
+                       (unsigned)a.M, a.N, (int)K, 0, dW, dW_acc, ra);
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }

@@ -86,6 +86,7 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.hq_range_update(nul, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_probe_mfma_rate(4, 4, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_weight_quantize(nul, 16, nul, nul, nul) == hq.HQ_E_BADARG
+    assert L.hq_gemm_wgrad_update(ctypes.byref(good), *([nul] * 7), 0, nul, nul, 2, nul) == hq.HQ_E_BADARG
     assert L.hq_gemm_dynamic_sr(hq.HQ_ENTRY_FWD, 0, ctypes.byref(good), *([nul] * 6), 1, *([nul] * 4), 0, nul) == hq.HQ_E_BADARG
     assert L.hq_tensor_quantize(nul, 16, nul, nul, nul, nul, nul) == hq.HQ_E_BADARG
     assert L.hq_tensor_quantize_sr(nul, 16, nul, 5, nul, nul, nul, nul) == hq.HQ_E_BADARG

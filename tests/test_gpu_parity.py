@@ -697,6 +697,57 @@ def test_side_stream_and_graph_replay(H, hq, L):
         torch.cuda.synchronize()
 
 
+RIDE = [wl.conv("ride_band", 4, 20, 64, 64, 3), wl.conv("ride_tiles", 2, 9, 24, 40, 3), wl.conv("ride_first", 2, 23, 4, 48, 7, stride=2),
+        wl.conv("ride_c128", 2, 14, 128, 128, 3), wl.depthwise("ride_dw3", 2, 13, 48), wl.depthwise("ride_dw_s2", 2, 12, 32, stride=2),
+        wl.linear("ride_lin", 96, 2048, 2048)]
+
+
+@pytest.mark.parametrize("L", RIDE, ids=[l.name for l in RIDE])
+def test_wgrad_with_range_updates_riding_along(H, hq, L):
+    """hq_gemm_wgrad_update = hq_gemm_wgrad + hq_range_update_batch: same weight gradient, same
+    ranges, statistics consumed, on every weight-gradient path; two steps in a row."""
+    X, W, dY = rand_layer_inputs(L, 6100)
+    Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
+    p = H.hq_problem(L)
+    rs, ss = hq.RANGE.itemsize, hq.STATS.itemsize
+    nws = max(hq.hq_workspace_bytes(e, p) for e in (hq.HQ_ENTRY_WGRAD, hq.HQ_ENTRY_DYNAMIC_FWD, hq.HQ_ENTRY_DYNAMIC_DGRAD))
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+    Y = torch.empty(wl.out_shape(L), dtype=torch.int8, device="cuda")
+    dX = torch.empty(wl.in_shape(L), dtype=torch.int8, device="cuda")
+    yq, dxq = hq.new_qparams(0, 0), hq.new_qparams(0, 0)
+    results = []
+    for fused_update in (False, True):
+        R, ST = hq.new_ranges([False, True]), hq.new_stats(2)
+        dW = torch.zeros(wl.w_shape(L), dtype=torch.float32, device="cuda")
+        dWa = torch.zeros(wl.w_shape(L), dtype=torch.int32, device="cuda")
+        hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_FWD, hq.HQ_DYN_CURRENT, p, Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, R[:rs], Y, yq,
+                           ST[:ss], ws, nws)
+        hq.hq_gemm_dynamic(hq.HQ_ENTRY_DYNAMIC_DGRAD, hq.HQ_DYN_CURRENT, p, dYd.codes, dYd.qp, Wdev.Wd, Wdev.qp, Wdev.wdsum, R[rs:], dX,
+                           dxq, ST[ss:], ws, nws)
+        hq.hq_range_update_batch(R, ST, 2)
+        snaps = []
+        for step in range(2):
+            Xd.qp.copy_(hq.new_qparams(float(X.scale) * 1.2 ** step, X.zero_point))
+            hq.hq_gemm_fwd(p, Xd.codes, Xd.qp, Wdev.W, Wdev.qp, Wdev.wsum, R[:rs], Y, yq, ST[:ss])
+            hq.hq_gemm_dgrad(p, dYd.codes, dYd.qp, Wdev.Wd, Wdev.qp, Wdev.wdsum, R[rs:], dX, dxq, ST[ss:])
+            if fused_update:
+                hq.hq_gemm_wgrad_update(p, Xd.codes, Xd.qp, dYd.codes, dYd.qp, dW, dWa, ws, nws, R, ST, 2)
+            else:
+                hq.hq_gemm_wgrad(p, Xd.codes, Xd.qp, dYd.codes, dYd.qp, dW, dWa, ws, nws)
+                hq.hq_range_update_batch(R, ST, 2)
+            torch.cuda.synchronize()
+            st = hq.from_device(ST, hq.STATS)
+            assert (st["count"] == 0).all() and (st["acc_min"] == 2**31 - 1).all() and (st["part"]["clip_hi"] == 0).all()
+            snaps.append([t.clone() for t in (dW, dWa, R, Y, dX)])
+        results.append(snaps)
+        Xd.qp.copy_(hq.new_qparams(float(X.scale), X.zero_point))
+    for a, b in zip(results[0], results[1]):
+        assert all(torch.equal(x, y) for x, y in zip(a, b))
+    ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+    assert np.array_equal(results[1][1][1].cpu().numpy(), ref)
+    assert not torch.equal(results[1][0][2], results[1][1][2])          # the ranges did move between the steps
+
+
 NARROW = [wl.conv("nb_band", 2, 20, 64, 64, 3), wl.conv("nb_gemm", 2, 9, 24, 40, 3),
           wl.conv("nb_bandw", 1, 12, 128, 128, 3), wl.conv("nb_first", 2, 23, 4, 48, 7, stride=2),
           wl.depthwise("nb_dw", 2, 13, 48), wl.linear("nb_lin", 300, 72, 80)]
