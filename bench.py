@@ -125,7 +125,7 @@ class Layer:
         self.fwd(); self.dgrad(); self.wgrad(); self.upd_both()
 
     def dynamic_step(self):
-        self.dyn_fwd(); self.dyn_dgrad(); self.wgrad(); self.upd_both()
+        self.dyn_fwd(); self.dyn_dgrad(); self.wgrad_upd()
 
 
 class DeviceLayer(Layer):
