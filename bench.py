@@ -342,7 +342,7 @@ def main():
     # timed region: exactly K steps.  The dominant launch is bracketed by events on every EV-th step only:
     # an event between two kernels keeps the second from starting while the first drains, which costs
     # the step about as much as the range update does
-    EV = 5
+    EV = 10
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range((K + EV - 1) // EV)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
