@@ -70,7 +70,11 @@ class Range(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        if os.environ.get("HQ_ORACLE_SANITIZE") == "1":       # the instrumented build, see build_sanitized.py
+            from . import build_sanitized
+            path = build_sanitized.build(force=False)
+        else:
+            path = _build.build(force=False)
         L = C.CDLL(path)
         i8p, i32p, i64p, f32p = (C.POINTER(t) for t in (C.c_int8, C.c_int32, C.c_int64, C.c_float))
         PP = C.POINTER(Problem)

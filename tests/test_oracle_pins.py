@@ -643,3 +643,79 @@ def test_workload_shapes_match_the_configurations():
     assert [l.Cout for l in layers if l.name.endswith("conv0")] == [64, 128, 256, 512]
     assert wl.out_hw(layers[0]) == (112, 112) and wl.out_hw(layers[5]) == (28, 28)
     assert abs(wl.c3_grad_scale(49) - 1e-3) < 1e-12 and wl.c3_grad_scale(0) == 1.0
+
+
+# --------------------------------------------------------------------------- FP32 weight gradient
+def _rne_f32(x):
+    """Exact rational -> nearest fp32 (ties to even), computed in integers: the one rounding an
+    IEEE single-precision operation performs on its exact result."""
+    x = Fraction(x)
+    if x == 0:
+        return f32(0.0)
+    sign, ax = (-1 if x < 0 else 1), abs(x)
+    e = ax.numerator.bit_length() - ax.denominator.bit_length()       # 2^(e-1) < ax < 2^(e+1)
+    if Fraction(2) ** e > ax:
+        e -= 1                                                          # now 2^e <= ax < 2^(e+1)
+    ulp_exp = max(e - 23, -149)                                         # subnormals share one spacing
+    q = ax / Fraction(2) ** ulp_exp
+    n, rem = divmod(q.numerator, q.denominator)
+    twice = 2 * rem
+    if twice > q.denominator or (twice == q.denominator and (n & 1)):
+        n += 1
+    v = sign * Fraction(n) * Fraction(2) ** ulp_exp
+    assert abs(v) < Fraction(2) ** 128
+    out = f32(float(v))                                                 # v is representable: exact
+    assert Fraction(float(out)) == v
+    return out
+
+
+def _fr(x):
+    return Fraction(float(x))
+
+
+def test_fp32_weight_gradient_scale_is_pinned_by_exact_rationals():
+    """Sec. 3.1 keeps the weight gradient in FP32: dW = (s_x * s_g) * float(c), the scale product
+    rounded first, then one multiply per element.  Expectations come from exact rational
+    arithmetic with one explicit rounding per operation; the cases include triples on which the
+    other association s_x * (s_g * c), and a double-precision product rounded once, give
+    different bits, so an oracle with either of those fails here."""
+    assert _rne_f32(Fraction(1, 3)) == f32(1.0) / f32(3.0) and _rne_f32(Fraction(16777217)) == f32(16777216.0)
+    assert _rne_f32(Fraction(16777219)) == f32(16777220.0) and _rne_f32(Fraction(-5, 2 ** 151)) == f32(-2.0 ** -149)
+
+    # hand values, exact in fp32 (powers of two and small integers)
+    got = oracle.wgrad_scale(np.array([0, 1, -1, 3, -7, 2 ** 24, -2 ** 31], np.int32), 0.5, 0.25)
+    assert got.tolist() == [0.0, 0.125, -0.125, 0.375, -0.875, 2097152.0, -268435456.0]
+    assert oracle.acc_scale(0.5, 0.25) == f32(0.125) and oracle.acc_scale(3.0, 0.0625) == f32(0.1875)
+
+    g = np.random.default_rng(20210504)
+    differs_assoc = differs_double = differs_conv = 0
+    for _ in range(300):
+        sx = f32(g.uniform(1e-3, 0.1)); sg = f32(g.uniform(1e-6, 1e-2))
+        c = np.concatenate([g.integers(-2 ** 31, 2 ** 31, 48), g.integers(-3000, 3000, 16),
+                            [2 ** 24 + 1, 2 ** 25 + 3, -(2 ** 30) - 65, 2 ** 31 - 1]]).astype(np.int32)
+        s = _rne_f32(_fr(sx) * _fr(sg))
+        assert oracle.acc_scale(sx, sg) == s and oracle.acc_scale(sg, sx) == s
+        got = oracle.wgrad_scale(c, sx, sg)
+        for ci, gi in zip(c.tolist(), got):
+            cf = _rne_f32(Fraction(ci))                                # int32 -> fp32 conversion rounds
+            want = _rne_f32(_fr(s) * _fr(cf))
+            assert gi == want and np.signbit(gi) == np.signbit(want), (sx, sg, ci, gi, want)
+            differs_assoc += _rne_f32(_fr(sx) * _fr(_rne_f32(_fr(sg) * _fr(cf)))) != want
+            differs_double += _rne_f32(_fr(sx) * _fr(sg) * ci) != want
+            differs_conv += _rne_f32(_fr(s) * ci) != want
+    # the cases do tell the three plausible mistakes apart from the definition
+    assert differs_assoc > 100 and differs_double > 100 and differs_conv > 100
+
+
+def test_accumulator_unit_feeds_the_range_update_as_one_fp32_product():
+    """The real value of one accumulator unit is the fp32 product s_a * s_b (one rounding); the
+    statistics enter eq. (2)-(3) as that product times the integer extreme (a second rounding)."""
+    g = np.random.default_rng(7)
+    for _ in range(50):
+        sa = f32(g.uniform(1e-3, 0.1)); sb = f32(g.uniform(1e-4, 0.05))
+        mn, mx = int(g.integers(-2 ** 30, 0)), int(g.integers(1, 2 ** 30))
+        r = oracle.Range.new(0.9, False)
+        a = oracle.acc_scale(sa, sb)
+        oracle.range_update(r, mn, mx, a)                               # sets q^0 = min-max of the first batch
+        assert f32(r.qmin) == _rne_f32(_fr(a) * _fr(_rne_f32(Fraction(mn))))
+        assert f32(r.qmax) == _rne_f32(_fr(a) * _fr(_rne_f32(Fraction(mx))))
