@@ -206,7 +206,10 @@ int hq_range_update_batch(hq_range *r, hq_stats *st, int32_t n, void *stream);
  *             HQ_DYN_RUNNING: running min-max (Sec. 4.1, last paragraph): r is first moved by
  *             eq. (2)-(3) with THIS tensor's statistics, then used to quantize it.
  *   r         supplies the grid (qlo, qhi, symmetric) and eta; see `mode` for what is written
- *   st        as in hq_gemm_fwd (left filled, so hq_range_update can follow)
+ *   st        as in hq_gemm_fwd.  HQ_DYN_CURRENT leaves it filled, so that hq_range_update can follow
+ *             and move r by eq. (2)-(3).  HQ_DYN_RUNNING has already moved r with these statistics:
+ *             follow it with hq_stats_reset, not hq_range_update (which would apply the same
+ *             minimum and maximum to r a second time)
  *   ws        >= hq_workspace_bytes(op, p) bytes: the 32-bit round trip                     */
 #define HQ_DYN_CURRENT 0
 #define HQ_DYN_RUNNING 1
@@ -276,7 +279,9 @@ int hq_tensor_quantize_sr(const float *X, size_t n, const hq_range *r, uint64_t 
  * (8 bytes read, 1 byte written per element).  mode, r, st as for hq_gemm_dynamic: HQ_DYN_CURRENT
  * quantizes with this tensor's own range and sets q^0 if r is not initialized; HQ_DYN_RUNNING
  * moves r by eq. (2)-(3) with this tensor first and quantizes with the result.  st is left
- * filled, so hq_range_update can follow.  With n == 0, q_out receives r->qp and r is untouched. */
+ * filled: after HQ_DYN_CURRENT hq_range_update can follow, after HQ_DYN_RUNNING hq_stats_reset
+ * (the range has already taken these statistics in).  With n == 0, q_out receives r->qp and r is
+ * untouched.                                                                                   */
 int hq_tensor_quantize_dynamic(int32_t mode, const float *X, size_t n, hq_range *r, int8_t *Q,
                                hq_qparams *q_out, hq_stats *st, void *stream);
 

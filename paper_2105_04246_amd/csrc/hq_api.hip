@@ -245,7 +245,7 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
     if (rc != HQ_OK) return rc;
     if (!A || !aq || !Bw || !bq || !bsum || !range || !st || (!out && !out32) || (out && !outq)) return HQ_E_BADARG;
     if (misaligned(A, 16) || misaligned(Bw, 16) || misaligned(bsum, 16) || misaligned(out, 16) ||
-        misaligned(out32, 16) || misaligned(st, 8) || misaligned(range, 4) || misaligned(aq, 4) ||
+        misaligned(out32, 16) || misaligned(st, 128) || misaligned(range, 4) || misaligned(aq, 4) ||
         misaligned(bq, 4) || misaligned(outq, 4)) return HQ_E_BADARG;
     if (sr_seed) {
         // stochastic rounding: the two 3x3 / 1x1 fast paths, else the two general kernels
@@ -310,7 +310,7 @@ int hq_gemm_wgrad_update(const hq_problem *p, const int8_t *X, const hq_qparams 
     if (rc != HQ_OK) return rc;
     if (!X || !xq || !dY || !gq || !dW || !r || !st || n < 1 || n > 4096) return HQ_E_BADARG;
     if (misaligned(X, 16) || misaligned(dY, 16) || misaligned(dW, 16) || misaligned(dW_acc, 16) ||
-        misaligned(xq, 4) || misaligned(gq, 4) || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
+        misaligned(xq, 4) || misaligned(gq, 4) || misaligned(r, 4) || misaligned(st, 128)) return HQ_E_BADARG;
     const size_t need = hq_wgrad_workspace_bytes(p);
     if (need && (!ws || ws_bytes < need || misaligned(ws, 16))) return HQ_E_WORKSPACE;
     const HqRideAlong ra = {r, st, n, 0};
@@ -321,28 +321,28 @@ int hq_gemm_wgrad_update(const hq_problem *p, const int8_t *X, const hq_qparams 
 
 int hq_range_update(hq_range *r, hq_stats *st, void *stream)
 {
-    if (!r || !st || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
+    if (!r || !st || misaligned(r, 4) || misaligned(st, 128)) return HQ_E_BADARG;
     hipLaunchKernelGGL(range_update_kernel, dim3(1), dim3(64), 0, as_stream(stream), r, st);
     return launch_status();
 }
 
 int hq_range_update_batch(hq_range *r, hq_stats *st, int32_t n, void *stream)
 {
-    if (!r || !st || n <= 0 || misaligned(r, 4) || misaligned(st, 8)) return HQ_E_BADARG;
+    if (!r || !st || n <= 0 || misaligned(r, 4) || misaligned(st, 128)) return HQ_E_BADARG;
     hipLaunchKernelGGL(range_update_kernel, dim3(n), dim3(64), 0, as_stream(stream), r, st);
     return launch_status();
 }
 
 int hq_stats_reset(hq_stats *st, int32_t n, void *stream)
 {
-    if (!st || n <= 0 || misaligned(st, 8)) return HQ_E_BADARG;
+    if (!st || n <= 0 || misaligned(st, 128)) return HQ_E_BADARG;
     hipLaunchKernelGGL(stats_reset_kernel, dim3(n), dim3(64), 0, as_stream(stream), st);
     return launch_status();
 }
 
 int hq_stats_fold(hq_stats *st, int32_t n, void *stream)
 {
-    if (!st || n <= 0 || misaligned(st, 8)) return HQ_E_BADARG;
+    if (!st || n <= 0 || misaligned(st, 128)) return HQ_E_BADARG;
     hipLaunchKernelGGL(stats_fold_kernel, dim3(n), dim3(64), 0, as_stream(stream), st);
     return launch_status();
 }
