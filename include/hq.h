@@ -171,6 +171,22 @@ int hq_gemm_wgrad(const hq_problem *p /* host */,
                   const int8_t *dY, const hq_qparams *gq,
                   float *dW, int32_t *dW_acc, void *ws, size_t ws_bytes, void *stream);
 
+/* hq_gemm_wgrad for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the workspace is a fixed array of
+ * HQ_STATIC_SCRATCH_BYTES that the library itself holds on every GPU it is loaded on, from load
+ * until the process ends.  No allocation happens in this call or below it.  Same kernels, same
+ * results and same remaining arguments as hq_gemm_wgrad.
+ *   - Problems with hq_workspace_bytes(HQ_ENTRY_WGRAD, p) > HQ_STATIC_SCRATCH_BYTES are refused
+ *     with HQ_E_WORKSPACE and nothing is launched.
+ *   - All calls on one GPU share that GPU's array (each call clears what it needs at zero, the
+ *     rest is overwritten before it is read): calls that overlap in time on one GPU, e.g. on two
+ *     streams, race; calls on one stream, or otherwise ordered, do not.                        */
+#define HQ_STATIC_SCRATCH_BYTES (64u << 20)
+int hq_gemm_wgrad_static(const hq_problem *p /* host */,
+                         const int8_t *X, const hq_qparams *xq,
+                         const int8_t *dY, const hq_qparams *gq,
+                         float *dW, int32_t *dW_acc, void *stream);
+
 /* hq_gemm_wgrad followed by hq_range_update_batch(r, st, n) in one call: the range updates run as
  * n extra workgroups of the call's last launch, next to its own work, instead of in a launch of
  * their own.  For the layer step fwd, dgrad, wgrad: the statistics must come from launches earlier

@@ -16,6 +16,7 @@ HQ_OK, HQ_E_BADARG, HQ_E_BADSHAPE, HQ_E_WORKSPACE, HQ_E_HIP = 0, -1, -2, -3, -4
 HQ_LINEAR, HQ_CONV2D, HQ_DEPTHWISE = 0, 1, 2
 HQ_ENTRY_FWD, HQ_ENTRY_DGRAD, HQ_ENTRY_WGRAD, HQ_ENTRY_DYNAMIC_FWD, HQ_ENTRY_DYNAMIC_DGRAD = 0, 1, 2, 3, 4
 HQ_DYN_CURRENT, HQ_DYN_RUNNING = 0, 1
+HQ_STATIC_SCRATCH_BYTES = 64 << 20
 
 # Host views of the device structs (little-endian, same field order as include/hq.h).
 QPARAMS = np.dtype([("scale", "<f4"), ("zero_point", "<i4")])
@@ -46,7 +47,7 @@ class HqError(RuntimeError):
 
 
 _lib = None
-EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_gemm_wgrad_update", "hq_range_update",
+EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_gemm_wgrad_static", "hq_gemm_wgrad_update", "hq_range_update",
            "hq_range_update_batch",
            "hq_gemm_dynamic", "hq_gemm_dynamic_sr", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_sr", "hq_tensor_quantize_dynamic",
            "hq_probe_mfma_rate",
@@ -70,6 +71,7 @@ def lib():
         L.hq_gemm_dgrad.argtypes = [PP] + [vp] * 10
         L.hq_gemm_dgrad_sr.argtypes = [PP] + [vp] * 6 + [C.c_uint64] + [vp] * 4
         L.hq_gemm_wgrad.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.hq_gemm_wgrad_static.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp]
         L.hq_gemm_wgrad_update.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp, C.c_int32, vp]
         L.hq_range_update.argtypes = [vp, vp, vp]
         L.hq_range_update_batch.argtypes = [vp, vp, C.c_int32, vp]
@@ -132,6 +134,11 @@ def hq_gemm_dgrad_sr(p, dY, gq, Wd, wq, wdsum, gr, seed, dX, dxq, st, stream=Non
 def hq_gemm_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, ws_bytes, stream=None):
     _check("hq_gemm_wgrad", lib().hq_gemm_wgrad(C.byref(p), _ptr(X), _ptr(xq), _ptr(dY), _ptr(gq), _ptr(dW),
                                                 _ptr(dW_acc), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def hq_gemm_wgrad_static(p, X, xq, dY, gq, dW, dW_acc, stream=None):
+    _check("hq_gemm_wgrad_static", lib().hq_gemm_wgrad_static(C.byref(p), _ptr(X), _ptr(xq), _ptr(dY), _ptr(gq), _ptr(dW),
+                                                              _ptr(dW_acc), _stream(stream)))
 
 
 def hq_gemm_wgrad_update(p, X, xq, dY, gq, dW, dW_acc, ws, ws_bytes, r, st, n, stream=None):

@@ -4,7 +4,33 @@
 #include "hq_device.h"
 #include "hq_internal.h"
 
+#include <mutex>
+
+// Scratch memory of hq_gemm_wgrad_static: one array per GPU, held from the moment the library is
+// loaded on that GPU until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and launchers receive the device address that call returns.
+static __device__ __align__(256) unsigned char hq_static_scratch[HQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int HQ_MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[HQ_MAX_DEVICES];           // device address of hq_static_scratch on each GPU, once resolved
+
+// Device address of the current GPU's copy of the scratch array (resolved on the first call per GPU).
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= HQ_MAX_DEVICES) return HQ_E_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(hq_static_scratch)) != hipSuccess || !ptr) return HQ_E_HIP;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return HQ_OK;
+}
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -220,7 +246,7 @@ const char *hq_error_string(int code)
     case HQ_OK: return "ok";
     case HQ_E_BADARG: return "bad argument (null or misaligned pointer, bad enum)";
     case HQ_E_BADSHAPE: return "unsupported shape";
-    case HQ_E_WORKSPACE: return "workspace missing or too small";
+    case HQ_E_WORKSPACE: return "workspace missing, too small, or (static variant) problem beyond the built-in scratch";
     case HQ_E_HIP: return "HIP launch failed";
     default: return "unknown hq error code";
     }
@@ -300,6 +326,19 @@ int hq_gemm_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, co
     if (p->kind == HQ_DEPTHWISE)
         return hq_launch_depthwise_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream));
     return hq_launch_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, as_stream(stream));
+}
+
+int hq_gemm_wgrad_static(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
+                         const hq_qparams *gq, float *dW, int32_t *dW_acc, void *stream)
+{
+    int rc = check_problem(p);
+    if (rc != HQ_OK) return rc;
+    if (!X || !xq || !dY || !gq || !dW) return HQ_E_BADARG;
+    if (hq_wgrad_workspace_bytes(p) > (size_t)HQ_STATIC_SCRATCH_BYTES) return HQ_E_WORKSPACE;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != HQ_OK) return rc;
+    return hq_gemm_wgrad(p, X, xq, dY, gq, dW, dW_acc, ws, (size_t)HQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 int hq_gemm_wgrad_update(const hq_problem *p, const int8_t *X, const hq_qparams *xq, const int8_t *dY,
