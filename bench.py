@@ -70,7 +70,7 @@ class Layer:
         self.yr, self.gr, self.yst, self.gst = state
         self.ws_w = hq.hq_workspace_bytes(hq.HQ_ENTRY_WGRAD, self.p)
         self.ws_f = hq.hq_workspace_bytes(hq.HQ_ENTRY_DYNAMIC_FWD, self.p)
-        self.ws_d = hq.hq_workspace_bytes(hq.HQ_ENTRY_DYNAMIC_DGRAD, self.p)
+        self.ws_d = hq.hq_workspace_bytes(hq.HQ_ENTRY_DYNAMIC_DGRAD, self.p) if L.C != 3 else 0
         self.ws = torch.empty(max(self.ws_w, self.ws_f, self.ws_d, 16), dtype=torch.uint8, device="cuda")
 
     # the five entry points ------------------------------------------------------------
@@ -107,7 +107,9 @@ class Layer:
 
     def init_ranges(self):
         """Iteration 0: the first batch sets q^0 through the dynamic path (Sec. 4.1)."""
-        self.dyn_fwd(); self.upd_y(); self.dyn_dgrad(); self.upd_g()
+        self.dyn_fwd(); self.upd_y()
+        if self.L.C != 3:                      # a 3-channel first layer has no input gradient
+            self.dyn_dgrad(); self.upd_g()
 
     def upd_both(self):
         self.hq.hq_range_update_batch(self.ranges, self.stats, 2)

@@ -97,7 +97,10 @@ typedef struct {
  *           Wd [C][R][S][Cout]        the same weights re-laid for hq_gemm_dgrad (depthwise: = W)
  * Supported: C % 4 == 0 and Cout % 4 == 0 for HQ_LINEAR / HQ_CONV2D (full-rate path when the
  * reduced channel count is a multiple of 16); C % 4 == 0 for HQ_DEPTHWISE; B*H*W and
- * B*OH*OW below 2^31.                                                                        */
+ * B*OH*OW below 2^31.  In addition HQ_CONV2D takes C == 3 (a network's first layer on RGB images,
+ * pixels of 3 bytes) in hq_gemm_fwd, hq_gemm_dynamic (forward), hq_gemm_wgrad and
+ * hq_weight_prepare, for filters of at most 7 rows and S * 3 <= 32 bytes per row and Cout a
+ * multiple of 16 up to 64; the input gradient of such a layer is refused (HQ_E_BADSHAPE).      */
 typedef struct {
     int32_t kind;
     int32_t B, H, W, C;

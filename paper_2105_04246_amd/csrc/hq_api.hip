@@ -162,7 +162,8 @@ int check_problem(const hq_problem *p)
     if (p->kind == HQ_DEPTHWISE && p->Cout != p->C) return HQ_E_BADSHAPE;
     if (p->H + 2 * p->pad < p->R || p->W + 2 * p->pad < p->S) return HQ_E_BADSHAPE;
     if (p->pad >= p->R || p->pad >= p->S) return HQ_E_BADSHAPE;       // every output has a real tap
-    if ((p->C % 4) != 0 || (p->Cout % 4) != 0) return HQ_E_BADSHAPE;
+    // channel counts are multiples of 4, except that a convolution may read 3-channel (RGB) inputs
+    if (((p->C % 4) != 0 && !(p->kind == HQ_CONV2D && p->C == 3)) || (p->Cout % 4) != 0) return HQ_E_BADSHAPE;
     const long OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
     const long lim = 0x7fffffffL;
     if ((long)p->B * p->H * p->W >= lim || (long)p->B * OH * OW >= lim) return HQ_E_BADSHAPE;
@@ -273,6 +274,11 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
     if (misaligned(A, 16) || misaligned(Bw, 16) || misaligned(bsum, 16) || misaligned(out, 16) ||
         misaligned(out32, 16) || misaligned(st, 128) || misaligned(range, 4) || misaligned(aq, 4) ||
         misaligned(bq, 4) || misaligned(outq, 4)) return HQ_E_BADARG;
+    if (p->C == 3) {
+        // 3-channel input: the first-layer kernel or nothing (a network's first layer needs no input gradient)
+        if (dgrad || sr_seed) return HQ_E_BADSHAPE;
+        return hq_try_launch_direct(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
+    }
     if (sr_seed) {
         // stochastic rounding: the two 3x3 / 1x1 fast paths, else the two general kernels
         if (p->kind == HQ_DEPTHWISE)

@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
     wload(0, wv0);
     const int bs0 = tid < a.N ? a.bsum[tid] : 0;
     const int za = a.aq->zero_point;
-    const int fillw = (za & 0xff) * 0x01010101;
+    const int fillw = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const v4i fill = {fillw, fillw, fillw, fillw};
 
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int za = a.aq->zero_point;
-    const int fillw = (za & 0xff) * 0x01010101;
+    const int fillw = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const v4i fillv = {fillw, fillw, fillw, fillw}, zerov = {0, 0, 0, 0};
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
     HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_kernel(const DwArgs a
     const int c4n = a.C >> 2;
     const size_t total = (size_t)a.M * c4n;
     const int za = a.aq->zero_point;
-    const int fill = (za & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const bool fused = a.out32 == nullptr;
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
     HqRequant rq = {1.0f, 0.0f, 0.0f, 0};
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_kernel(const Dw3Args a)
     const size_t out_img = (size_t)blockIdx.z * a.H * a.W;
 
     const int za = a.aq->zero_point;
-    const int fill = (za & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const bool fused = a.out32 == nullptr;
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
     HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_depthwise_wgrad_kernel(const Dw
     for (int i = threadIdx.x; i < words; i += blockDim.x) lds[i] = 0;
     __syncthreads();
     const int zx = a.xq->zero_point;
-    const int fill = (zx & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(zx & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const int lanes_per_pixel = ct >> 2;                           // <= 64
     const int pixels_per_pass = HQ_THREADS / lanes_per_pixel;
     const int cg = threadIdx.x % lanes_per_pixel, prow = threadIdx.x / lanes_per_pixel;
@@ -354,7 +354,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_dw3x3_wgrad_kernel(const Dw3Wgr
     const int y0 = blockIdx.y * a.rows_per_strip, y1 = min(a.H, y0 + a.rows_per_strip);
     const int zx = a.xq->zero_point;
     const bool want_xsum = a.gq->zero_point != 0;
-    const int fill = (zx & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(zx & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const bool okl = ox > 0, okr = ox + 1 < a.W;
     const size_t rowbytes = (size_t)a.W * a.C;
 

@@ -1,5 +1,5 @@
-// Forward GEMM of a network's first layer (few input channels, e.g. the 7x7 stride-2 stem with the
-// image padded to 4 channels) on int8 MFMA with the fused in-hindsight epilogue (paper Sec. 3.1,
+// Forward GEMM of a network's first layer (3 or 4 input channels, e.g. the 7x7 stride-2 stem on RGB
+// images, or on images padded to 4 channels) on int8 MFMA with the fused in-hindsight epilogue (paper Sec. 3.1,
 // Sec. 3.2 static quantization, Sec. 4 steps 1 and 2).
 //
 // In NHWC the S taps of one filter row are S * C contiguous bytes of the input, and with
@@ -11,6 +11,10 @@
 // The weight fragments of all R k-steps stay in registers for the whole launch.  The output is
 // large compared with the input (64 channels out of 4), so the kernel is bound by the epilogue's
 // vector-ALU work and by the HBM write of the codes.
+// With 3 channels a pixel is 3 bytes, so a lane's 4-byte words start at any byte address and a word
+// can hold bytes of two taps: words are loaded unaligned and the bytes whose tap lies outside the
+// image (or past the filter row) are replaced under a per-word byte mask; the few words that would
+// reach past either end of the tensor are assembled from single bytes instead.
 #include "hq_device.h"
 #include "hq_internal.h"
 #include <type_traits>
@@ -29,15 +33,40 @@ struct DirectArgs {
     int32_t *out32;
     hq_qparams *outq;
     hq_stats *st;
-    int M, N, C, R, S, H, W, Ho, Wo, stride, pad;
+    int M, N, C, R, S, H, W, Ho, Wo, stride, pad, Bn;
     unsigned magic_Wo, magic_Ho;   // ceil(2^32 / d)
     int tiles;                     // tiles of 32 * DR_MI pixels
 };
 
 __device__ inline int dr_sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
-// NT: 32-channel blocks of the output (N <= 32 * NT).
-template <int NT, bool FUSED>
+// Bytes e of a 32-bit word with lo <= e < hi (little endian), as a mask of whole bytes.
+__device__ inline unsigned dr_bytemask(int lo, int hi)
+{
+    lo = max(lo, 0); hi = min(hi, 4);
+    if (hi <= lo) return 0u;
+    const unsigned upto_hi = hi == 4 ? 0xffffffffu : (1u << (8 * hi)) - 1u;
+    return upto_hi & ~((1u << (8 * lo)) - 1u);
+}
+
+// The 4 bytes at p (any alignment), of which only those under `mask` are wanted: one unaligned load when
+// the word lies inside [begin, end), single guarded bytes otherwise (first / last bytes of a tensor).
+__device__ inline unsigned dr_load_word(const int8_t *p, unsigned mask, const int8_t *begin, const int8_t *end)
+{
+    if (p >= begin && p + 4 <= end) {
+        unsigned v;
+        __builtin_memcpy(&v, p, 4);
+        return v;
+    }
+    unsigned v = 0;
+#pragma unroll
+    for (int e = 0; e < 4; e++)
+        if ((mask >> (8 * e)) & 1u) v |= (unsigned)(unsigned char)p[e] << (8 * e);
+    return v;
+}
+
+// NT: 32-channel blocks of the output (N <= 32 * NT).  CH: input channels, 4 (a tap is one aligned word) or 3.
+template <int NT, bool FUSED, int CH>
 __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectArgs a)
 {
     __shared__ int red[4 * (HQ_THREADS / 64)];
@@ -45,7 +74,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5;
     const int za = a.aq->zero_point;
-    const int fill = (za & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const int rowbytes = a.S * a.C;                     // valid bytes of a k-step
     if (tid < 32 * NT) bzs[tid] = tid < a.N ? za * a.bsum[tid] : 0;
 
@@ -61,8 +90,14 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
             if (r < a.R && n < a.N) {
                 const int8_t *w = a.Bw + ((size_t)n * a.R + r) * rowbytes + 16 * half;
 #pragma unroll
-                for (int d = 0; d < 4; d++)
-                    if (16 * half + 4 * d < rowbytes) v[d] = *reinterpret_cast<const int *>(w + 4 * d);
+                for (int d = 0; d < 4; d++) {
+                    if (CH == 4) {
+                        if (16 * half + 4 * d < rowbytes) v[d] = *reinterpret_cast<const int *>(w + 4 * d);
+                    } else {
+                        const unsigned mk = dr_bytemask(0, rowbytes - (16 * half + 4 * d));     // bytes of this filter row
+                        if (mk) v[d] = (int)(dr_load_word(w + 4 * d, mk, a.Bw, a.Bw + (size_t)a.N * a.R * rowbytes) & mk);
+                    }
+                }
             }
             wf[r][j] = v;
         }
@@ -84,26 +119,54 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
             const unsigned mm = ok ? (unsigned)m : 0u;
             const unsigned t = hq_magic_div(mm, a.magic_Wo), ox = mm - t * a.Wo;         // t = b * Ho + oy
             const unsigned b = hq_magic_div(t, a.magic_Ho), oy = t - b * a.Ho;
-            const int iy0 = (int)oy * a.stride - a.pad, ix0 = (int)ox * a.stride - a.pad + 4 * half;   // C == 4: tap = word
-            const int8_t *p0 = a.A + ((size_t)b * a.H * a.W + ix0) * a.C;
-            bool wok[4];
+            const int iy0 = (int)oy * a.stride - a.pad;
+            if (CH == 4) {
+                const int ix0 = (int)ox * a.stride - a.pad + 4 * half;                       // C == 4: tap = word
+                const int8_t *p0 = a.A + ((size_t)b * a.H * a.W + ix0) * a.C;
+                bool wok[4];
 #pragma unroll
-            for (int d = 0; d < 4; d++) wok[d] = ok && 4 * half + d < a.S && ix0 + d >= 0 && ix0 + d < a.W;
+                for (int d = 0; d < 4; d++) wok[d] = ok && 4 * half + d < a.S && ix0 + d >= 0 && ix0 + d < a.W;
 #pragma unroll
-            for (int r = 0; r < DR_MAXR; r++) {
-                // every lane loads (lanes without a source read the tensor's first word instead and
-                // drop it): no branch per word, and the loads of a tile issue back to back
-                v4i v;
-                const int iy = iy0 + r;
-                const bool rok = r < a.R && iy >= 0 && iy < a.H;
-                const int8_t *p = p0 + (ptrdiff_t)iy * a.W * a.C;
+                for (int r = 0; r < DR_MAXR; r++) {
+                    // every lane loads (lanes without a source read the tensor's first word instead and
+                    // drop it): no branch per word, and the loads of a tile issue back to back
+                    v4i v;
+                    const int iy = iy0 + r;
+                    const bool rok = r < a.R && iy >= 0 && iy < a.H;
+                    const int8_t *p = p0 + (ptrdiff_t)iy * a.W * a.C;
 #pragma unroll
-                for (int d = 0; d < 4; d++) {
-                    const bool k = rok && wok[d];
-                    const int x = *reinterpret_cast<const int *>(k ? p + 4 * d : a.A);
-                    v[d] = k ? x : fill;
+                    for (int d = 0; d < 4; d++) {
+                        const bool k = rok && wok[d];
+                        const int x = *reinterpret_cast<const int *>(k ? p + 4 * d : a.A);
+                        v[d] = k ? x : fill;
+                    }
+                    af[r][i] = v;
                 }
-                af[r][i] = v;
+            } else {
+                // byte k of the k-step is channel k % 3 of tap k / 3: the taps inside the image and the filter
+                // row are the bytes k0 <= k < k1, the same for every filter row of this pixel
+                const int ixb = (int)ox * a.stride - a.pad;
+                const int k0 = CH * max(0, -ixb), k1 = CH * min(a.S, a.W - ixb);
+                unsigned mk[4];
+#pragma unroll
+                for (int d = 0; d < 4; d++) mk[d] = ok ? dr_bytemask(k0 - (16 * half + 4 * d), k1 - (16 * half + 4 * d)) : 0u;
+                const int8_t *p0 = a.A + ((ptrdiff_t)b * a.H * a.W + ixb) * CH + 16 * half;
+                const int8_t *aend = a.A + (size_t)a.Bn * a.H * a.W * CH;
+#pragma unroll
+                for (int r = 0; r < DR_MAXR; r++) {
+                    v4i v;
+                    const int iy = iy0 + r;
+                    const bool rok = r < a.R && iy >= 0 && iy < a.H;
+                    const int8_t *p = p0 + (ptrdiff_t)iy * a.W * CH;
+#pragma unroll
+                    for (int d = 0; d < 4; d++) {
+                        const unsigned m = rok ? mk[d] : 0u;
+                        unsigned x = 0;
+                        if (m) x = dr_load_word(p + 4 * d, m, a.A, aend);
+                        v[d] = (int)((x & m) | ((unsigned)fill & ~m));
+                    }
+                    af[r][i] = v;
+                }
             }
         }
     };
@@ -187,20 +250,20 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
 
 } // namespace
 
-// Forward layers with 4 input channels, a filter row of at most 32 bytes, at most DR_MAXR filter
+// Forward layers with 3 or 4 input channels, a filter row of at most 32 bytes, at most DR_MAXR filter
 // rows and 16..64 output channels in multiples of 16; HQ_E_BADSHAPE means "not covered".
 int hq_try_launch_direct(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
                          const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
                          int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream)
 {
-    if (dgrad || p->kind != HQ_CONV2D || p->C != 4 || p->S * p->C > 32 || p->R > DR_MAXR) return HQ_E_BADSHAPE;
+    if (dgrad || p->kind != HQ_CONV2D || (p->C != 4 && p->C != 3) || p->S * p->C > 32 || p->R > DR_MAXR) return HQ_E_BADSHAPE;
     if (p->Cout > 64 || p->Cout % 16 != 0) return HQ_E_BADSHAPE;
     const int OH = (p->H + 2 * p->pad - p->R) / p->stride + 1, OW = (p->W + 2 * p->pad - p->S) / p->stride + 1;
     DirectArgs a;
     a.A = A; a.Bw = Bw; a.bsum = bsum; a.aq = aq; a.bq = bq; a.range = range;
     a.out8 = out8; a.out32 = out32; a.outq = outq; a.st = st;
     a.M = p->B * OH * OW; a.N = p->Cout; a.C = p->C; a.R = p->R; a.S = p->S; a.H = p->H; a.W = p->W;
-    a.Ho = OH; a.Wo = OW; a.stride = p->stride; a.pad = p->pad;
+    a.Ho = OH; a.Wo = OW; a.stride = p->stride; a.pad = p->pad; a.Bn = p->B;
     if ((unsigned long long)a.M * (unsigned long long)(OW > OH ? OW : OH) >= (1ull << 32)) return HQ_E_BADSHAPE;   // hq_magic_div's range
     a.magic_Wo = hq_magic32((unsigned)OW);
     a.magic_Ho = hq_magic32((unsigned)OH);
@@ -208,12 +271,13 @@ int hq_try_launch_direct(const hq_problem *p, int dgrad, const int8_t *A, const 
     int blocks = (a.tiles + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
     const bool fused = out32 == nullptr;
-    if (a.N > 32) {
-        if (fused) hipLaunchKernelGGL((hq_direct_kernel<2, true>), dim3(blocks), dim3(HQ_THREADS), 0, stream, a);
-        else       hipLaunchKernelGGL((hq_direct_kernel<2, false>), dim3(blocks), dim3(HQ_THREADS), 0, stream, a);
+    auto launch = [&](auto kern) { hipLaunchKernelGGL(kern, dim3(blocks), dim3(HQ_THREADS), 0, stream, a); };
+    if (p->C == 4) {
+        if (a.N > 32) { if (fused) launch(hq_direct_kernel<2, true, 4>); else launch(hq_direct_kernel<2, false, 4>); }
+        else          { if (fused) launch(hq_direct_kernel<1, true, 4>); else launch(hq_direct_kernel<1, false, 4>); }
     } else {
-        if (fused) hipLaunchKernelGGL((hq_direct_kernel<1, true>), dim3(blocks), dim3(HQ_THREADS), 0, stream, a);
-        else       hipLaunchKernelGGL((hq_direct_kernel<1, false>), dim3(blocks), dim3(HQ_THREADS), 0, stream, a);
+        if (a.N > 32) { if (fused) launch(hq_direct_kernel<2, true, 3>); else launch(hq_direct_kernel<2, false, 3>); }
+        else          { if (fused) launch(hq_direct_kernel<1, true, 3>); else launch(hq_direct_kernel<1, false, 3>); }
     }
     return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
 }

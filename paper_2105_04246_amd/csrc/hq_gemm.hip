@@ -137,7 +137,7 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
         const int rpp = HQ_THREADS / ppr;                   // rows per pass of the workgroup
         const int rl = tid / ppr, piece = tid - rl * ppr;
         const int zcode = a.range->qp.zero_point & 0xff;    // inside the grid by construction
-        const int fillw = zcode * 0x01010101;
+        const int fillw = (int)((unsigned)zcode * 0x01010101u);
         if (rl < rpp) {
             // the row's pixel is decoded once and then stepped (rpp rows per pass)
             int m = m0 + rl;
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
     }
 
     const int za = a.aq->zero_point;
-    const int fill = (za & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
 
     // z_a * (sum of the weights the reduction runs over), visible after the first barrier
     if (tid < BN) {

@@ -64,12 +64,42 @@ template <int P> __device__ inline v4i read_frag_tr(const int8_t *tile, int lane
     return f;
 }
 
+// Bytes e of a 32-bit word with lo <= e < hi (little endian), as a mask of whole bytes.
+__device__ inline unsigned wg_bytemask(int lo, int hi)
+{
+    lo = max(lo, 0); hi = min(hi, 4);
+    if (hi <= lo) return 0u;
+    const unsigned upto_hi = hi == 4 ? 0xffffffffu : (1u << (8 * hi)) - 1u;
+    return upto_hi & ~((1u << (8 * lo)) - 1u);
+}
+
+// The 4 bytes at p (any alignment), of which only those under `mask` are wanted: one unaligned load when
+// the word lies inside [begin, end), single guarded bytes otherwise (first / last bytes of a tensor).
+__device__ inline unsigned wg_load_word(const int8_t *p, unsigned mask, const int8_t *begin, const int8_t *end)
+{
+    if (p >= begin && p + 4 <= end) {
+        unsigned v;
+        __builtin_memcpy(&v, p, 4);
+        return v;
+    }
+    unsigned v = 0;
+#pragma unroll
+    for (int e = 0; e < 4; e++)
+        if ((mask >> (8 * e)) & 1u) v |= (unsigned)(unsigned char)p[e] << (8 * e);
+    return v;
+}
+
 // PACKED: layers with fewer than 16 input channels (a network's first layer).  The tile's columns
 // then run over (tap, channel) pairs as they lie in a row of G_W, so a 16-byte chunk of the staged
 // tile holds 16 / C taps (one 4-byte load each) instead of one tap padded with zeros.
-template <int TN, int TK, bool PACKED>
+// PACKED3: the same for 3-channel inputs (RGB images).  The S * 3 bytes of a filter row are contiguous in
+// the input, but a 4-byte word of columns starts at any byte and can run over into the next filter row:
+// it is put together from (at most) two unaligned loads under byte masks that drop the taps outside
+// the image.
+template <int TN, int TK, bool PACKED, bool PACKED3 = false>
 __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 {
+    static_assert(!PACKED3 || PACKED, "the 3-channel form is a packed form");
     constexpr int PG = TN + 32, PX = TK + 32;           // LDS pitches (32 mod 64: best for the transposing reads)
     constexpr int WTN = TN / 2, WTK = TK / 2;           // 2 x 2 wavefronts
     constexpr int NT = WTN / 32, KT = WTK / 32;
@@ -107,16 +137,27 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     const int m_begin = bz * a.m_per_split;
     const int m_end = min(a.M, m_begin + a.m_per_split);
     const int zx = a.xq->zero_point;
-    const int fill = (zx & 0xff) * 0x01010101;
+    const int fill = (int)((unsigned)(zx & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     // (a column sum is only ever multiplied by the other operand's zero point: not formed when that is 0)
     const bool do_gsum = bx == 0 && wk == 0 && zx != 0;                      // column sums of G: first tile column
     const bool do_xsum = by == 0 && wn == 0 && a.gq->zero_point != 0;        // column sums of Xg: first tile row
 
     int pk_r[4], pk_s[4], pk_off[4], pk_ow[XLD], pk_oh[XLD], pk_b[XLD];
+    int pk_n0[4], pk_n1[4];                      // PACKED3: bytes of word d in filter row pk_r[d] / in the row after it
     if (PACKED) {
 #pragma unroll
         for (int d = 0; d < 4; d++) {
             const int kc = c0 + (tid % XCH) * 16 + 4 * d;
+            if (PACKED3) {
+                // word d = columns kc .. kc + 3; column k is byte k % rowlen of filter row k / rowlen
+                const int rowlen = a.S * 3, nvalid = min(4, kcols - kc);
+                pk_r[d] = kc < kcols ? kc / rowlen : -1;
+                pk_s[d] = kc - (kc / rowlen) * rowlen;                 // byte inside the filter row
+                pk_n0[d] = max(0, min(nvalid, rowlen - pk_s[d]));
+                pk_n1[d] = max(0, nvalid - pk_n0[d]);
+                pk_off[d] = pk_r[d] * a.W * 3 + pk_s[d];
+                continue;
+            }
             const int t = kc / a.C, cc = kc - t * a.C;
             pk_r[d] = kc < kcols ? t / a.S : -1;
             pk_s[d] = t % a.S;
@@ -145,7 +186,33 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
             v4i v = {0, 0, 0, 0};
             if (PACKED) {
                 // the thread's four (tap, channel) columns never change; its pixels advance by MB per stage
-                if (m < m_end) {
+                if (PACKED3 && m < m_end) {
+                    const int iy0 = pk_oh[i] * a.stride - a.pad, ix0 = pk_ow[i] * a.stride - a.pad;
+                    const int8_t *base = a.X + (((ptrdiff_t)pk_b[i] * a.H + iy0) * a.W + ix0) * 3;
+                    const int8_t *xend = a.X + (size_t)(a.M / (a.OH * a.OW)) * a.H * a.W * 3;
+                    const int j0 = 3 * max(0, -ix0), j1 = 3 * min(a.S, a.W - ix0);   // bytes of a filter row inside the image
+#pragma unroll
+                    for (int d = 0; d < 4; d++) {
+                        if (pk_r[d] < 0) continue;                                   // past the last column: stays 0
+                        unsigned w = 0, got = 0;
+                        const int iy = iy0 + pk_r[d];
+                        if (iy >= 0 && iy < a.H) {
+                            const unsigned mk = wg_bytemask(j0 - pk_s[d], min(j1 - pk_s[d], pk_n0[d]));
+                            if (mk) w = wg_load_word(base + pk_off[d], mk, a.X, xend) & mk;
+                            got = mk;
+                        }
+                        if (pk_n1[d] > 0 && iy + 1 >= 0 && iy + 1 < a.H) {
+                            const unsigned mk = wg_bytemask(j0, min(j1, pk_n1[d]));
+                            if (mk) {
+                                const unsigned x = wg_load_word(base + (pk_r[d] + 1) * a.W * 3, mk, a.X, xend) & mk;
+                                w |= x << (8 * pk_n0[d]);
+                                got |= mk << (8 * pk_n0[d]);
+                            }
+                        }
+                        const unsigned all = wg_bytemask(0, pk_n0[d] + pk_n1[d]);     // columns that exist
+                        v[d] = (int)(w | ((unsigned)fill & all & ~got));              // taps outside the image: real zero
+                    }
+                } else if (m < m_end) {
                     const int iy0 = pk_oh[i] * a.stride - a.pad, ix0 = pk_ow[i] * a.stride - a.pad;
                     const int8_t *base = a.X + (((size_t)pk_b[i] * a.H + iy0) * a.W + ix0) * a.C;
 #pragma unroll
@@ -343,7 +410,7 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
     const int c0 = cp * 64, n0 = np * 64;
     const int s_begin = split * a.stages_per_block, s_end = min(a.nstages, s_begin + a.stages_per_block);
     const int zx = a.xq->zero_point;
-    const int fillw = (zx & 0xff) * 0x01010101;
+    const int fillw = (int)((unsigned)(zx & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     // a column sum is only ever multiplied by the other operand's zero point (the finalize kernel's
     // correction terms): with that zero point at 0 it is not formed at all
     const bool do_gsum = cp == 0 && cblk == 0 && th == 0 && zx != 0;
@@ -791,7 +858,8 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((ws_words + 255) / 256 > 1024 ? 1024 : (ws_words + 255) / 256)),
                        dim3(256), 0, stream, zero_from, ws_words);
     dim3 grid((unsigned)(xt * yt * splits));
-    if (packed)   hipLaunchKernelGGL((hq_wgrad_kernel<64, 256, true>), grid, dim3(HQ_THREADS), 0, stream, a);
+    if (a.C == 3) hipLaunchKernelGGL((hq_wgrad_kernel<64, 256, true, true>), grid, dim3(HQ_THREADS), 0, stream, a);
+    else if (packed) hipLaunchKernelGGL((hq_wgrad_kernel<64, 256, true>), grid, dim3(HQ_THREADS), 0, stream, a);
     else if (big) hipLaunchKernelGGL((hq_wgrad_kernel<128, 128, false>), grid, dim3(HQ_THREADS), 0, stream, a);
     else          hipLaunchKernelGGL((hq_wgrad_kernel<64, 64, false>), grid, dim3(HQ_THREADS), 0, stream, a);
 

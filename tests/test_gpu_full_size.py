@@ -84,7 +84,7 @@ def test_c4_full_size_block(H, hq):
 
 
 def test_c5_resnet18_stack_small_batch(H, hq):
-    """Every layer of the ResNet-18-shaped stack (7x7/2 stem on 4 input channels, 3x3 stages with
+    """Every layer of the ResNet-18-shaped stack (7x7/2 stem on 3-channel images, 3x3 stages with
     stride-2 downsampling and 1x1/2 shortcuts, FC 512->1000) at batch 4: dynamic init + one
     in-hindsight iteration of fwd and dgrad (no dgrad for the stem), wgrad once; whole tensors
     against the oracle."""
@@ -172,6 +172,45 @@ def test_c5_full_batch_sampled(H, hq, which):
         want, _, _ = oracle.requant(c, a_scale, ref.scale, ref.zero_point, ref.qlo, ref.qhi)
         assert np.array_equal(codes.reshape(nrow, -1)[rows], want)
         assert (int(s1["acc_min"]), int(s1["acc_max"]), int(s1["count"])) == (int(s0["acc_min"]), int(s0["acc_max"]), codes.size)
+
+
+C5_LAYERS = [l.name for l in wl.resnet18_layers(B=256)]
+
+
+@pytest.mark.parametrize("which", C5_LAYERS)
+def test_c5_full_batch_whole_tensors(H, hq, which):
+    """The ResNet-18-shaped step at batch 256, the size it is quoted on, one layer per case: forward and
+    input gradient (none for the stem) through the dynamic first iteration and one in-hindsight
+    iteration, and the weight gradient, every output element, statistic and clip count against the
+    oracle on the whole tensors.  The oracle's weight gradient sums up to 3.2 M products per element
+    in 64 bits and reports whether every sum fits 32 bits, which the 32-bit accumulators of the
+    kernels need (Sec. 3.2)."""
+    layers = wl.resnet18_layers(B=256)
+    idx = C5_LAYERS.index(which)
+    L = layers[idx]
+    X, W, dY = wl.layer_inputs(L, 5, 0, idx, image_input=(idx == 0))
+    Wdev, Xd, dYd = H.DevWeights(L, W), H.DevTensor(X), H.DevTensor(dY)
+    for op, A, Adev, sym in (("fwd", X, Xd, False), ("dgrad", dY, dYd, True)):
+        if op == "dgrad" and idx == 0:
+            continue
+        a_scale = oracle.acc_scale(A.scale, W.scale)
+        c = H.oracle_acc(L, op, A, W)                      # 64-bit sums, asserted to fit 32 bits
+        r, st, ref_r = hq.new_range(0.9, sym), hq.new_stats(), oracle.Range.new(0.9, sym)
+        for t in range(2):
+            want = oracle.in_hindsight_step(c, a_scale, ref_r)
+            codes, q = H.gpu_quantized_op(L, op, Adev, Wdev, r, st, "dynamic" if t == 0 else "fused")
+            got_st = H.read_stats(st)
+            hq.hq_range_update(r, st)
+            H.assert_stats_equal(got_st, want, a_scale)     # min, max, clip counts and count, all with ==
+            assert np.float32(q["scale"]) == want["scale"] and int(q["zero_point"]) == want["zero_point"]
+            assert np.array_equal(codes, want["codes"]), (L.name, op, t)
+            H.assert_range_close(H.read_range(r), ref_r)
+            del codes
+        del c
+    dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+    ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+    assert np.array_equal(dWa, ref), L.name
+    assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale)), L.name
 
 
 def test_real_tensor_quantizer_full_size(H, hq):

@@ -75,6 +75,7 @@ SMALL = [
     wl.conv("bandw_multi_img", 3, 10, 128, 192, 3),  # streamed-weights path: tiles of two whole images (last one short), ragged channel chunk
     wl.conv("bandw_rows", 2, 30, 192, 128, 3),       # ... tiles of rows, last tile of an image short; wgrad blocks 3 x 2
     wl.conv("first_layer", 2, 23, 4, 48, 7, stride=2),   # 4-channel first layer: direct kernel, ragged channel block, odd size
+    wl.conv("first_layer_c8", 2, 19, 8, 32, 3),      # 8-channel first layer: packed weight gradient, general forward
     wl.conv("c5x5_s3", 2, 17, 16, 32, 5, stride=3),  # stride 3: nine pixel classes in the input gradient
     wl.conv("band_early_tail", 128, 24, 64, 64, 3),  # bands of 288 pixels: the 32-pixel last tile is taken in the first half step
     wl.LayerShape("c2x1_s3", wl.CONV, 1, 2, 10, 4, 2, 1, 3, 0, 36),   # filter of width 1 and height 2 (division by 1 in the tap arithmetic)
@@ -105,6 +106,48 @@ def test_small_shapes_all_ops(H, hq, L):
         ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
         assert np.array_equal(dWa, ref)
         assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+
+
+# ---------------------------------------------------------------------------------------
+# 3-channel (RGB) first layers: forward (fused and dynamic) and weight gradient; 3-byte pixels
+# ---------------------------------------------------------------------------------------
+RGB = [
+    wl.conv("rgb_stem", 2, 37, 3, 64, 7, stride=2),                      # the ResNet stem's geometry on a small odd image
+    wl.conv("rgb_3x3", 3, 20, 3, 64, 3),                                 # VGG's first layer
+    wl.conv("rgb_3x3_n16", 1, 9, 3, 16, 3, stride=1, pad=0),             # one column group, no padding
+    wl.conv("rgb_5x5_s3", 2, 23, 3, 48, 5, stride=3, pad=1),             # ragged channel block
+    wl.LayerShape("rgb_7x10", wl.CONV, 2, 15, 31, 3, 7, 10, 2, 4, 32),   # widest filter row the kernel takes (30 bytes)
+    wl.LayerShape("rgb_w1", wl.CONV, 3, 12, 1, 3, 3, 1, 1, 0, 32),       # images one pixel wide
+    wl.LayerShape("rgb_1x1", wl.CONV, 1, 5, 7, 3, 1, 1, 1, 0, 16),       # a word holds one pixel and a byte of the next
+    wl.conv("rgb_one_pixel", 1, 1, 3, 16, 3),                            # 3 bytes of input in all: every word reaches past the tensor
+]
+
+
+@pytest.mark.parametrize("L", RGB, ids=[l.name for l in RGB])
+@pytest.mark.parametrize("g_asym", [False, True], ids=["gsym", "gasym"])
+def test_rgb_first_layer(H, hq, L, g_asym):
+    y_track = H.TensorTrack(0.9, False)
+    Wdev = None
+    for t in range(3):
+        g = np.random.default_rng([77, t])
+        X = wl.normal_image(g, wl.in_shape(L))                            # signed image, zero point inside the grid
+        W = wl.he_weight(g, L)
+        if g_asym:
+            dY = wl.to_asymmetric_codes(g.laplace(0, 1e-3, wl.out_shape(L)).astype(np.float32) + np.float32(4e-4))
+        else:
+            dY = wl.laplace_gradient(g, wl.out_shape(L), 1e-3)
+        if Wdev is None:
+            W0, Wdev = W, H.DevWeights(L, W)
+        Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+        y_track.step(L, "fwd", X, W0, Xd, Wdev)                           # t = 0 dynamic, then fused
+        dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+        ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+        assert np.array_equal(dWa, ref)
+        assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+    # the input gradient of a 3-channel layer is refused, not computed wrongly
+    with pytest.raises(hq.HqError) as e:
+        H.gpu_quantized_op(L, "dgrad", dYd, Wdev, hq.new_range(0.9, True), hq.new_stats(1), "fused")
+    assert e.value.code == hq.HQ_E_BADSHAPE
 
 
 def random_shapes(n, seed):

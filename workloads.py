@@ -212,11 +212,10 @@ def c4_inputs(t, B=128):
 
 
 def resnet18_layers(B=256, image=224):
-    """ResNet-18-shaped stack: stem, 4 stages of 3x3 convs with 1x1 stride-2 shortcuts, FC.
-    The stem input carries 4 channels (RGB plus one channel of real zeros) so that a
-    pixel is one aligned 32-bit word."""
+    """ResNet-18-shaped stack: stem on 3-channel images, 4 stages of 3x3 convs with 1x1 stride-2
+    shortcuts, FC."""
     s = image // 4                                            # after stem /2 and max-pool /2
-    layers = [conv("stem_7x7", B, image, 4, 64, 7, stride=2)]
+    layers = [conv("stem_7x7", B, image, 3, 64, 7, stride=2)]
     layers += [conv("s1_conv%d" % i, B, s, 64, 64, 3) for i in range(4)]
     cin = 64
     for stage, cout in ((2, 128), (3, 256), (4, 512)):
@@ -231,9 +230,8 @@ def resnet18_layers(B=256, image=224):
 
 def vgg16_layers(B=256, image=64, classes=200):
     """VGG16-shaped stack (13 3x3 convs in five blocks with 2x2 pooling between them, three
-    linear layers) on 64x64 images with 200 classes, the size of the Tiny ImageNet runs; the
-    first layer's input carries 4 channels like the ResNet stem's."""
-    layers, cin, s = [], 4, image
+    linear layers) on 64x64 3-channel images with 200 classes, the size of the Tiny ImageNet runs."""
+    layers, cin, s = [], 3, image
     for block, (cout, n) in enumerate(((64, 2), (128, 2), (256, 3), (512, 3), (512, 3))):
         for i in range(n):
             layers.append(conv("b%d_conv%d" % (block + 1, i), B, s, cin, cout, 3))
@@ -249,14 +247,10 @@ def layer_inputs(L, config, t, index, image_input=False, grad_b=1e-3):
     """Independent synthetic operands for one layer of a stack."""
     g = rng(config, t, 100 * index)
     if image_input:
-        x = g.standard_normal(in_shape(L), dtype=np.float32)
-        x[..., 3:] = 0
-        X = to_asymmetric_codes(x)
+        X = normal_image(g, in_shape(L))
     else:
         X = relu_activation(g, in_shape(L))
     W = he_weight(rng(config, 0, 100 * index + 1), L)
-    if image_input:
-        W.codes[..., 3:] = 0
     dY = laplace_gradient(rng(config, t, 100 * index + 2), out_shape(L), grad_b)
     return X, W, dY
 
