@@ -327,6 +327,7 @@ int hq_gemm_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, co
     if (!X || !xq || !dY || !gq || !dW) return HQ_E_BADARG;
     if (misaligned(X, 16) || misaligned(dY, 16) || misaligned(dW, 16) || misaligned(dW_acc, 16) ||
         misaligned(xq, 4) || misaligned(gq, 4)) return HQ_E_BADARG;
+    if (p->C == 3 && p->S * 3 > 32) return HQ_E_BADSHAPE;     // 3-channel inputs: a filter row fits 32 bytes
     const size_t need = hq_wgrad_workspace_bytes(p);
     if (need && (!ws || ws_bytes < need || misaligned(ws, 16))) return HQ_E_WORKSPACE;
     if (p->kind == HQ_DEPTHWISE)
@@ -356,6 +357,7 @@ int hq_gemm_wgrad_update(const hq_problem *p, const int8_t *X, const hq_qparams 
     if (!X || !xq || !dY || !gq || !dW || !r || !st || n < 1 || n > 4096) return HQ_E_BADARG;
     if (misaligned(X, 16) || misaligned(dY, 16) || misaligned(dW, 16) || misaligned(dW_acc, 16) ||
         misaligned(xq, 4) || misaligned(gq, 4) || misaligned(r, 4) || misaligned(st, 128)) return HQ_E_BADARG;
+    if (p->C == 3 && p->S * 3 > 32) return HQ_E_BADSHAPE;
     const size_t need = hq_wgrad_workspace_bytes(p);
     if (need && (!ws || ws_bytes < need || misaligned(ws, 16))) return HQ_E_WORKSPACE;
     const HqRideAlong ra = {r, st, n, 0};

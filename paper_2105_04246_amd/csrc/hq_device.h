@@ -16,6 +16,52 @@ __host__ __device__ inline unsigned hq_magic32(unsigned d) { return (unsigned)((
 __device__ inline unsigned hq_magic_div(unsigned x, unsigned magic) { return magic ? __umulhi(x, magic) : x; }
 
 // ---------------------------------------------------------------------------------------
+// 3-byte pixels (RGB inputs): a lane's 4-byte word of the reduction starts at any byte address and
+// can hold bytes of two taps.  Words are loaded unaligned and the unwanted bytes replaced under a
+// byte mask.
+// ---------------------------------------------------------------------------------------
+
+// Bytes e of a 32-bit word with lo <= e < hi (little endian), as a mask of whole bytes.
+__device__ inline unsigned hq_bytemask(int lo, int hi)
+{
+    lo = max(lo, 0); hi = min(hi, 4);
+    if (hi <= lo) return 0u;
+    const unsigned upto_hi = hi == 4 ? 0xffffffffu : (1u << (8 * hi)) - 1u;
+    return upto_hi & ~((1u << (8 * lo)) - 1u);
+}
+
+// 16 consecutive bytes starting at p (any alignment) of a tensor that occupies [begin, end): aligned loads
+// of the five 32-bit words that hold them (one 16-byte and one 4-byte load where all five lie inside the
+// tensor, guarded single words at its first and last bytes), then a byte-wise funnel shift.  Unaligned
+// word loads are served far more slowly.  Bytes outside the tensor arrive as anything: the caller masks them
+// (they belong to taps outside the image).  An aligned word that holds the tensor's last byte is read
+// whole, i.e. up to the next multiple of 4 of `end`.
+__device__ inline v4i hq_load16_any(const int8_t *p, const int8_t *begin, const int8_t *end)
+{
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(p);
+    const int8_t *a = reinterpret_cast<const int8_t *>(addr & ~(uintptr_t)3);
+    const unsigned sh = (unsigned)(addr & 3);
+    const int8_t *end4 = reinterpret_cast<const int8_t *>((reinterpret_cast<uintptr_t>(end) + 3) & ~(uintptr_t)3);
+    int w[5];
+    if (a >= begin && a + 20 <= end4) {
+        v4i x;
+        __builtin_memcpy(&x, __builtin_assume_aligned(a, 4), 16);
+        w[0] = x[0]; w[1] = x[1]; w[2] = x[2]; w[3] = x[3];
+        w[4] = *reinterpret_cast<const int *>(a + 16);
+    } else {
+#pragma unroll
+        for (int d = 0; d < 5; d++) {
+            const int8_t *q = a + 4 * d;
+            w[d] = (q >= begin && q < end4) ? *reinterpret_cast<const int *>(q) : 0;
+        }
+    }
+    v4i v;
+#pragma unroll
+    for (int d = 0; d < 4; d++) v[d] = (int)__builtin_amdgcn_alignbyte((unsigned)w[d + 1], (unsigned)w[d], sh);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------
 // Quantizer arithmetic.  Each fp32 operation rounds once (no contraction), so that the
 // result is a function of the operands alone.
 // ---------------------------------------------------------------------------------------

@@ -13,8 +13,8 @@
 // vector-ALU work and by the HBM write of the codes.
 // With 3 channels a pixel is 3 bytes, so a lane's 4-byte words start at any byte address and a word
 // can hold bytes of two taps: words are loaded unaligned and the bytes whose tap lies outside the
-// image (or past the filter row) are replaced under a per-word byte mask; the few words that would
-// reach past either end of the tensor are assembled from single bytes instead.
+// image (or past the filter row) are replaced under a per-word byte mask.  The 16 bytes themselves come
+// from aligned loads of the words that hold them and a byte-wise funnel shift.
 #include "hq_device.h"
 #include "hq_internal.h"
 #include <type_traits>
@@ -39,31 +39,6 @@ struct DirectArgs {
 };
 
 __device__ inline int dr_sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
-
-// Bytes e of a 32-bit word with lo <= e < hi (little endian), as a mask of whole bytes.
-__device__ inline unsigned dr_bytemask(int lo, int hi)
-{
-    lo = max(lo, 0); hi = min(hi, 4);
-    if (hi <= lo) return 0u;
-    const unsigned upto_hi = hi == 4 ? 0xffffffffu : (1u << (8 * hi)) - 1u;
-    return upto_hi & ~((1u << (8 * lo)) - 1u);
-}
-
-// The 4 bytes at p (any alignment), of which only those under `mask` are wanted: one unaligned load when
-// the word lies inside [begin, end), single guarded bytes otherwise (first / last bytes of a tensor).
-__device__ inline unsigned dr_load_word(const int8_t *p, unsigned mask, const int8_t *begin, const int8_t *end)
-{
-    if (p >= begin && p + 4 <= end) {
-        unsigned v;
-        __builtin_memcpy(&v, p, 4);
-        return v;
-    }
-    unsigned v = 0;
-#pragma unroll
-    for (int e = 0; e < 4; e++)
-        if ((mask >> (8 * e)) & 1u) v |= (unsigned)(unsigned char)p[e] << (8 * e);
-    return v;
-}
 
 // NT: 32-channel blocks of the output (N <= 32 * NT).  CH: input channels, 4 (a tap is one aligned word) or 3.
 template <int NT, bool FUSED, int CH>
@@ -94,8 +69,9 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
                     if (CH == 4) {
                         if (16 * half + 4 * d < rowbytes) v[d] = *reinterpret_cast<const int *>(w + 4 * d);
                     } else {
-                        const unsigned mk = dr_bytemask(0, rowbytes - (16 * half + 4 * d));     // bytes of this filter row
-                        if (mk) v[d] = (int)(dr_load_word(w + 4 * d, mk, a.Bw, a.Bw + (size_t)a.N * a.R * rowbytes) & mk);
+                        const unsigned mk = hq_bytemask(0, rowbytes - (16 * half + 4 * d));     // bytes of this filter row
+                        const v4i x = hq_load16_any(w, a.Bw, a.Bw + (size_t)a.N * a.R * rowbytes);
+                        v[d] = (int)((unsigned)x[d] & mk);
                     }
                 }
             }
@@ -149,21 +125,19 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
                 const int k0 = CH * max(0, -ixb), k1 = CH * min(a.S, a.W - ixb);
                 unsigned mk[4];
 #pragma unroll
-                for (int d = 0; d < 4; d++) mk[d] = ok ? dr_bytemask(k0 - (16 * half + 4 * d), k1 - (16 * half + 4 * d)) : 0u;
+                for (int d = 0; d < 4; d++) mk[d] = ok ? hq_bytemask(k0 - (16 * half + 4 * d), k1 - (16 * half + 4 * d)) : 0u;
                 const int8_t *p0 = a.A + ((ptrdiff_t)b * a.H * a.W + ixb) * CH + 16 * half;
                 const int8_t *aend = a.A + (size_t)a.Bn * a.H * a.W * CH;
 #pragma unroll
                 for (int r = 0; r < DR_MAXR; r++) {
-                    v4i v;
                     const int iy = iy0 + r;
-                    const bool rok = r < a.R && iy >= 0 && iy < a.H;
-                    const int8_t *p = p0 + (ptrdiff_t)iy * a.W * CH;
+                    const bool rok = ok && r < a.R && iy >= 0 && iy < a.H;
+                    const v4i x = hq_load16_any(rok ? p0 + (ptrdiff_t)iy * a.W * CH : a.A, a.A, aend);
+                    v4i v;
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
                         const unsigned m = rok ? mk[d] : 0u;
-                        unsigned x = 0;
-                        if (m) x = dr_load_word(p + 4 * d, m, a.A, aend);
-                        v[d] = (int)((x & m) | ((unsigned)fill & ~m));
+                        v[d] = (int)(((unsigned)x[d] & m) | ((unsigned)fill & ~m));
                     }
                     af[r][i] = v;
                 }

@@ -64,38 +64,14 @@ template <int P> __device__ inline v4i read_frag_tr(const int8_t *tile, int lane
     return f;
 }
 
-// Bytes e of a 32-bit word with lo <= e < hi (little endian), as a mask of whole bytes.
-__device__ inline unsigned wg_bytemask(int lo, int hi)
-{
-    lo = max(lo, 0); hi = min(hi, 4);
-    if (hi <= lo) return 0u;
-    const unsigned upto_hi = hi == 4 ? 0xffffffffu : (1u << (8 * hi)) - 1u;
-    return upto_hi & ~((1u << (8 * lo)) - 1u);
-}
-
-// The 4 bytes at p (any alignment), of which only those under `mask` are wanted: one unaligned load when
-// the word lies inside [begin, end), single guarded bytes otherwise (first / last bytes of a tensor).
-__device__ inline unsigned wg_load_word(const int8_t *p, unsigned mask, const int8_t *begin, const int8_t *end)
-{
-    if (p >= begin && p + 4 <= end) {
-        unsigned v;
-        __builtin_memcpy(&v, p, 4);
-        return v;
-    }
-    unsigned v = 0;
-#pragma unroll
-    for (int e = 0; e < 4; e++)
-        if ((mask >> (8 * e)) & 1u) v |= (unsigned)(unsigned char)p[e] << (8 * e);
-    return v;
-}
-
 // PACKED: layers with fewer than 16 input channels (a network's first layer).  The tile's columns
 // then run over (tap, channel) pairs as they lie in a row of G_W, so a 16-byte chunk of the staged
 // tile holds 16 / C taps (one 4-byte load each) instead of one tap padded with zeros.
-// PACKED3: the same for 3-channel inputs (RGB images).  The S * 3 bytes of a filter row are contiguous in
-// the input, but a 4-byte word of columns starts at any byte and can run over into the next filter row:
-// it is put together from (at most) two unaligned loads under byte masks that drop the taps outside
-// the image.
+// PACKED3: 3-channel inputs (RGB images).  The S * 3 <= 32 bytes of a filter row are contiguous in the
+// input; every filter row gets 32 tile columns of its own (column = 32 * r + 3 * s + channel, the columns
+// past S * 3 stay zero), so a thread's 16-byte chunk is 16 consecutive bytes of memory at any byte
+// address: aligned loads plus a byte-wise funnel shift, then byte masks that replace the taps outside the
+// image with the zero-point code.
 template <int TN, int TK, bool PACKED, bool PACKED3 = false>
 __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 {
@@ -143,19 +119,16 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     const bool do_xsum = by == 0 && wn == 0 && a.gq->zero_point != 0;        // column sums of Xg: first tile row
 
     int pk_r[4], pk_s[4], pk_off[4], pk_ow[XLD], pk_oh[XLD], pk_b[XLD];
-    int pk_n0[4], pk_n1[4];                      // PACKED3: bytes of word d in filter row pk_r[d] / in the row after it
     if (PACKED) {
 #pragma unroll
         for (int d = 0; d < 4; d++) {
             const int kc = c0 + (tid % XCH) * 16 + 4 * d;
             if (PACKED3) {
-                // word d = columns kc .. kc + 3; column k is byte k % rowlen of filter row k / rowlen
-                const int rowlen = a.S * 3, nvalid = min(4, kcols - kc);
-                pk_r[d] = kc < kcols ? kc / rowlen : -1;
-                pk_s[d] = kc - (kc / rowlen) * rowlen;                 // byte inside the filter row
-                pk_n0[d] = max(0, min(nvalid, rowlen - pk_s[d]));
-                pk_n1[d] = max(0, nvalid - pk_n0[d]);
-                pk_off[d] = pk_r[d] * a.W * 3 + pk_s[d];
+                // word d = bytes 4 * d .. 4 * d + 3 of this thread's 16 bytes of filter row pk_r[0]
+                const int q = (c0 >> 4) + (tid % XCH);                 // 16-byte chunk: filter row q / 2, half q % 2
+                pk_r[d] = (q >> 1) < a.R ? (q >> 1) : -1;
+                pk_s[d] = 16 * (q & 1) + 4 * d;                        // first byte of the word inside the filter row
+                pk_off[d] = pk_r[d] * a.W * 3 + 16 * (q & 1);
                 continue;
             }
             const int t = kc / a.C, cc = kc - t * a.C;
@@ -188,29 +161,17 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
                 // the thread's four (tap, channel) columns never change; its pixels advance by MB per stage
                 if (PACKED3 && m < m_end) {
                     const int iy0 = pk_oh[i] * a.stride - a.pad, ix0 = pk_ow[i] * a.stride - a.pad;
+                    const int iy = iy0 + pk_r[0];
+                    const bool rok = pk_r[0] >= 0 && iy >= 0 && iy < a.H;
                     const int8_t *base = a.X + (((ptrdiff_t)pk_b[i] * a.H + iy0) * a.W + ix0) * 3;
                     const int8_t *xend = a.X + (size_t)(a.M / (a.OH * a.OW)) * a.H * a.W * 3;
                     const int j0 = 3 * max(0, -ix0), j1 = 3 * min(a.S, a.W - ix0);   // bytes of a filter row inside the image
+                    const v4i x = hq_load16_any(rok ? base + pk_off[0] : a.X, a.X, xend);
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
-                        if (pk_r[d] < 0) continue;                                   // past the last column: stays 0
-                        unsigned w = 0, got = 0;
-                        const int iy = iy0 + pk_r[d];
-                        if (iy >= 0 && iy < a.H) {
-                            const unsigned mk = wg_bytemask(j0 - pk_s[d], min(j1 - pk_s[d], pk_n0[d]));
-                            if (mk) w = wg_load_word(base + pk_off[d], mk, a.X, xend) & mk;
-                            got = mk;
-                        }
-                        if (pk_n1[d] > 0 && iy + 1 >= 0 && iy + 1 < a.H) {
-                            const unsigned mk = wg_bytemask(j0, min(j1, pk_n1[d]));
-                            if (mk) {
-                                const unsigned x = wg_load_word(base + (pk_r[d] + 1) * a.W * 3, mk, a.X, xend) & mk;
-                                w |= x << (8 * pk_n0[d]);
-                                got |= mk << (8 * pk_n0[d]);
-                            }
-                        }
-                        const unsigned all = wg_bytemask(0, pk_n0[d] + pk_n1[d]);     // columns that exist
-                        v[d] = (int)(w | ((unsigned)fill & all & ~got));              // taps outside the image: real zero
+                        const unsigned mk = rok ? hq_bytemask(j0 - pk_s[d], j1 - pk_s[d]) : 0u;
+                        const unsigned all = pk_r[0] >= 0 ? hq_bytemask(0, a.S * 3 - pk_s[d]) : 0u;   // columns that exist
+                        v[d] = (int)(((unsigned)x[d] & mk) | ((unsigned)fill & all & ~mk));             // outside the image: real zero
                     }
                 } else if (m < m_end) {
                     const int iy0 = pk_oh[i] * a.stride - a.pad, ix0 = pk_ow[i] * a.stride - a.pad;
@@ -315,7 +276,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     for (int i = 0; i < NT; i++)
 #pragma unroll
         for (int j = 0; j < KT; j++) {
-            const int c = c0 + wk * WTK + j * 32 + (lane & 31);
+            int c = c0 + wk * WTK + j * 32 + (lane & 31);
+            if (PACKED3) c = (c >> 5) < a.R && (c & 31) < a.S * 3 ? (c >> 5) * a.S * 3 + (c & 31) : kcols;   // tile column -> weight column
             if (c >= (PACKED ? kcols : a.C)) continue;
 #pragma unroll
             for (int r = 0; r < 16; r++) {
@@ -338,7 +300,8 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 #pragma unroll
         for (int j = 0; j < KT; j++) {
             int s = xs[j] + __shfl_xor(xs[j], 32);
-            const int c = c0 + wk * WTK + j * 32 + (lane & 31);
+            int c = c0 + wk * WTK + j * 32 + (lane & 31);
+            if (PACKED3) c = (c >> 5) < a.R && (c & 31) < a.S * 3 ? (c >> 5) * a.S * 3 + (c & 31) : kcols;
             if (lane < 32 && c < (PACKED ? kcols : a.C) && s != 0) atomicAdd(a.xsum + (size_t)tap * a.C + c, s);
         }
     }
@@ -838,7 +801,9 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     const bool big = a.N > 64 && a.C > 64, packed = a.C < 16;
     const int TN = big ? 128 : 64, TK = packed ? 256 : big ? 128 : 64;
     a.ctiles = (a.C + TK - 1) / TK;
-    const int xt = packed ? (int)((K + TK - 1) / TK) : p->R * p->S * a.ctiles, yt = (a.N + TN - 1) / TN;
+    // (3-channel inputs: 32 tile columns per filter row)
+    const int xt = a.C == 3 ? (p->R * 32 + TK - 1) / TK : packed ? (int)((K + TK - 1) / TK) : p->R * p->S * a.ctiles;
+    const int yt = (a.N + TN - 1) / TN;
     const int stages_total = (a.M + MB - 1) / MB;
     // Workgroups to aim at.  Small tiles need many resident workgroups to hide their stage latency;
     // 128x128 tiles carry 64 KB of atomics each, and those queue on the same lines when every split
