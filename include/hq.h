@@ -208,6 +208,32 @@ int hq_gemm_wgrad_update(const hq_problem *p /* host */,
  * run it on the stream that produced the tensor, any time after the producing kernel.        */
 int hq_range_update(hq_range *r, hq_stats *st, void *stream);
 
+/* State of the saturation-driven estimator of one quantizer (Sec. 4 names the saturation ratio, the
+ * share of values outside the quantization grid, as the other statistic that is cheap to take at
+ * the accumulator): the band the ratio may lie in, the ratio to aim at when the range is moved, how
+ * many iterations in a row the ratio must lie outside the band before that happens (tau), and the
+ * running count of such iterations (streak, start at 0).                                      */
+typedef struct {
+    float   alpha_min, alpha_max, alpha_target;
+    int32_t tau, streak;
+} hq_saturation;
+
+/* Saturation-driven range update for n quantizers (arrays r[n], st[n], sat[n]), one launch, to be
+ * called where hq_range_update would be.  The paper gives no equation for this variant; the rule:
+ *   alpha = (clip_lo + clip_hi) / count of the tensor just quantized (fp32)
+ *   alpha_min <= alpha <= alpha_max: the range stays, streak = 0
+ *   otherwise streak += 1, and once streak > tau the range is rescaled about zero,
+ *     (qmin, qmax) *= ln(alpha_target) / ln(clamp(alpha, 1 / (2 count), 1/2)),   streak = 0:
+ *   for a zero-mean Laplace tensor with scale b a share exp(-q / b) lies beyond +-q, so this is the
+ *   quantile b ln(1 / alpha_target) with b taken from the observed ratio (the inverse CDF of the
+ *   Laplace distribution; no pass over the data).  ln is evaluated by a fixed sequence of fp32
+ *   operations (exponent plus an odd polynomial in (m - 1) / (m + 1)), each rounded once.
+ * A range that is not initialized takes q^0 from the minimum and maximum in st, as
+ * hq_range_update does (Sec. 4.1).  r->qp is re-derived, st is folded first and emptied afterwards;
+ * with st->count == 0 nothing changes.  The statistics must come from GEMM outputs
+ * (fp32_keys == 0).                                                                           */
+int hq_range_update_saturation(hq_range *r, hq_stats *st, hq_saturation *sat, int32_t n, void *stream);
+
 /* The same update for n quantizers in one launch: r[i] is updated from st[i], i < n (arrays of
  * records).  A tensor's range is read next by its own layer's launch of the following iteration,
  * so a training step can keep the range states of all its tensors in one array and update them

@@ -67,6 +67,16 @@ class Range(C.Structure):
         return Range(0.0, 0.0, eta, -top - 1, top, 0, 0, 1.0, 0)
 
 
+class Saturation(C.Structure):
+    """State of the saturation-driven estimator of one quantizer (band, target, patience, streak)."""
+    _fields_ = [("alpha_min", C.c_float), ("alpha_max", C.c_float), ("alpha_target", C.c_float),
+                ("tau", C.c_int32), ("streak", C.c_int32)]
+
+    @staticmethod
+    def new(alpha_min=1e-5, alpha_max=1e-3, alpha_target=1e-4, tau=2):
+        return Saturation(alpha_min, alpha_max, alpha_target, tau, 0)
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -95,6 +105,10 @@ def lib():
         L.hqo_sr_bits.argtypes = [C.c_uint64, C.c_uint64]
         L.hqo_sr_bits.restype = C.c_uint32
         L.hqo_range_update.argtypes = [C.POINTER(Range), C.c_int32, C.c_int32, C.c_float]
+        L.hqo_ln_fixed.argtypes = [C.c_float]
+        L.hqo_ln_fixed.restype = C.c_float
+        L.hqo_range_update_saturation.argtypes = [C.POINTER(Range), C.POINTER(Saturation), C.c_uint64, C.c_uint64,
+                                                  C.c_uint64, C.c_int32, C.c_int32, C.c_float]
         L.hqo_wgrad_scale.argtypes = [i32p, C.c_int64, C.c_float, C.c_float, f32p]
         L.hqo_quantize_weights.argtypes = [f32p, C.c_int64, i8p, f32p]
         L.hqo_range_update_real.argtypes = [C.POINTER(Range), C.c_float, C.c_float]
@@ -215,6 +229,33 @@ def range_update(r, acc_min, acc_max, acc_scale):
     """eq. (2)-(3) in place on ``r``; the first call sets q^0."""
     lib().hqo_range_update(C.byref(r), int(acc_min), int(acc_max), float(acc_scale))
     return r
+
+
+def ln_fixed(x):
+    """The fixed-sequence fp32 logarithm the saturation-driven update uses."""
+    return np.float32(lib().hqo_ln_fixed(float(np.float32(x))))
+
+
+def range_update_saturation(r, sat, out, acc_scale):
+    """Saturation-driven update in place on ``r`` / ``sat`` from the statistics ``out`` of the tensor
+    just quantized (a dict as returned by quantize_static / quantize_dynamic)."""
+    lib().hqo_range_update_saturation(C.byref(r), C.byref(sat), int(out["clip_lo"]), int(out["clip_hi"]),
+                                      int(out["count"]), int(out["acc_min"]), int(out["acc_max"]), float(acc_scale))
+    return r
+
+
+def saturation_step(c, a_scale, r, sat, seed=None):
+    """One iteration under the saturation-driven estimator: the first batch is quantized dynamically
+    and sets q^0 (Sec. 4.1); later ones statically with the range in ``r``.  In both cases the clip
+    counts of this batch then decide whether the range moves (the first batch clips nothing, so it
+    counts as one iteration below the band), the same order of steps as in_hindsight_step."""
+    if not r.initialized:
+        out = quantize_dynamic(c, a_scale, r.symmetric, r.qlo, r.qhi)
+        range_update(r, out["acc_min"], out["acc_max"], a_scale)      # sets q^0
+    else:
+        out = quantize_static(c, a_scale, r, seed)
+    range_update_saturation(r, sat, out, a_scale)
+    return out
 
 
 def range_update_real(r, gmin, gmax):

@@ -359,6 +359,82 @@ void hqo_range_update(hqo_range *r, int32_t acc_min, int32_t acc_max, float acc_
     hqo_range_update_real(r, acc_scale * (float)acc_min, acc_scale * (float)acc_max);
 }
 
+/* ------------------------------------------------------------------------- */
+/* Saturation-driven range update (Sec. 4: the saturation ratio as the statistic).            */
+/* ------------------------------------------------------------------------- */
+
+/* Natural logarithm of a positive normal fp32 number, evaluated with a fixed sequence of fp32
+ * operations (each rounded once) so that every implementation of this sequence returns the same
+ * bits: x = m * 2^e with m in [sqrt(1/2), sqrt(2)), s = (m - 1) / (m + 1),
+ * ln x = e * ln 2 + 2 s (1 + s^2/3 + s^4/5 + s^6/7).  Absolute error below 1e-6.               */
+float hqo_ln_fixed(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, 4);
+    int e = (int)((bits >> 23) & 0xff) - 127;
+    uint32_t mb = (bits & 0x007fffffu) | 0x3f800000u;          /* m in [1, 2) */
+    float m;
+    memcpy(&m, &mb, 4);
+    if (m > 1.41421354f) { m = m * 0.5f; e += 1; }
+    float t = m - 1.0f;
+    float d = m + 1.0f;
+    float sq = t / d;
+    float s2 = sq * sq;
+    float p = s2 * (1.0f / 7.0f);
+    p = p + 0.2f;
+    p = p * s2;
+    p = p + (1.0f / 3.0f);
+    p = p * s2;
+    p = p + 1.0f;
+    float lm = 2.0f * sq;
+    lm = lm * p;
+    float le = (float)e * 0.693147182f;
+    return le + lm;
+}
+
+/* State of the saturation-driven estimator for one quantizer: the acceptable band of the
+ * saturation ratio, the ratio to aim at when the range is moved, the number of consecutive
+ * iterations the ratio must lie outside the band before that happens, and the running count
+ * of such iterations.                                                                         */
+typedef struct { float alpha_min, alpha_max, alpha_target; int32_t tau, streak; } hqo_saturation;
+
+/* One iteration of the saturation-driven update (the variant Sec. 4 names next to min-max; the
+ * rule below is this build's reading, the paper gives no equation for it):
+ *   alpha = (clip_lo + clip_hi) / count                         the saturation ratio of the tensor just quantized
+ *   alpha inside [alpha_min, alpha_max]: the range stays, the streak ends
+ *   otherwise the streak grows; once it exceeds tau, the range is rescaled about zero by
+ *     rho = ln(alpha_target) / ln(alpha^),  alpha^ = clamp(alpha, 1 / (2 count), 1/2),
+ *   which for a zero-mean Laplace tensor (tail mass exp(-q / b) beyond q) is the quantile q' =
+ *   b ln(1 / alpha_target) with b estimated from the observed ratio: the inverse CDF of the
+ *   Laplace distribution, no pass over the data.  The first call (range not initialised) sets
+ *   q^0 from the minimum and maximum of the first batch, as Sec. 4.1 does.                     */
+void hqo_range_update_saturation(hqo_range *r, hqo_saturation *sat, uint64_t clip_lo, uint64_t clip_hi,
+                                 uint64_t count, int32_t acc_min, int32_t acc_max, float acc_scale)
+{
+    if (count == 0) return;
+    if (!r->initialized) {
+        r->qmin = acc_scale * (float)acc_min; r->qmax = acc_scale * (float)acc_max; r->initialized = 1;
+        sat->streak = 0;
+    } else {
+        float alpha = (float)(clip_lo + clip_hi) / (float)count;
+        if (alpha >= sat->alpha_min && alpha <= sat->alpha_max) {
+            sat->streak = 0;
+        } else {
+            sat->streak += 1;
+            if (sat->streak > sat->tau) {
+                float floor_ = 0.5f / (float)count;
+                float ah = alpha < floor_ ? floor_ : alpha;
+                if (ah > 0.5f) ah = 0.5f;
+                float rho = hqo_ln_fixed(sat->alpha_target) / hqo_ln_fixed(ah);
+                r->qmin = rho * r->qmin;
+                r->qmax = rho * r->qmax;
+                sat->streak = 0;
+            }
+        }
+    }
+    hqo_qparams(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi, &r->scale, &r->zero_point);
+}
+
 /* Static quantization (Sec. 3.2) of a real-valued tensor with a given quantizer (s, z): the
  * arithmetic of hqo_requant with the real value in the accumulator's place and unit 1, so
  * m = 1 / s.  Also returns the tensor's minimum and maximum, which eq. (2)-(3) consume.  */

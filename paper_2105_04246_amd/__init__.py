@@ -28,6 +28,7 @@ STATS_PART = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("clip_lo", "<u8"
 STATS = np.dtype([("acc_min", "<i4"), ("acc_max", "<i4"), ("acc_scale", "<f4"), ("fp32_keys", "<u4"),
                   ("clip_lo", "<u8"), ("clip_hi", "<u8"), ("count", "<u8"), ("pad", "u1", (88,)),
                   ("part", STATS_PART, (STATS_PARTS,))])
+SATURATION = np.dtype([("alpha_min", "<f4"), ("alpha_max", "<f4"), ("alpha_target", "<f4"), ("tau", "<i4"), ("streak", "<i4")])
 assert QPARAMS.itemsize == 8 and RANGE.itemsize == 36 and STATS_PART.itemsize == 128
 assert STATS.itemsize == 128 * (1 + STATS_PARTS)
 
@@ -48,7 +49,7 @@ class HqError(RuntimeError):
 
 _lib = None
 EXPORTS = ("hq_workspace_bytes", "hq_gemm_fwd", "hq_gemm_dgrad", "hq_gemm_dgrad_sr", "hq_gemm_wgrad", "hq_gemm_wgrad_static", "hq_gemm_wgrad_update", "hq_range_update",
-           "hq_range_update_batch",
+           "hq_range_update_batch", "hq_range_update_saturation",
            "hq_gemm_dynamic", "hq_gemm_dynamic_sr", "hq_stats_reset", "hq_stats_fold", "hq_weight_prepare", "hq_weight_quantize", "hq_tensor_quantize", "hq_tensor_quantize_sr", "hq_tensor_quantize_dynamic",
            "hq_probe_mfma_rate",
            "hq_error_string")
@@ -75,6 +76,7 @@ def lib():
         L.hq_gemm_wgrad_update.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp, C.c_int32, vp]
         L.hq_range_update.argtypes = [vp, vp, vp]
         L.hq_range_update_batch.argtypes = [vp, vp, C.c_int32, vp]
+        L.hq_range_update_saturation.argtypes = [vp, vp, vp, C.c_int32, vp]
         L.hq_gemm_dynamic.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 10 + [C.c_size_t, vp]
         L.hq_gemm_dynamic_sr.argtypes = [C.c_int32, C.c_int32, PP] + [vp] * 6 + [C.c_uint64] + [vp] * 4 + [C.c_size_t, vp]
         L.hq_stats_reset.argtypes = [vp, C.c_int32, vp]
@@ -153,6 +155,10 @@ def hq_range_update(r, st, stream=None):
 
 def hq_range_update_batch(r, st, n, stream=None):
     _check("hq_range_update_batch", lib().hq_range_update_batch(_ptr(r), _ptr(st), n, _stream(stream)))
+
+
+def hq_range_update_saturation(r, st, sat, n=1, stream=None):
+    _check("hq_range_update_saturation", lib().hq_range_update_saturation(_ptr(r), _ptr(st), _ptr(sat), n, _stream(stream)))
 
 
 def hq_gemm_dynamic(op, mode, p, A, aq, Bw, bq, bsum, r, out, outq, st, ws, ws_bytes, stream=None):
@@ -241,6 +247,13 @@ def new_range(eta=0.9, symmetric=False, device="cuda", bits=8):
     rec["eta"], rec["symmetric"] = eta, int(symmetric)
     rec["qlo"], rec["qhi"] = (-top, top) if symmetric else (-top - 1, top)
     rec["scale"] = 1.0
+    return to_device(rec, device)
+
+
+def new_saturation(alpha_min=1e-5, alpha_max=1e-3, alpha_target=1e-4, tau=2, n=1, device="cuda"):
+    """n saturation-estimator states (hq_saturation) with the same settings, streak 0."""
+    rec = np.zeros(n, SATURATION)
+    rec["alpha_min"], rec["alpha_max"], rec["alpha_target"], rec["tau"] = alpha_min, alpha_max, alpha_target, tau
     return to_device(rec, device)
 
 

@@ -53,6 +53,27 @@ __global__ __launch_bounds__(64) void range_update_kernel(hq_range *r, hq_stats 
     hq_range_update_wave(r + blockIdx.x, st + blockIdx.x);
 }
 
+// Saturation-driven update of one quantizer per workgroup (one wavefront): folds the statistics, moves the
+// range by the rule stated with hq_range_update_saturation, empties the record.
+__global__ __launch_bounds__(64) void range_update_saturation_kernel(hq_range *r, hq_stats *st, hq_saturation *sat)
+{
+    r += blockIdx.x; st += blockIdx.x; sat += blockIdx.x;
+    hq_range rr = *r;
+    hq_saturation ss = *sat;
+    const float acc_scale = st->acc_scale;
+    const unsigned long long count = st->count;
+    const HqStatsFolded f = hq_stats_fold_wave(st);
+    if (threadIdx.x == 0) {
+        if (count != 0) {
+            hq_saturation_update(&rr, &ss, f.clip_lo + f.clip_hi, count,
+                                 __fmul_rn(acc_scale, (float)f.acc_min), __fmul_rn(acc_scale, (float)f.acc_max));
+            *r = rr; *sat = ss;
+        }
+        st->acc_min = INT_MAX; st->acc_max = INT_MIN; st->acc_scale = 0.0f; st->fp32_keys = 0;
+        st->clip_lo = 0; st->clip_hi = 0; st->count = 0;
+    }
+}
+
 __global__ __launch_bounds__(64) void stats_reset_kernel(hq_stats *st) { stats_clear_wave(st + blockIdx.x); }
 
 __global__ __launch_bounds__(64) void stats_fold_kernel(hq_stats *st) { hq_stats_fold_wave(st + blockIdx.x); }
@@ -377,6 +398,13 @@ int hq_range_update_batch(hq_range *r, hq_stats *st, int32_t n, void *stream)
 {
     if (!r || !st || n <= 0 || misaligned(r, 4) || misaligned(st, 128)) return HQ_E_BADARG;
     hipLaunchKernelGGL(range_update_kernel, dim3(n), dim3(64), 0, as_stream(stream), r, st);
+    return launch_status();
+}
+
+int hq_range_update_saturation(hq_range *r, hq_stats *st, hq_saturation *sat, int32_t n, void *stream)
+{
+    if (!r || !st || !sat || n <= 0 || misaligned(r, 4) || misaligned(st, 128) || misaligned(sat, 4)) return HQ_E_BADARG;
+    hipLaunchKernelGGL(range_update_saturation_kernel, dim3(n), dim3(64), 0, as_stream(stream), r, st, sat);
     return launch_status();
 }
 

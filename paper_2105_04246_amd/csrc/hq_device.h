@@ -111,6 +111,56 @@ __device__ inline void hq_ema_update(hq_range *r, float gmin, float gmax)
     r->qp = hq_qparams_from_range(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi);
 }
 
+// ---------------------------------------------------------------------------------------
+// Saturation-driven update (Sec. 4 names the saturation ratio as a statistic; the rule is this
+// library's, stated with hq_range_update_saturation).
+// ---------------------------------------------------------------------------------------
+
+// ln x for a positive normal x by a fixed sequence of fp32 operations, each rounded once:
+// x = m * 2^e, m in [sqrt(1/2), sqrt(2)), s = (m - 1) / (m + 1), ln x = e ln 2 + 2 s (1 + s^2/3 + s^4/5 + s^6/7).
+__device__ inline float hq_ln_fixed(float x)
+{
+    const unsigned bits = __float_as_uint(x);
+    int e = (int)((bits >> 23) & 0xffu) - 127;
+    float m = __uint_as_float((bits & 0x007fffffu) | 0x3f800000u);
+    if (m > 1.41421354f) { m = __fmul_rn(m, 0.5f); e += 1; }
+    const float sq = __fdiv_rn(__fsub_rn(m, 1.0f), __fadd_rn(m, 1.0f));
+    const float s2 = __fmul_rn(sq, sq);
+    float p = __fmul_rn(s2, 1.0f / 7.0f);
+    p = __fadd_rn(p, 0.2f);
+    p = __fmul_rn(p, s2);
+    p = __fadd_rn(p, 1.0f / 3.0f);
+    p = __fmul_rn(p, s2);
+    p = __fadd_rn(p, 1.0f);
+    const float lm = __fmul_rn(__fmul_rn(2.0f, sq), p);
+    return __fadd_rn(__fmul_rn((float)e, 0.693147182f), lm);
+}
+
+__device__ inline void hq_saturation_update(hq_range *r, hq_saturation *sat, unsigned long long clipped,
+                                            unsigned long long count, float gmin, float gmax)
+{
+    if (!r->initialized) {
+        r->qmin = gmin; r->qmax = gmax; r->initialized = 1;
+        sat->streak = 0;
+    } else {
+        const float alpha = __fdiv_rn((float)clipped, (float)count);
+        if (alpha >= sat->alpha_min && alpha <= sat->alpha_max) {
+            sat->streak = 0;
+        } else {
+            sat->streak += 1;
+            if (sat->streak > sat->tau) {
+                const float fl = __fdiv_rn(0.5f, (float)count);
+                const float ah = fminf(fmaxf(alpha, fl), 0.5f);
+                const float rho = __fdiv_rn(hq_ln_fixed(sat->alpha_target), hq_ln_fixed(ah));
+                r->qmin = __fmul_rn(rho, r->qmin);
+                r->qmax = __fmul_rn(rho, r->qmax);
+                sat->streak = 0;
+            }
+        }
+    }
+    r->qp = hq_qparams_from_range(r->qmin, r->qmax, r->symmetric, r->qlo, r->qhi);
+}
+
 // Everything the epilogue needs to turn a zero-point-corrected accumulator into a code.
 struct HqRequant {
     float mult;        // (s_a * s_b) / s_out

@@ -932,3 +932,49 @@ def test_batched_range_update(H, hq):
             assert int(st["count"]) == 0 and int(st["acc_min"]) == 2**31 - 1
         idle = H.read_range(tracks[2].r)
         assert int(idle["initialized"]) == 0 and float(idle["qmin"]) == 0.0 and float(idle["qmax"]) == 0.0
+
+
+# ---------------------------------------------------------------------------------------
+# Saturation-driven range update (Sec. 4: the saturation ratio as the statistic)
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("op", ["dgrad", "fwd"])
+def test_saturation_driven_update_follows_a_drifting_tensor(H, hq, op):
+    """Twelve iterations of one layer whose data operand shrinks 0.7x per iteration and jumps up 30x at
+    iteration 8: the range waits for more than tau = 1 iterations outside the band, then moves by the
+    Laplace quantile rule.  Codes, statistics, quantizer, range and streak against the oracle after
+    every iteration; the range must have moved in both directions."""
+    L = wl.conv("sat_conv", 4, 20, 32, 48, 3)
+    sym = op == "dgrad"
+    g = np.random.default_rng(99)
+    W = wl.he_weight(g, L)
+    Wdev = H.DevWeights(L, W)
+    r, st = hq.new_range(0.9, sym), hq.new_stats(1)
+    sat = hq.new_saturation(alpha_min=2e-4, alpha_max=5e-3, alpha_target=1e-3, tau=1)
+    ref_r, ref_sat = oracle.Range.new(0.9, sym), oracle.Saturation.new(2e-4, 5e-3, 1e-3, 1)
+    widths, moved = [], []
+    for t in range(12):
+        gain = 0.7 ** t * (30.0 if t >= 8 else 1.0)
+        if sym:
+            A = wl.laplace_gradient(g, wl.out_shape(L), 1e-3)
+        else:
+            A = wl.relu_activation(g, wl.in_shape(L))
+        A = wl.QTensor(A.codes, np.float32(A.scale * gain), A.zero_point)     # same kind of codes, real values scaled
+        Adev = H.DevTensor(A)
+        a_scale = oracle.acc_scale(A.scale, W.scale)
+        c = H.oracle_acc(L, op, A, W)
+        before = (ref_r.qmin, ref_r.qmax)
+        want = oracle.saturation_step(c, a_scale, ref_r, ref_sat)
+        codes, q = H.gpu_quantized_op(L, op, Adev, Wdev, r, st, "dynamic" if t == 0 else "fused")
+        got_st = H.read_stats(st)
+        hq.hq_range_update_saturation(r, st, sat)
+        H.assert_stats_equal(got_st, want, a_scale)
+        assert np.float32(q["scale"]) == want["scale"] and int(q["zero_point"]) == want["zero_point"]
+        assert np.array_equal(codes, want["codes"])
+        H.assert_range_close(H.read_range(r), ref_r)
+        got_sat = hq.from_device(sat, hq.SATURATION)[0]
+        assert int(got_sat["streak"]) == ref_sat.streak and int(got_sat["tau"]) == 1
+        assert int(H.read_stats(st)["count"]) == 0
+        widths.append(ref_r.qmax - ref_r.qmin)
+        moved.append(t > 0 and (ref_r.qmin, ref_r.qmax) != before)
+    assert any(widths[t] < widths[t - 1] for t in range(1, 8)) and widths[-1] > widths[7]
+    assert 2 <= sum(moved) < 11                          # it moved, and not on every iteration

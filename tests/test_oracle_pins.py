@@ -719,3 +719,107 @@ def test_accumulator_unit_feeds_the_range_update_as_one_fp32_product():
         oracle.range_update(r, mn, mx, a)                               # sets q^0 = min-max of the first batch
         assert f32(r.qmin) == _rne_f32(_fr(a) * _fr(_rne_f32(Fraction(mn))))
         assert f32(r.qmax) == _rne_f32(_fr(a) * _fr(_rne_f32(Fraction(mx))))
+
+
+# --------------------------------------------------------------------------- saturation-driven update
+def test_fixed_sequence_logarithm_is_a_logarithm():
+    """The fp32 logarithm the saturation-driven update evaluates with a fixed operation sequence
+    agrees with the mathematical one to 1e-6 (absolute, or relative for large magnitudes)."""
+    g = np.random.default_rng(11)
+    xs = np.concatenate([10.0 ** g.uniform(-30, 0, 4000), g.uniform(0.4, 1.0, 4000),
+                         [1.0, 0.5, 0.25, 2.0 ** -20, 0.70710678, 0.70710689, 2e-38]]).astype(np.float32)
+    for x in xs:
+        got, want = float(oracle.ln_fixed(x)), math.log(float(x))
+        assert abs(got - want) <= 1e-6 * max(1.0, abs(want)), (x, got, want)
+    assert oracle.ln_fixed(1.0) == 0.0
+    assert oracle.ln_fixed(2.0 ** -8) * f32(2.0) == oracle.ln_fixed(2.0 ** -16)      # e * ln 2, exactly
+
+
+def _sat_out(clip, count, mn=-1000, mx=1000):
+    return dict(clip_lo=clip // 2, clip_hi=clip - clip // 2, count=count, acc_min=mn, acc_max=mx)
+
+
+def test_saturation_update_band_streak_and_rescaling_by_hand():
+    """Sec. 4 names the saturation ratio as a statistic; the rule pinned here (DESIGN reading): inside
+    the band nothing moves; outside it for more than tau iterations in a row the range is rescaled by
+    ln(alpha_target) / ln(alpha)."""
+    r = oracle.Range.new(0.9, True)
+    sat = oracle.Saturation.new(alpha_min=2.0 ** -12, alpha_max=2.0 ** -6, alpha_target=2.0 ** -8, tau=2)
+    # first call: q^0 from the first batch's min-max
+    oracle.range_update_saturation(r, sat, _sat_out(0, 4096, -500, 750), 0.01)
+    assert (r.qmin, r.qmax, r.initialized, sat.streak) == (f32(0.01) * f32(-500), f32(0.01) * f32(750), 1, 0)
+    q0 = (r.qmin, r.qmax)
+    # inside the band (2^-12 <= alpha <= 2^-6): nothing moves, at the edges too
+    for clip in (1 << 8, 1 << 4, 1 << 10):                                     # alpha = 2^-8, 2^-12, 2^-6 of 2^16
+        oracle.range_update_saturation(r, sat, _sat_out(clip, 1 << 16), 0.01)
+        assert (r.qmin, r.qmax) == q0 and sat.streak == 0
+    # too much clipping (alpha = 2^-4), but only twice in a row, then back inside: no update
+    for _ in range(2):
+        oracle.range_update_saturation(r, sat, _sat_out(1 << 12, 1 << 16), 0.01)
+    assert (r.qmin, r.qmax) == q0 and sat.streak == 2
+    oracle.range_update_saturation(r, sat, _sat_out(1 << 8, 1 << 16), 0.01)
+    assert (r.qmin, r.qmax) == q0 and sat.streak == 0
+    # three times in a row (more than tau = 2): rescaled by ln(2^-8) / ln(2^-4) = 2, exactly
+    for k in range(3):
+        oracle.range_update_saturation(r, sat, _sat_out(1 << 12, 1 << 16), 0.01)
+        assert sat.streak == (k + 1) % 3
+    assert (r.qmin, r.qmax) == (f32(2) * q0[0], f32(2) * q0[1])
+    assert r.scale == f32(2) * q0[1] / f32(127)                                # quantizer re-derived (symmetric grid)
+    # too little clipping (alpha = 2^-16 < alpha_min): after three iterations the range halves
+    for _ in range(3):
+        oracle.range_update_saturation(r, sat, _sat_out(1, 1 << 16), 0.01)
+    assert (r.qmin, r.qmax) == q0
+    # nothing clipped at all: the ratio is taken as half an element, 1 / (2 count)
+    for _ in range(3):
+        oracle.range_update_saturation(r, sat, _sat_out(0, 1 << 15), 0.01)
+    assert (r.qmin, r.qmax) == (f32(0.5) * q0[0], f32(0.5) * q0[1])
+    # everything clipped: the ratio is capped at 1/2, the range grows by ln(2^-8) / ln(1/2) = 8
+    for _ in range(3):
+        oracle.range_update_saturation(r, sat, _sat_out(1 << 15, 1 << 15), 0.01)
+    assert (r.qmin, r.qmax) == (f32(4) * q0[0], f32(4) * q0[1])
+    # no statistics: nothing happens
+    before = (r.qmin, r.qmax, sat.streak)
+    oracle.range_update_saturation(r, sat, _sat_out(0, 0), 0.01)
+    assert (r.qmin, r.qmax, sat.streak) == before
+
+
+@pytest.mark.parametrize("start", [0.25, 4.0])
+def test_saturation_update_reaches_the_laplace_quantile(start):
+    """For a zero-mean Laplace(0, b) tensor a fraction exp(-q / b) lies beyond +-q, so the rescaled
+    range must land on q' = b ln(1 / alpha_target) whatever range it started from, and the next
+    batch then saturates at about alpha_target (the inverse-CDF step of Sec. 4's saturation variant)."""
+    g = np.random.default_rng(3)
+    b, a_scale, target, n = 400.0, f32(1e-3), 1e-3, 1 << 21
+    sat = oracle.Saturation.new(alpha_min=5e-4, alpha_max=2e-3, alpha_target=target, tau=0)
+    r = oracle.Range.new(0.9, True)
+    q_star = b * math.log(1 / target)                                          # in accumulator units
+    r.qmin, r.qmax, r.initialized = -start * q_star * float(a_scale), start * q_star * float(a_scale), 1
+    lib_range = oracle.qparams(r.qmin, r.qmax, 1, -127, 127)
+    r.scale, r.zero_point = float(lib_range[0]), int(lib_range[1])
+    ratios = []
+    for t in range(3):
+        c = np.rint(g.laplace(0, b, n)).astype(np.int32)
+        out = oracle.quantize_static(c, a_scale, r)
+        ratios.append((out["clip_lo"] + out["clip_hi"]) / n)
+        oracle.range_update_saturation(r, sat, out, a_scale)
+    if start < 1:
+        assert abs(ratios[0] - math.exp(-start * math.log(1 / target))) < 0.01  # started too narrow: e^(-q/b)
+    else:
+        assert ratios[0] == 0                                                  # started too wide: nothing clips
+    # started too narrow: one step lands on the quantile; too wide: the unseen tail is taken as half an
+    # element, so the first step overshoots downwards and the second corrects it
+    assert abs(r.qmax / (q_star * float(a_scale)) - 1) < 0.08
+    assert 0.5 * target < ratios[2] < 2 * target
+
+
+def test_saturation_step_orders_the_first_batch_like_in_hindsight_min_max():
+    """First batch: quantized with its own min-max (nothing clips), which also becomes q^0; its clip
+    counts then enter the saturation rule like any other batch's (one iteration below the band)."""
+    c = np.array([-700, -3, 0, 5, 900, 12], np.int32)
+    r, sat = oracle.Range.new(0.9, True), oracle.Saturation.new(1e-3, 1e-1, 1e-2, tau=3)
+    out = oracle.saturation_step(c, f32(0.5), r, sat)
+    assert (r.qmin, r.qmax, r.initialized, sat.streak) == (-350.0, 450.0, 1, 1)
+    assert out["clip_lo"] + out["clip_hi"] == 0 and out["codes"].tolist() == [-99, 0, 0, 1, 127, 2]
+    # second batch, statically with q^0: one of six values clips (alpha = 1/6 > alpha_max), streak 2
+    out = oracle.saturation_step(np.array([-700, -3, 0, 5, 2000, 12], np.int32), f32(0.5), r, sat)
+    assert out["clip_hi"] == 1 and out["codes"][4] == 127 and sat.streak == 2 and (r.qmin, r.qmax) == (-350.0, 450.0)
