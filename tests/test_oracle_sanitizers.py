@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 # millions of values keep a reduced range through HQ_ORACLE_SANITIZE, see test_oracle_pins.py)
 SELECT = ("linear or conv or depthwise or minmax or qparams or idempotent or clip_counts or range_update "
           "or static_with_current or in_hindsight_sequence or weight_quantizer or weight_gradient_scale "
-          "or accumulator_unit or real_tensor_quantizer or stochastic_rounding_against")
+          "or accumulator_unit or real_tensor_quantizer or stochastic_rounding_against or saturation or logarithm")
 
 
 def test_pins_pass_under_address_and_undefined_behaviour_sanitizers():
