@@ -304,8 +304,6 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
         // stochastic rounding: the two 3x3 / 1x1 fast paths, else the two general kernels
         if (p->kind == HQ_DEPTHWISE)
             return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
-        rc = hq_try_launch_conv3(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
-        if (rc != HQ_E_BADSHAPE) return rc;
         rc = hq_try_launch_bandw(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
         if (rc != HQ_E_BADSHAPE) return rc;
         rc = hq_try_launch_band(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream), sr_seed);
@@ -315,8 +313,6 @@ static int gemm_common(const hq_problem *p, int dgrad, const int8_t *A, const hq
     if (p->kind == HQ_DEPTHWISE)
         return hq_launch_depthwise(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     rc = hq_try_launch_direct(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
-    if (rc != HQ_E_BADSHAPE) return rc;
-    rc = hq_try_launch_conv3(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     if (rc != HQ_E_BADSHAPE) return rc;
     rc = hq_try_launch_bandw(p, dgrad, A, aq, Bw, bq, bsum, range, out, out32, outq, st, as_stream(stream));
     if (rc != HQ_E_BADSHAPE) return rc;

@@ -27,17 +27,6 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
                         int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream,
                         const uint64_t *sr_seed = nullptr);
 
-// 3x3 stride-1 layers with 128 or more reduced channels: flat pixel tiles, wavefront tiles of up to 128 x 128,
-// one workgroup per compute unit; HQ_E_BADSHAPE: not covered.  sr_seed as for hq_launch_gemm.
-// force_cfg (tuning builds): 0 = choose the tile shape, else 10 * MT + NT.
-#ifndef HQ_C3_FORCE
-#define HQ_C3_FORCE 0
-#endif
-int hq_try_launch_conv3(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Bw,
-                        const hq_qparams *bq, const int32_t *bsum, const hq_range *range, int8_t *out8,
-                        int32_t *out32, hq_qparams *outq, hq_stats *st, hipStream_t stream,
-                        const uint64_t *sr_seed = nullptr, int force_cfg = HQ_C3_FORCE);
-
 // sr_seed as for hq_launch_gemm (stochastic rounding runs in the general stencil kernel).
 int hq_launch_depthwise(const hq_problem *p, int dgrad, const int8_t *A, const hq_qparams *aq, const int8_t *Wt,
                         const hq_qparams *bq, const int32_t *wsum, const hq_range *range, int8_t *out8,
