@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch plain device copies of known size (counter calibration under rocprofv3 --pmc)")
+    ap.add_argument("--stack-only", choices=["fused", "dynamic"],
+                    help="run nothing but the ResNet-18-shaped stack: range initialisation, one warm-up step and "
+                         "--steps steps of the chosen kind (for counter collection under rocprofv3 --pmc: the "
+                         "last `launches_per_step` dispatches of the run are one step)")
     return ap.parse_args()
 
 
@@ -155,10 +159,30 @@ class DeviceLayer(Layer):
         Layer.__init__(self, hq, torch, wl, L, as_q(xc, sx, -128), as_q(wc, sw, 0), as_q(gc, sg, 0), state)
 
 
-def stack_step(hq, torch, wl, specs, label, reps=3):
+def kernel_family(wl, L, op):
+    """Name of the kernel the library's dispatch picks for one launch (mirrors the rules of hq_api.hip / the launchers)."""
+    k3 = L.kind == wl.CONV and L.R == 3 and L.S == 3 and L.stride == 1 and L.pad == 1
+    if op == "wgrad":
+        if k3 and L.C % 64 == 0 and L.Cout % 64 == 0:
+            return "hq_wgrad_band_kernel + wband_finalize_kernel"
+        return "hq_wgrad_kernel + wgrad_finalize_kernel"
+    cin = L.Cout if op == "dgrad" else L.C
+    cout = L.C if op == "dgrad" else L.Cout
+    if op == "fwd" and L.kind == wl.CONV and L.C in (3, 4):
+        return "hq_direct_kernel"
+    if k3 and cin % 64 == 0 and cin >= 128 and cout >= 128:
+        return "hq_bandw_kernel"
+    if k3 and cin == 64:
+        return "hq_band_kernel"
+    return "hq_gemm_kernel"
+
+
+def stack_step(hq, torch, wl, specs, label, reps=20, warmup=3, config=None, only=None):
     """One quantized training step over a stack of layers at batch 256: a forward and a wgrad launch
     per layer and a dgrad launch for all but the first, with in-hindsight ranges, against the same
-    step with the dynamic two-pass path."""
+    step with the dynamic two-pass path.  With `config` the operands are the host-generated tensors of
+    workloads.layer_inputs(L, config, 1, index) -- the generator the parity tests use -- otherwise they
+    are drawn on the device with the same recipe."""
     # all range states of the step in one array ([activations of every layer], [gradients of every
     # layer]) and their statistics in another: one update launch after each sweep
     n = len(specs)
@@ -166,7 +190,13 @@ def stack_step(hq, torch, wl, specs, label, reps=3):
     rs, ss = hq.RANGE.itemsize, hq.STATS.itemsize
     state = lambda i: (ranges[i * rs:(i + 1) * rs], ranges[(n + i) * rs:(n + i + 1) * rs],
                        stats[i * ss:(i + 1) * ss], stats[(n + i) * ss:(n + i + 1) * ss])
-    layers = [DeviceLayer(hq, torch, wl, L, 1000 + i, state(i)) for i, L in enumerate(specs)]
+    layers = []
+    for i, L in enumerate(specs):
+        if config is None:
+            layers.append(DeviceLayer(hq, torch, wl, L, 1000 + i, state(i)))
+        else:
+            X, W, dY = wl.layer_inputs(L, config, 1, i, image_input=(i == 0))
+            layers.append(Layer(hq, torch, wl, L, X, W, dY, state(i)))
     for ly in layers:
         ly.init_ranges()
 
@@ -182,25 +212,58 @@ def stack_step(hq, torch, wl, specs, label, reps=3):
 
     fused = lambda: sweep(lambda ly: ly.fwd(), lambda ly: ly.dgrad())
     dynamic = lambda: sweep(lambda ly: ly.dyn_fwd(), lambda ly: ly.dyn_dgrad())
+    # kernel launches of one step: 1 per fused GEMM, 3 per dynamic one (two passes and the range between
+    # them), 2 per weight gradient (3 where the integer sums start from zero), 2 range updates
+    if only is not None:
+        # counter collection: a stats_fold_kernel launch (used nowhere else in a step) brackets every step
+        step = fused if only == "fused" else dynamic
+        mark = hq.new_stats(1)
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            hq.hq_stats_fold(mark, 1)
+            step()
+        hq.hq_stats_fold(mark, 1)
+        torch.cuda.synchronize()
+        return {"workload": label, "kind": only, "steps": reps, "ms_per_step_wall": (time.perf_counter() - t0) * 1e3 / reps}
 
     fused_sr = lambda: sweep(lambda ly: ly.fwd(), lambda ly: ly.dgrad_sr())       # the paper's gradient rounding (Sec. 5)
-    f_ms, d_ms = time_calls(torch, fused, reps, 1), time_calls(torch, dynamic, reps, 1)
-    sr_ms = time_calls(torch, fused_sr, reps, 1)
-    # every layer's three launches on their own (three repetitions each, back to back)
-    per_layer = []
+    f_ms, d_ms = time_calls(torch, fused, reps, warmup), time_calls(torch, dynamic, reps, warmup)
+    sr_ms = time_calls(torch, fused_sr, reps, warmup)
+    # every layer's three launches on their own (five repetitions each, back to back)
+    per_layer, fam = [], {}
     for i, (L, ly) in enumerate(zip(specs, layers)):
         gop = 2 * wl.macs(L) / 1e9
-        row = {"layer": L.name, "gop": gop, "fwd_ms": time_calls(torch, ly.fwd, 3, 1),
-               "dgrad_ms": time_calls(torch, ly.dgrad, 3, 1) if i > 0 else None, "wgrad_ms": time_calls(torch, ly.wgrad, 3, 1)}
+        row = {"layer": L.name, "gop": gop, "fwd_ms": time_calls(torch, ly.fwd, 5, 1),
+               "dgrad_ms": time_calls(torch, ly.dgrad, 5, 1) if i > 0 else None, "wgrad_ms": time_calls(torch, ly.wgrad, 5, 1)}
         row["fwd_tops"] = gop / row["fwd_ms"]
         per_layer.append(row)
+        for op in ("fwd", "dgrad", "wgrad"):
+            if row[op + "_ms"] is None:
+                continue
+            f = fam.setdefault(kernel_family(wl, L, op), {"launches": 0, "ms": 0.0, "gop": 0.0, "alg_bytes": 0})
+            f["launches"] += 1; f["ms"] += row[op + "_ms"]; f["gop"] += gop; f["alg_bytes"] += wl.fused_bytes(L, op)
     hq.hq_stats_reset(stats, 2 * n)
     ops = sum(2 * wl.macs(L) * (3 if i > 0 else 2) for i, L in enumerate(specs))
     fb = sum(wl.fused_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
     db = sum(wl.dynamic_bytes(L, o) for i, L in enumerate(specs) for o in (("fwd", "dgrad", "wgrad") if i > 0 else ("fwd", "wgrad")))
+    # the kernel that takes the largest share of the fused step, against the int8 MFMA peak
+    dom = max(fam, key=lambda k: fam[k]["ms"])
+    d = fam[dom]
+    roofline = {"kernel": dom, "bound": "mfma", "launches_per_step": d["launches"], "ms_per_step": d["ms"],
+                "achieved": d["gop"] / d["ms"], "peak": PEAK_INT8_TOPS, "unit": "TOP/s",        # GOP / ms = TOP/s
+                "frac": d["gop"] / d["ms"] / PEAK_INT8_TOPS,
+                "hbm_frac_of_8TBs": d["alg_bytes"] / (d["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "how": "sum over the step's launches of this kernel, each timed alone (5 back-to-back repetitions, HIP events)"}
     return {"workload": "%s: %d fwd + %d dgrad + %d wgrad" % (label, n, n - 1, n), "ops": ops,
+            "inputs": "workloads.layer_inputs (host-generated, the parity tests' generator)" if config is not None
+                      else "drawn on the device with the recipe of workloads.py (not the parity tests' tensors)",
+            "timed_steps": reps, "warmup_steps": warmup,
             "fused_ms_per_step": f_ms, "dynamic_ms_per_step": d_ms, "fused_tops": ops / (f_ms * 1e-3) / 1e12,
+            "speedup_vs_dynamic": d_ms / f_ms,
             "fused_ms_per_step_stochastic_dgrad": sr_ms, "per_layer": per_layer,
+            "time_by_kernel_ms": {k: v["ms"] for k, v in fam.items()}, "roofline": roofline,
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb}}
 
 
@@ -296,7 +359,7 @@ def cpu_baseline(wl, sample_B, min_seconds=10.0):
     dt = time.perf_counter() - t0
     ops = passes * 3 * 2 * wl.macs(L)
     return {"value": ops / dt / 1e12, "unit": "TOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "same layer and step at batch %d of 128, %d whole passes (%.1f GOP) in %.1f s"
+            "sample": "the headline layer and step at batch %d of 128 (the same seeded inputs), %d whole passes (%.1f GOP) in %.1f s"
                       % (sample_B, passes, ops / 1e9, dt)}
 
 
@@ -322,6 +385,17 @@ def main():
     import workloads as wl
 
     torch.cuda.set_device(0)
+    if args.stack_only:
+        out = stack_step(hq, torch, wl, wl.resnet18_layers(B=256), "ResNet-18-shaped stack, batch 256 @224x224",
+                         reps=args.steps, only=args.stack_only)
+        if args.calibrate_copy:
+            a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+            b = torch.empty_like(a)
+            b.copy_(a)
+            torch.cuda.synchronize()
+            out["calibration_copy_bytes"] = {"read": a.numel(), "write": a.numel()}
+        print(json.dumps(out))
+        return
     L, X, W = wl.c2_inputs(1)
     dY = wl.laplace_gradient(wl.rng(2, 1, 2), wl.out_shape(L), 1e-3)
     lay = Layer(hq, torch, wl, L, X, W, dY)
@@ -383,6 +457,9 @@ def main():
     roofline = {"kernel": names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": achieved / PEAK_INT8_TOPS, "peak_measured": peak_measured,
                 "frac_of_measured": achieved / peak_measured, "traffic": stored_traffic(dom),
+                "traffic_source": "stored: profiles/hbm_traffic.json, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs "
+                                  "summarised in profiles/ (not measured in this run; all of this layer's tensors fit "
+                                  "the 256 MB last-level cache, so these are bytes between L2 and the fabric)",
                 "algorithmic_bytes": wl.fused_bytes(L, dom), "avg_launch_ms": dom_ms, "empty_event_pair_ms": pair_ms,
                 "launches_timed": "every %dth of the %d timed steps" % (EV, K),
                 "hbm_frac_of_8TBs": wl.fused_bytes(L, dom) / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
@@ -410,7 +487,7 @@ def main():
             "fwd_fused_ms": time_calls(torch, lay.fwd, reps), "fwd_dynamic_ms": time_calls(torch, lay.dyn_fwd, reps),
             "dgrad_fused_ms": time_calls(torch, lay.dgrad, reps), "dgrad_dynamic_ms": time_calls(torch, lay.dyn_dgrad, reps),
             "algorithmic_hbm_bytes_per_step": {"fused": fb, "dynamic": db, "ratio": db / fb},
-            "measured_hbm_bytes_per_step": stored_traffic("step")}
+            "measured_hbm_bytes_per_step": stored_traffic("step"), "traffic_source": "stored: profiles/hbm_traffic.json"}
         # the same input-gradient GEMM with stochastic rounding in the epilogue
         out["stochastic_rounding"] = {"dgrad_sr_ms": time_calls(torch, lay.dgrad_sr, reps),
                                       "dgrad_nearest_even_ms": out["fused_vs_dynamic"]["dgrad_fused_ms"]}
@@ -448,9 +525,12 @@ def main():
             del ly
             torch.cuda.empty_cache()
         out["other_layers"] = extra
-        out["resnet18_step"] = stack_step(hq, torch, wl, wl.resnet18_layers(B=256), "ResNet-18-shaped stack, batch 256 @224x224")
+        out["resnet18_step"] = stack_step(hq, torch, wl, wl.resnet18_layers(B=256), "ResNet-18-shaped stack, batch 256 @224x224",
+                                          config=5)
+        out["resnet18_step"]["measured_hbm_bytes_per_step"] = stored_traffic("resnet18_step")
+        out["resnet18_step"]["traffic_source"] = "stored: profiles/hbm_traffic.json (rocprofv3 --pmc over bench.py --stack-only)"
         torch.cuda.empty_cache()
-        out["vgg16_step"] = stack_step(hq, torch, wl, wl.vgg16_layers(B=256), "VGG16-shaped stack, batch 256 @64x64")
+        out["vgg16_step"] = stack_step(hq, torch, wl, wl.vgg16_layers(B=256), "VGG16-shaped stack, batch 256 @64x64", reps=5, warmup=1)
         torch.cuda.empty_cache()
         out["real_tensor_quantizer"] = tensor_quantizer(hq, torch, wl)
         torch.cuda.empty_cache()
@@ -489,7 +569,7 @@ def main():
         out["calibration_copy_bytes"] = {"read": a.numel(), "write": a.numel()}
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, 64)
+        out["cpu_baseline"] = cpu_baseline(wl, 128)
     print(json.dumps(out))
 
 
