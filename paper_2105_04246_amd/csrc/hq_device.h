@@ -216,6 +216,21 @@ __device__ inline HqEpilogue hq_make_epilogue(float acc_scale, const hq_range *r
 
 __device__ inline float hq_round_scaled(int c, float mult) { return rintf(__fmul_rn((float)c, mult)); }
 
+// Three-operand integer minimum / maximum (v_min3_i32 / v_max3_i32).  Written out because the compiler
+// balances a chain of two-operand minima into a tree and then needs 12 instructions for 16 values, not 8.
+__device__ inline int hq_min3(int a, int b, int c)
+{
+    int r;
+    asm("v_min3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ inline int hq_max3(int a, int b, int c)
+{
+    int r;
+    asm("v_max3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // N = 4 or 16 accumulators -> N / 4 words of signed codes.  v_cvt_pk_u8_f32 saturates to
 // 0..255, which after the flip of the top bits is the clamp to -128..127.
 template <int N, bool FULL_GRID>
@@ -224,7 +239,7 @@ __device__ inline void hq_requant_group(const int *c, const HqEpilogue &ep, int 
 {
     int gmn = c[0], gmx = c[0];
 #pragma unroll
-    for (int e = 1; e + 1 < N; e += 2) { gmn = min(gmn, min(c[e], c[e + 1])); gmx = max(gmx, max(c[e], c[e + 1])); }
+    for (int e = 1; e + 1 < N; e += 2) { gmn = hq_min3(gmn, c[e], c[e + 1]); gmx = hq_max3(gmx, c[e], c[e + 1]); }
     gmn = min(gmn, c[N - 1]); gmx = max(gmx, c[N - 1]);
     mn = min(mn, gmn); mx = max(mx, gmx);
     float f[N];
@@ -297,7 +312,7 @@ __device__ inline void hq_requant_group_sr(const int *c, const HqEpilogue &ep, c
 {
     int gmn = c[0], gmx = c[0];
 #pragma unroll
-    for (int e = 1; e + 1 < N; e += 2) { gmn = min(gmn, min(c[e], c[e + 1])); gmx = max(gmx, max(c[e], c[e + 1])); }
+    for (int e = 1; e + 1 < N; e += 2) { gmn = hq_min3(gmn, c[e], c[e + 1]); gmx = hq_max3(gmx, c[e], c[e + 1]); }
     gmn = min(gmn, c[N - 1]); gmx = max(gmx, c[N - 1]);
     mn = min(mn, gmn); mx = max(mx, gmx);
     const unsigned lo0 = (unsigned)idx0, hi0 = (unsigned)(idx0 >> 32);
@@ -338,7 +353,7 @@ __device__ inline void hq_requant_group_sr(const int *c, const HqEpilogue &ep, c
 template <int N> __device__ inline void hq_minmax_group(const int *c, int &mn, int &mx)
 {
 #pragma unroll
-    for (int e = 0; e + 1 < N; e += 2) { mn = min(mn, min(c[e], c[e + 1])); mx = max(mx, max(c[e], c[e + 1])); }
+    for (int e = 0; e + 1 < N; e += 2) { mn = hq_min3(mn, c[e], c[e + 1]); mx = hq_max3(mx, c[e], c[e + 1]); }
 }
 
 __device__ inline unsigned hq_pack4(int a, int b, int c, int d)
