@@ -47,6 +47,19 @@ struct BandwArgs {
     HqSr sr;                       // seed of stochastic rounding (epilogue mode 2)
 };
 
+// 16-byte rows of one repeated byte value, indexed by that value: the source of the lanes of a direct-to-LDS
+// load that lie outside the image (zero-point code) or beyond the weight tensor (0), so that every lane of
+// every load has an address and a wavefront's count of outstanding loads does not depend on its data.
+struct BwFillRows {
+    unsigned w[256][4];
+    constexpr BwFillRows() : w()
+    {
+        for (int v = 0; v < 256; v++)
+            for (int k = 0; k < 4; k++) w[v][k] = (unsigned)v * 0x01010101u;
+    }
+};
+__device__ const BwFillRows bw_fill_rows = BwFillRows();
+
 __device__ inline int bw_sigma32(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 __device__ inline int bw_swz(int row) { return (row >> 2) & 3; }
 
@@ -63,10 +76,12 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
     int *bz = reinterpret_cast<int *>(Pl + 2 * (size_t)patch_bytes);    // [128]
     int *red = bz + BW_BN;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // scalar: branches on it are uniform
     const int za = a.aq->zero_point;
     const int fillw = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
-    const v4i fillv = {fillw, fillw, fillw, fillw}, zerov = {0, 0, 0, 0};
+    const int8_t *fill_src = reinterpret_cast<const int8_t *>(bw_fill_rows.w[za & 0xff]);
+    const int8_t *zero_src = reinterpret_cast<const int8_t *>(bw_fill_rows.w[0]);
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
     HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
     if (FUSED) ep = hq_make_epilogue(acc_scale, a.range);
@@ -103,13 +118,10 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
                 const int pr = (int)hq_magic_div((unsigned)r1, a.magic_PW), pc = r1 - pr * a.PW;
                 const int iy = y0 + pr - a.pad, ix = pc - a.pad;
                 const bool inside = q < a.patch_px * 4 && il < timg && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-                int8_t *dst = dstp + (size_t)(q0 + (tid & ~63)) * 16;   // this wavefront's 1 KiB
-                if (inside) {
+                int8_t *dst = dstp + (size_t)(q0 + wave * 64) * 16;     // this wavefront's 1 KiB
+                if (q0 + wave * 64 < a.patch_px * 4) {                  // (uniform over the wavefront)
                     const int8_t *src = a.A + (((size_t)(b0 + il) * a.H + iy) * a.W + ix) * a.C + cchunk * BW_CK + ck * 16;
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                     (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-                } else if (q < ((a.patch_px * 4 + 63) & ~63)) {
-                    *reinterpret_cast<v4i *>(dst + lane * 16) = fillv;
+                    hq_global_to_lds16(inside ? src : fill_src, dst);
                 }
             }
         };
@@ -133,14 +145,8 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
                 const int woff = (a.flip ? 8 - tap : tap) * a.C + cchunk * BW_CK;
 #pragma unroll
                 for (int k = 0; k < 2; k++) {
-                    int8_t *dst = Wl + (size_t)(buf * 2 + u) * BW_BN * BW_CK + (size_t)(HQ_THREADS * k + (tid & ~63)) * 16;
-                    if (wrow_ok[k]) {
-                        const int8_t *src = wsrc[k] + woff;
-                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-                    } else {
-                        *reinterpret_cast<v4i *>(dst + lane * 16) = zerov;
-                    }
+                    int8_t *dst = Wl + (size_t)(buf * 2 + u) * BW_BN * BW_CK + (size_t)(HQ_THREADS * k + wave * 64) * 16;
+                    hq_global_to_lds16(wrow_ok[k] ? wsrc[k] + woff : zero_src, dst);
                 }
             }
         };
@@ -160,7 +166,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             const int oy = r1 / a.W, ox = r1 - oy * a.W;
             prow[i] = (il * a.PH + oy) * a.PW + ox;
         }
-        const bool active = wave * 64 < npix;
+        const bool active = wave * 64 < npix;                          // scalar
         int wfoff[2];                                      // weight fragment offset of k-step ks in 32-row block 0
 #pragma unroll                                             // (the swizzle repeats every 8 rows: block j adds j * 2048)
         for (int ks = 0; ks < 2; ks++)
@@ -182,59 +188,64 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             }
 
         for (int s = 0; s < nstages; s++) {
-            if (s + 1 < nstages) issue_weights(s + 1, (s + 1) & 1);
-            {
-                // the next chunk's patch is requested by the first stage that lies wholly inside this chunk:
-                // every reader of the buffer it overwrites finished before that stage's opening barrier
-                const int c0 = (2 * s) / 9, t0 = 2 * s - c0 * 9;
-                if (t0 <= 1 && c0 + 1 < cchunks) issue_patch(c0 + 1, (c0 + 1) & 1);
+            // four k-steps (two per (tap, chunk) step) with two fragment register sets: the fragments of
+            // k-step kk + 1 are requested before the MFMAs of k-step kk are issued, and the stage's first
+            // fragments before the next stage's loads, whose address arithmetic then runs under their latency
+            const bool full = 2 * s + 1 < nsteps;
+            const int c0 = (2 * s) / 9, t0 = 2 * s - c0 * 9;
+            // the next chunk's patch is requested by the first stage that lies wholly inside this chunk:
+            // every reader of the buffer it overwrites finished before that stage's opening barrier
+            const bool patch_now = t0 <= 1 && c0 + 1 < cchunks;
+            const int8_t *Wb[2], *Pb[2];
+            int toff[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int step = min(2 * s + u, nsteps - 1);
+                const int cchunk = step / 9, tap = step - cchunk * 9;
+                Wb[u] = Wl + (size_t)((s & 1) * 2 + u) * BW_BN * BW_CK;
+                Pb[u] = Pl + (size_t)(cchunk & 1) * patch_bytes;
+                toff[u] = (tap / 3) * a.PW + (tap % 3);
             }
+            v4i wfA[BW_NT], afA[2], wfB[BW_NT], afB[2];
+            auto load_frags = [&](int kk, v4i (&wf)[BW_NT], v4i (&af)[2]) {
+                const int u = kk >> 1, ks = kk & 1;
+#pragma unroll
+                for (int j = 0; j < BW_NT; j++) wf[j] = *reinterpret_cast<const v4i *>(Wb[u] + j * 32 * BW_CK + wfoff[ks]);
+#pragma unroll
+                for (int i = 0; i < 2; i++) {
+                    const int row = prow[i] + toff[u];
+                    af[i] = *reinterpret_cast<const v4i *>(Pb[u] + row * BW_CK + 16 * ((2 * ks + half) ^ bw_swz(row)));
+                }
+            };
+            auto mfmas = [&](const v4i (&wf)[BW_NT], const v4i (&af)[2]) {
+#pragma unroll
+                for (int i = 0; i < 2; i++)
+#pragma unroll
+                    for (int j = 0; j < BW_NT; j++)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
+            };
             if (active) {
-                // four k-steps (two per (tap, chunk) step); the fragments of k-step kk+1 are requested
-                // before the MFMAs of k-step kk are issued (two register sets)
-                const int nkk = 2 * min(2, nsteps - 2 * s);
-                const int8_t *Wb[2], *Pb[2];
-                int toff[2];
-#pragma unroll
-                for (int u = 0; u < 2; u++) {
-                    const int step = min(2 * s + u, nsteps - 1);
-                    const int cchunk = step / 9, tap = step - cchunk * 9;
-                    Wb[u] = Wl + (size_t)((s & 1) * 2 + u) * BW_BN * BW_CK;
-                    Pb[u] = Pl + (size_t)(cchunk & 1) * patch_bytes;
-                    toff[u] = (tap / 3) * a.PW + (tap % 3);
-                }
-                v4i wfA[BW_NT], afA[2], wfB[BW_NT], afB[2];
-                auto load_frags = [&](int kk, v4i (&wf)[BW_NT], v4i (&af)[2]) {
-                    const int u = kk >> 1, ks = kk & 1;
-#pragma unroll
-                    for (int j = 0; j < BW_NT; j++) wf[j] = *reinterpret_cast<const v4i *>(Wb[u] + j * 32 * BW_CK + wfoff[ks]);
-#pragma unroll
-                    for (int i = 0; i < 2; i++) {
-                        const int row = prow[i] + toff[u];
-                        af[i] = *reinterpret_cast<const v4i *>(Pb[u] + row * BW_CK + 16 * ((2 * ks + half) ^ bw_swz(row)));
-                    }
-                };
-                auto mfmas = [&](const v4i (&wf)[BW_NT], const v4i (&af)[2]) {
-#pragma unroll
-                    for (int i = 0; i < 2; i++)
-#pragma unroll
-                        for (int j = 0; j < BW_NT; j++)
-                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
-                };
                 load_frags(0, wfA, afA);
-#pragma unroll
-                for (int kk = 0; kk < 4; kk += 2) {
-                    if (kk < nkk) {
-                        load_frags(kk + 1, wfB, afB);
-                        __builtin_amdgcn_sched_barrier(0);
-                        mfmas(wfA, afA);
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (kk + 2 < nkk) load_frags(kk + 2, wfA, afA);
-                        __builtin_amdgcn_sched_barrier(0);
-                        mfmas(wfB, afB);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+                if (s + 1 < nstages) issue_weights(s + 1, (s + 1) & 1);
+                if (patch_now) issue_patch(c0 + 1, (c0 + 1) & 1);
+                load_frags(1, wfB, afB);
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(wfA, afA);
+                __builtin_amdgcn_sched_barrier(0);
+                if (full) {
+                    load_frags(2, wfA, afA);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfmas(wfB, afB);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_frags(3, wfB, afB);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfmas(wfA, afA);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                mfmas(wfB, afB);
+            } else {
+                if (s + 1 < nstages) issue_weights(s + 1, (s + 1) & 1);
+                if (patch_now) issue_patch(c0 + 1, (c0 + 1) & 1);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();

@@ -216,6 +216,20 @@ __device__ inline HqEpilogue hq_make_epilogue(float acc_scale, const hq_range *r
 
 __device__ inline float hq_round_scaled(int c, float mult) { return rintf(__fmul_rn((float)c, mult)); }
 
+// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l of the wavefront
+// lands at wave_base + 16 * l.  Written as an asm statement because the compiler, once it has issued such a load
+// itself, waits for every outstanding LDS read before using any of them (it stops counting them), which
+// defeats fragment double buffering in the loops that follow.  The caller waits for the load with an explicit
+// "s_waitcnt vmcnt(..)" before a barrier; the compiler's own counts stay safe because loads retire in order.
+__device__ inline void hq_global_to_lds16(const void *src, void *wave_base)
+{
+    const unsigned m = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) void *)wave_base);
+    unsigned keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "v"(src), "s"(m) : "memory");
+}
+
 // Three-operand integer minimum / maximum (v_min3_i32 / v_max3_i32).  Written out because the compiler
 // balances a chain of two-operand minima into a tree and then needs 12 instructions for 16 values, not 8.
 __device__ inline int hq_min3(int a, int b, int c)
