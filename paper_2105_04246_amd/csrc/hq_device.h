@@ -38,21 +38,28 @@ __device__ inline unsigned hq_bytemask(int lo, int hi)
 // whole, i.e. up to the next multiple of 4 of `end`.
 __device__ inline v4i hq_load16_any(const int8_t *p, const int8_t *begin, const int8_t *end)
 {
-    const uintptr_t addr = reinterpret_cast<uintptr_t>(p);
-    const int8_t *a = reinterpret_cast<const int8_t *>(addr & ~(uintptr_t)3);
-    const unsigned sh = (unsigned)(addr & 3);
-    const int8_t *end4 = reinterpret_cast<const int8_t *>((reinterpret_cast<uintptr_t>(end) + 3) & ~(uintptr_t)3);
+    // (pointer arithmetic only: a pointer rebuilt from an integer would lose its address space and every load
+    // below would become a flat load, which the compiler can only wait for all at once)
+    const unsigned sh = (unsigned)(reinterpret_cast<uintptr_t>(p) & 3);
+    const int8_t *a = p - sh;
+    const int8_t *end4 = end + ((4u - (unsigned)(reinterpret_cast<uintptr_t>(end) & 3)) & 3u);
     int w[5];
-    if (a >= begin && a + 20 <= end4) {
+    // one uniform branch: wavefronts that touch neither end of the tensor (all but a few) take the two wide
+    // loads; the others load word by word from addresses moved inside the tensor where they would fall outside
+    const bool inner = a >= begin && a + 20 <= end4;
+    if (__builtin_amdgcn_ballot_w64(!inner) == 0) {
         v4i x;
         __builtin_memcpy(&x, __builtin_assume_aligned(a, 4), 16);
         w[0] = x[0]; w[1] = x[1]; w[2] = x[2]; w[3] = x[3];
         w[4] = *reinterpret_cast<const int *>(a + 16);
     } else {
+        const int8_t *safe = begin + ((4u - (unsigned)(reinterpret_cast<uintptr_t>(begin) & 3)) & 3u);
 #pragma unroll
         for (int d = 0; d < 5; d++) {
             const int8_t *q = a + 4 * d;
-            w[d] = (q >= begin && q < end4) ? *reinterpret_cast<const int *>(q) : 0;
+            const bool in = q >= begin && q < end4;
+            const int x = *reinterpret_cast<const int *>(in ? q : safe);
+            w[d] = in ? x : 0;
         }
     }
     v4i v;
