@@ -222,6 +222,224 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_direct_kernel(const DirectAr
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// The same layer with the input rows staged in LDS (even stride, W * C a multiple of 4): a workgroup walks
+// bands of whole output rows; the input rows a band needs are copied once into LDS with every pixel widened
+// to 4 bytes (3-channel pixels: three funnel shifts per four pixels; the fourth byte meets a zero weight)
+// inside a frame of zero-point pixels, so a lane's 16 bytes of an input fragment are two aligned 8-byte
+// LDS reads at (input row) * pitch + 4 * stride * ox, with no bounds logic and no byte masks.  The k-step of
+// filter row r is then tap s at bytes 4 s .. 4 s + 3 (weights of the fourth byte and of taps past S are 0).
+// The next band's rows are on their way (global -> registers) while this band is multiplied.
+struct StemArgs {
+    DirectArgs d;
+    int rows_out;                  // output rows per band
+    int in_rows;                   // (rows_out - 1) * stride + R
+    int LP;                        // LDS row pitch in bytes (multiple of 16)
+    int bands_per_image, nbands;
+    int groups;                    // 16-byte groups of four pixels per input row: W / 4
+    unsigned magic_groups;
+};
+
+constexpr int ST_TASKS = 5;        // staged 4-pixel groups per thread and band (host checks the fit)
+
+template <int NT, bool FUSED, int CH>
+__global__ __launch_bounds__(HQ_THREADS, 2) void hq_stem_kernel(const StemArgs sa)
+{
+    const DirectArgs &a = sa.d;
+    extern __shared__ __attribute__((aligned(16))) int8_t stem_lds[];
+    __shared__ int red[4 * (HQ_THREADS / 64)];
+    __shared__ __attribute__((aligned(16))) int bzs[32 * NT];       // z_a * bsum[n]
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int za = a.aq->zero_point;
+    const int fill = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
+    const int buf_bytes = sa.in_rows * sa.LP;
+    if (tid < 32 * NT) bzs[tid] = tid < a.N ? za * a.bsum[tid] : 0;
+    // the frame: every word of both buffers starts as zero-point pixels; staging only ever writes the W image
+    // columns of a row, so the columns left and right of the image keep this value
+    for (int q = tid; q < 2 * buf_bytes / 16; q += HQ_THREADS)
+        *reinterpret_cast<v4i *>(stem_lds + (size_t)q * 16) = v4i{fill, fill, fill, fill};
+
+    // weight fragments in the widened layout: byte 4 s + c of k-step r is W[n][r][s][c] (c < CH, s < S), else 0
+    v4i wf[DR_MAXR][NT];
+#pragma unroll
+    for (int j = 0; j < NT; j++) {
+        const int n = j * 32 + dr_sigma32(lane & 31);
+#pragma unroll
+        for (int r = 0; r < DR_MAXR; r++) {
+            v4i v = {0, 0, 0, 0};
+            if (r < a.R && n < a.N) {
+                const int8_t *w = a.Bw + ((size_t)n * a.R + r) * a.S * CH;
+#pragma unroll
+                for (int d = 0; d < 4; d++) {
+                    const int s = 4 * half + d;
+                    unsigned x = 0;
+                    if (s < a.S) {
+#pragma unroll
+                        for (int c = 0; c < CH; c++) x |= (unsigned)(uint8_t)w[s * CH + c] << (8 * c);
+                    }
+                    v[d] = (int)x;
+                }
+            }
+            wf[r][j] = v;
+        }
+    }
+
+    const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);
+    HqEpilogue ep = {1.0f, 0.0f, 0.0f, 0.0f, true};
+    if (FUSED) ep = hq_make_epilogue(acc_scale, a.range);
+    int mn = INT_MAX, mx = INT_MIN;
+    unsigned nlo = 0, nhi = 0;
+
+    // ---- staging: task = (input row of the band, group of four pixels); words held between load and store
+    int stw[ST_TASKS][CH];
+    auto band_rows = [&](int band, int &b, int &oy0, int &nrows) {
+        b = band / sa.bands_per_image;
+        oy0 = (band - b * sa.bands_per_image) * sa.rows_out;
+        nrows = min(sa.rows_out, a.Ho - oy0);
+    };
+    auto stage_load = [&](int band) {
+        int b, oy0, nrows;
+        band_rows(band, b, oy0, nrows);
+        const int iy0 = oy0 * a.stride - a.pad;
+#pragma unroll
+        for (int k = 0; k < ST_TASKS; k++) {
+            const int t = tid + k * HQ_THREADS;
+            const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
+            const int iy = iy0 + row;
+            const bool ok = band < sa.nbands && row < sa.in_rows && iy >= 0 && iy < a.H;
+            const int8_t *src = a.A + (ok ? (((size_t)b * a.H + iy) * a.W + 4 * g) * CH : 0);
+#pragma unroll
+            for (int c = 0; c < CH; c++) {
+                const int x = reinterpret_cast<const int *>(src)[c];
+                stw[k][c] = ok ? x : fill;
+            }
+        }
+    };
+    auto stage_store = [&](int buf) {
+#pragma unroll
+        for (int k = 0; k < ST_TASKS; k++) {
+            const int t = tid + k * HQ_THREADS;
+            const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
+            if (row >= sa.in_rows) continue;
+            v4i v;
+            if (CH == 4) {
+                v = v4i{stw[k][0], stw[k][1], stw[k][2], stw[k][3]};
+            } else {
+                const unsigned w0 = (unsigned)stw[k][0], w1 = (unsigned)stw[k][1], w2 = (unsigned)stw[k][2];
+                v[0] = (int)w0;                                         // p0: c0 c1 c2 (+ a byte of p1)
+                v[1] = (int)__builtin_amdgcn_alignbyte(w1, w0, 3);      // p1
+                v[2] = (int)__builtin_amdgcn_alignbyte(w2, w1, 2);      // p2
+                v[3] = (int)(w2 >> 8);                                  // p3
+            }
+            *reinterpret_cast<v4i *>(stem_lds + (size_t)buf * buf_bytes + (size_t)row * sa.LP + (size_t)(a.pad + 4 * g) * 4) = v;
+        }
+    };
+
+    // ---- fragments of one 32-pixel block of the band in buffer `buf`
+    auto load_frags = [&](int buf, int blk, int npix, v4i (&af)[DR_MAXR][DR_MI]) {
+        const int px = min(blk * 32 + (lane & 31), npix - 1);
+        const int orow = (int)hq_magic_div((unsigned)px, a.magic_Wo), ox = px - orow * a.Wo;
+        const int8_t *base = stem_lds + (size_t)buf * buf_bytes + (size_t)(orow * a.stride) * sa.LP + 4 * a.stride * ox + 16 * half;
+#pragma unroll
+        for (int r = 0; r < DR_MAXR; r++) {
+            if (r < a.R) {
+                const int2 lo = *reinterpret_cast<const int2 *>(base + (size_t)r * sa.LP);
+                const int2 hi = *reinterpret_cast<const int2 *>(base + (size_t)r * sa.LP + 8);
+                af[r][0] = v4i{lo.x, lo.y, hi.x, hi.y};
+            }
+        }
+    };
+    auto process = [&](size_t m0, int blk, int npix, const v4i (&af)[DR_MAXR][DR_MI]) {
+        v16i acc[NT];
+#pragma unroll
+        for (int j = 0; j < NT; j++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                const v4i bz = *reinterpret_cast<const v4i *>(bzs + j * 32 + 16 * half + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; e++) acc[j][4 * g + e] = -bz[e];
+            }
+#pragma unroll
+        for (int r = 0; r < DR_MAXR; r++) {
+            if (r < a.R) {
+#pragma unroll
+                for (int j = 0; j < NT; j++)
+                    acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[r][j], af[r][0], acc[j], 0, 0, 0);
+            }
+        }
+        auto epilogue = [&](auto full) {
+            constexpr bool FULL = decltype(full)::value;
+            const int px = blk * 32 + (lane & 31);
+            if (px >= npix) return;
+            const size_t m = m0 + px;
+#pragma unroll
+            for (int j = 0; j < NT; j++) {
+                const int nb = j * 32 + 16 * half;
+                if (nb >= a.N) continue;                           // N % 16 == 0: a group is all in or all out
+                int c[16];
+#pragma unroll
+                for (int e = 0; e < 16; e++) c[e] = acc[j][e];
+                const size_t o = m * a.N + nb;
+                if (FUSED) {
+                    int w[4];
+                    hq_requant_group<16, FULL>(c, ep, mn, mx, nlo, nhi, w);
+                    const v4i v = {w[0], w[1], w[2], w[3]};
+                    *reinterpret_cast<v4i *>(a.out8 + o) = v;
+                } else {
+                    hq_minmax_group<16>(c, mn, mx);
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const v4i v = {c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
+                        *reinterpret_cast<v4i *>(a.out32 + o + 4 * g) = v;
+                    }
+                }
+            }
+        };
+        if (ep.full_grid) epilogue(std::true_type()); else epilogue(std::false_type());
+    };
+
+    // ---- bands of this workgroup: a contiguous run
+    const int per = (sa.nbands + gridDim.x - 1) / gridDim.x;
+    const int band_begin = blockIdx.x * per, band_end = min(sa.nbands, band_begin + per);
+    __syncthreads();                                       // frame and bzs written
+    if (band_begin < band_end) {
+        stage_load(band_begin);
+        stage_store(0);
+    }
+    __syncthreads();
+    for (int band = band_begin; band < band_end; band++) {
+        const int buf = (band - band_begin) & 1;
+        int b, oy0, nrows;
+        band_rows(band, b, oy0, nrows);
+        const int npix = nrows * a.Wo, nblk = (npix + 31) / 32;
+        const size_t m0 = ((size_t)b * a.Ho + oy0) * a.Wo;
+        if (band + 1 < band_end) stage_load(band + 1);
+        v4i afA[DR_MAXR][DR_MI], afB[DR_MAXR][DR_MI];
+        int blk = wave;
+        if (blk < nblk) load_frags(buf, blk, npix, afA);
+        while (blk < nblk) {
+            if (blk + 4 < nblk) load_frags(buf, blk + 4, npix, afB);
+            process(m0, blk, npix, afA);
+            blk += 4;
+            if (blk >= nblk) break;
+            if (blk + 4 < nblk) load_frags(buf, blk + 4, npix, afA);
+            process(m0, blk, npix, afB);
+            blk += 4;
+        }
+        // the other buffer was last read in the previous band, behind whose closing barrier every wavefront is
+        if (band + 1 < band_end) stage_store(buf ^ 1);
+        __syncthreads();
+    }
+    hq_block_stats_commit(mn, mx, nlo, nhi, a.st, red);
+    if (blockIdx.x == 0 && tid == 0) {
+        a.st->acc_scale = acc_scale;
+        atomicAdd((unsigned long long *)&a.st->count, (unsigned long long)a.M * (unsigned long long)a.N);
+        if (FUSED) *a.outq = a.range->qp;
+    }
+}
+
 } // namespace
 
 // Forward layers with 3 or 4 input channels, a filter row of at most 32 bytes, at most DR_MAXR filter
@@ -242,9 +460,48 @@ int hq_try_launch_direct(const hq_problem *p, int dgrad, const int8_t *A, const 
     a.magic_Wo = hq_magic32((unsigned)OW);
     a.magic_Ho = hq_magic32((unsigned)OH);
     a.tiles = (a.M + 32 * DR_MI - 1) / (32 * DR_MI);
+    const bool fused = out32 == nullptr;
+    // staged form: even stride (8-byte aligned fragment reads), rows that start on a word, 16-byte groups of
+    // four pixels, at most 8 taps per filter row (a tap takes 4 bytes of the 32-byte k-step); the band is the largest run of output rows whose input rows fit two buffers of 31 KiB and
+    // whose staging fits ST_TASKS groups per thread
+    if (p->stride % 2 == 0 && p->W % 4 == 0 && p->S <= 8 && (reinterpret_cast<uintptr_t>(A) & 3) == 0) {
+        StemArgs sa;
+        sa.d = a;
+        sa.LP = ((4 * (OW - 1) * p->stride + 32 > 4 * (p->W + p->pad) ? 4 * (OW - 1) * p->stride + 32 : 4 * (p->W + p->pad)) + 15) & ~15;
+        sa.groups = p->W / 4;
+        sa.magic_groups = hq_magic32((unsigned)sa.groups);
+        int rows = 0;
+        for (int r = 1; r <= OH && r <= 64; r++) {
+            const int in_rows = (r - 1) * p->stride + p->R;
+            if ((size_t)in_rows * sa.LP > 31 * 1024 || in_rows * sa.groups > ST_TASKS * HQ_THREADS) break;
+            rows = r;
+        }
+        if (rows >= 1) {
+            // prefer a band height that divides the image and fills whole 128-pixel rounds of the four wavefronts
+            int best = rows;
+            for (int r = rows; r >= 1 && r * 2 > rows; r--)
+                if (OH % r == 0 && (r * OW) % 128 == 0) { best = r; break; }
+            sa.rows_out = best;
+            sa.in_rows = (best - 1) * p->stride + p->R;
+            sa.bands_per_image = (OH + best - 1) / best;
+            sa.nbands = p->B * sa.bands_per_image;
+            const size_t lds = 2 * (size_t)sa.in_rows * sa.LP;
+            int sblocks = sa.nbands < 512 ? sa.nbands : 512;
+            auto slaunch = [&](auto kern) {
+                hipLaunchKernelGGL(kern, dim3(sblocks), dim3(HQ_THREADS), lds, stream, sa);
+            };
+            if (p->C == 4) {
+                if (a.N > 32) { if (fused) slaunch(hq_stem_kernel<2, true, 4>); else slaunch(hq_stem_kernel<2, false, 4>); }
+                else          { if (fused) slaunch(hq_stem_kernel<1, true, 4>); else slaunch(hq_stem_kernel<1, false, 4>); }
+            } else {
+                if (a.N > 32) { if (fused) slaunch(hq_stem_kernel<2, true, 3>); else slaunch(hq_stem_kernel<2, false, 3>); }
+                else          { if (fused) slaunch(hq_stem_kernel<1, true, 3>); else slaunch(hq_stem_kernel<1, false, 3>); }
+            }
+            return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+        }
+    }
     int blocks = (a.tiles + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
-    const bool fused = out32 == nullptr;
     auto launch = [&](auto kern) { hipLaunchKernelGGL(kern, dim3(blocks), dim3(HQ_THREADS), 0, stream, a); };
     if (p->C == 4) {
         if (a.N > 32) { if (fused) launch(hq_direct_kernel<2, true, 4>); else launch(hq_direct_kernel<2, false, 4>); }

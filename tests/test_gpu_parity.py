@@ -120,6 +120,13 @@ RGB = [
     wl.LayerShape("rgb_w1", wl.CONV, 3, 12, 1, 3, 3, 1, 1, 0, 32),       # images one pixel wide
     wl.LayerShape("rgb_1x1", wl.CONV, 1, 5, 7, 3, 1, 1, 1, 0, 16),       # a word holds one pixel and a byte of the next
     wl.conv("rgb_one_pixel", 1, 1, 3, 16, 3),                            # 3 bytes of input in all: every word reaches past the tensor
+    # rows staged in LDS (even stride, width a multiple of 4): several bands per image with a short last one
+    wl.LayerShape("rgb_staged_224x100", wl.CONV, 1, 100, 224, 3, 7, 7, 2, 3, 64),
+    wl.LayerShape("rgb_staged_s2_w28", wl.CONV, 3, 18, 28, 3, 5, 5, 2, 2, 48),   # ragged channel block, one band per image
+    wl.LayerShape("rgb_staged_s4", wl.CONV, 2, 21, 16, 3, 3, 8, 4, 1, 16),       # stride 4, eight taps per filter row (the most)
+    wl.LayerShape("rgb_s4_nine_taps", wl.CONV, 2, 21, 16, 3, 3, 9, 4, 1, 16),    # nine taps: not staged
+    wl.LayerShape("c4_staged_224x60", wl.CONV, 1, 60, 224, 4, 7, 7, 2, 3, 64),   # the same kernel on 4-byte pixels
+    wl.LayerShape("c4_staged_s2_w12", wl.CONV, 5, 9, 12, 4, 3, 8, 2, 0, 32),     # widest filter row (32 bytes), no padding
 ]
 
 
@@ -144,6 +151,8 @@ def test_rgb_first_layer(H, hq, L, g_asym):
         ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
         assert np.array_equal(dWa, ref)
         assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+    if L.C != 3:
+        return
     # the input gradient of a 3-channel layer is refused, not computed wrongly
     with pytest.raises(hq.HqError) as e:
         H.gpu_quantized_op(L, "dgrad", dYd, Wdev, hq.new_range(0.9, True), hq.new_stats(1), "fused")
