@@ -64,6 +64,17 @@ template <int P> __device__ inline v4i read_frag_tr(const int8_t *tile, int lane
     return f;
 }
 
+// The same with the pitch as an argument.
+__device__ inline v4i read_frag_tr_rt(const int8_t *tile, int pitch, int lane)
+{
+    const int j = lane & 15, grp = (lane >> 4) & 1, half = lane >> 5;
+    const int8_t *p = tile + (half * 16 + (j >> 1)) * pitch + 16 * grp + 8 * (j & 1);
+    tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(p));
+    tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(p + 8 * pitch));
+    v4i f = {lo[0], lo[1], hi[0], hi[1]};
+    return f;
+}
+
 // PACKED: layers with fewer than 16 input channels (a network's first layer).  The tile's columns
 // then run over (tap, channel) pairs as they lie in a row of G_W, so a 16-byte chunk of the staged
 // tile holds 16 / C taps (one 4-byte load each) instead of one tap padded with zeros.
@@ -322,6 +333,207 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 // accumulate the same 36 tiles and are added through LDS at the end); inside a group a
 // wavefront owns one 32-channel block of C and taps 0..4 or 5..8 for both 32-blocks of Cout:
 // 7 fragments feed 10 MFMAs.
+// ---------------------------------------------------------------------------------------
+// Weight gradient of a network's first layer (3 or 4 input channels, even stride, W a multiple of 4, at most
+// 8 taps per filter row, at most 64 output channels in multiples of 16) with the input rows staged in LDS.
+// A workgroup walks bands of whole output rows.  The input rows of a band are copied into LDS once, every
+// pixel widened to 4 bytes, inside a frame of zero-point pixels; filter row r of output pixel (oy, ox) is then
+// the 32 bytes at (oy * stride + r) * pitch + 4 * stride * ox: rows of an implicit [pixel][32 columns] matrix
+// with a pitch of 4 * stride bytes, which the transposing LDS read takes as they lie (column 4 s + c of
+// filter row r; the columns of the fourth byte and of taps past S are dropped at the end).  The gradient rows
+// of the band are copied beside them.  Wavefront (wn, wk) owns output channels 32 wn .. 32 wn + 31 and filter
+// rows 4 wk .. 4 wk + 3; sums stay in registers over all bands of the workgroup and leave with one atomic
+// add per value.
+struct WstemArgs {
+    WgradArgs w;
+    int rows_out, in_rows, LP;     // output rows per band, input rows it needs, LDS pitch of an input row
+    int bands_per_image, nbands;
+    int groups;                    // 16-byte groups of four pixels per input row: W / 4
+    unsigned magic_groups, magic_OW;
+    int gpitch, gchunks;           // LDS pitch of a gradient row, 16-byte chunks of a gradient row that are staged
+    int kpad;                      // pixels of a full band rounded up to 32
+};
+constexpr int WS_XT = 3;           // staged groups of four pixels per thread and band
+constexpr int WS_GT = 4;           // staged 16-byte gradient chunks per thread and band
+
+template <int CH>
+__global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const WstemArgs sa)
+{
+    const WgradArgs &a = sa.w;
+    extern __shared__ __attribute__((aligned(16))) int8_t ws_lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wn = wave >> 1, wk = wave & 1;
+    const int zx = a.xq->zero_point;
+    const int fill = (int)((unsigned)(zx & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
+    const int xbytes = sa.in_rows * sa.LP, gbytes = sa.kpad * sa.gpitch, buf_bytes = xbytes + gbytes;
+    int8_t *zero_row = ws_lds + 2 * (size_t)buf_bytes;              // 64 bytes of 0: the source of pixels past a band
+    const bool do_gsum = wk == 0 && zx != 0;                        // column sums of G (times z_x later)
+    const bool do_xsum = wn == 0 && a.gq->zero_point != 0;          // column sums of the gathered input
+
+    // the frame: the input part of both buffers starts as zero-point pixels; staging only writes the W image
+    // columns of a row
+    for (int b = 0; b < 2; b++)
+        for (int q = tid; q < xbytes / 16; q += HQ_THREADS)
+            *reinterpret_cast<v4i *>(ws_lds + (size_t)b * buf_bytes + (size_t)q * 16) = v4i{fill, fill, fill, fill};
+    if (tid < 4) *reinterpret_cast<v4i *>(zero_row + tid * 16) = v4i{0, 0, 0, 0};
+
+    int stx[WS_XT][CH];
+    v4i stg[WS_GT];
+    auto band_rows = [&](int band, int &b, int &oy0, int &nrows) {
+        b = band / sa.bands_per_image;
+        oy0 = (band - b * sa.bands_per_image) * sa.rows_out;
+        nrows = min(sa.rows_out, a.OH - oy0);
+    };
+    auto stage_load = [&](int band) {
+        int b, oy0, nrows;
+        band_rows(band, b, oy0, nrows);
+        const int iy0 = oy0 * a.stride - a.pad;
+#pragma unroll
+        for (int k = 0; k < WS_XT; k++) {
+            const int t = tid + k * HQ_THREADS;
+            const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
+            const int iy = iy0 + row;
+            const bool ok = row < sa.in_rows && iy >= 0 && iy < a.H;
+            const int8_t *src = a.X + (ok ? (((size_t)b * a.H + iy) * a.W + 4 * g) * CH : 0);
+#pragma unroll
+            for (int c = 0; c < CH; c++) {
+                const int x = reinterpret_cast<const int *>(src)[c];
+                stx[k][c] = ok ? x : fill;
+            }
+        }
+        const int npix = nrows * a.OW;
+        const size_t m0 = ((size_t)b * a.OH + oy0) * a.OW;
+#pragma unroll
+        for (int k = 0; k < WS_GT; k++) {
+            const int t = tid + k * HQ_THREADS;
+            const int px = t / sa.gchunks, cc = t - px * sa.gchunks;
+            const bool ok = px < npix && 16 * cc < a.N;
+            const v4i x = *reinterpret_cast<const v4i *>(a.G + (ok ? (m0 + px) * a.N + 16 * cc : 0));
+            stg[k] = ok ? x : v4i{0, 0, 0, 0};
+        }
+    };
+    auto stage_store = [&](int buf) {
+        int8_t *xb = ws_lds + (size_t)buf * buf_bytes, *gb = xb + xbytes;
+#pragma unroll
+        for (int k = 0; k < WS_XT; k++) {
+            const int t = tid + k * HQ_THREADS;
+            const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
+            if (row >= sa.in_rows) continue;
+            v4i v;
+            if (CH == 4) {
+                v = v4i{stx[k][0], stx[k][1], stx[k][2], stx[k][3]};
+            } else {
+                const unsigned w0 = (unsigned)stx[k][0], w1 = (unsigned)stx[k][1], w2 = (unsigned)stx[k][2];
+                v[0] = (int)w0;
+                v[1] = (int)__builtin_amdgcn_alignbyte(w1, w0, 3);
+                v[2] = (int)__builtin_amdgcn_alignbyte(w2, w1, 2);
+                v[3] = (int)(w2 >> 8);
+            }
+            *reinterpret_cast<v4i *>(xb + (size_t)row * sa.LP + (size_t)(a.pad + 4 * g) * 4) = v;
+        }
+#pragma unroll
+        for (int k = 0; k < WS_GT; k++) {
+            const int t = tid + k * HQ_THREADS;
+            const int px = t / sa.gchunks, cc = t - px * sa.gchunks;
+            if (px < sa.kpad) *reinterpret_cast<v4i *>(gb + (size_t)px * sa.gpitch + 16 * cc) = stg[k];
+        }
+    };
+
+    v16i acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[j][e] = 0;
+    int gs = 0, xs[4] = {0, 0, 0, 0};
+
+    const int per = (sa.nbands + gridDim.x - 1) / gridDim.x;
+    const int band_begin = blockIdx.x * per, band_end = min(sa.nbands, band_begin + per);
+    __syncthreads();
+    if (band_begin < band_end) {
+        stage_load(band_begin);
+        stage_store(0);
+    }
+    __syncthreads();
+    // transposing read: lane l hands in the address of 8 bytes (columns 16 * grp + 8 * (j & 1) ..) of pixel row
+    // half * 16 + j / 2 (and of the row 8 further down) and receives column l % 32 of the 16 pixels of its half
+    const int tj = lane & 15, tgrp = (lane >> 4) & 1, thalf = lane >> 5;
+    const int tcol = 16 * tgrp + 8 * (tj & 1);
+    for (int band = band_begin; band < band_end; band++) {
+        const int buf = (band - band_begin) & 1;
+        int b, oy0, nrows;
+        band_rows(band, b, oy0, nrows);
+        const int npix = nrows * a.OW, nks = (npix + 31) / 32;
+        if (band + 1 < band_end) stage_load(band + 1);
+        const int8_t *xb = ws_lds + (size_t)buf * buf_bytes, *gb = xb + xbytes;
+        for (int ks = 0; ks < nks; ks++) {
+            const v4i gf = read_frag_tr_rt(gb + (size_t)ks * 32 * sa.gpitch + wn * 32, sa.gpitch, lane);
+            // this lane's two pixel rows of the k-step
+            const int8_t *pa[2];
+            int pstep[2];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int px = ks * 32 + thalf * 16 + (tj >> 1) + 8 * h;
+                const bool ok = px < npix;
+                const int orow = (int)hq_magic_div((unsigned)(ok ? px : 0), sa.magic_OW), ox = (ok ? px : 0) - orow * a.OW;
+                pa[h] = ok ? xb + (size_t)(orow * a.stride + wk * 4) * sa.LP + 4 * a.stride * ox + tcol : zero_row + tcol;
+                pstep[h] = ok ? sa.LP : 0;
+            }
+            v4i xf[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                if (wk * 4 + j < a.R) {
+                    const tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(pa[0] + j * pstep[0]));
+                    const tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(pa[1] + j * pstep[1]));
+                    xf[j] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+                if (wk * 4 + j < a.R) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gf, xf[j], acc[j], 0, 0, 0);
+            if (do_gsum) {
+#pragma unroll
+                for (int d = 0; d < 4; d++) gs = __builtin_amdgcn_sdot4(gf[d], 0x01010101, gs, false);
+            }
+            if (do_xsum) {
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    if (wk * 4 + j < a.R) {
+#pragma unroll
+                        for (int d = 0; d < 4; d++) xs[j] = __builtin_amdgcn_sdot4(xf[j][d], 0x01010101, xs[j], false);
+                    }
+            }
+        }
+        if (band + 1 < band_end) stage_store(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- flush.  G fragments were the first MFMA operand: lane l holds column l % 32 of the filter row and
+    // output channels 8 * (e / 4) + 4 * (l / 32) + e % 4 of the wavefront's block
+    const size_t krow = (size_t)a.R * a.S * CH;
+    const int col = lane & 31, tap = col >> 2, ch = col & 3;
+    const bool col_ok = tap < a.S && ch < CH;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const int r = wk * 4 + j;
+        if (r >= a.R || !col_ok) continue;
+        const size_t wc = ((size_t)r * a.S + tap) * CH + ch;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            const int n = wn * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            if (n < a.N && acc[j][e] != 0) atomicAdd(a.acc + (size_t)n * krow + wc, acc[j][e]);
+        }
+        if (do_xsum) {
+            const int s = xs[j] + __shfl_xor(xs[j], 32);
+            if (lane < 32 && s != 0) atomicAdd(a.xsum + wc, s);
+        }
+    }
+    if (do_gsum) {
+        const int s = gs + __shfl_xor(gs, 32);
+        const int n = wn * 32 + (lane & 31);
+        if (lane < 32 && n < a.N && s != 0) atomicAdd(a.gsum + n, s);
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 constexpr int WB_THREADS = 512;
 constexpr int WB_P = 96;               // LDS pitch of a 64-channel pixel row (32 mod 64: transposing reads)
@@ -796,6 +1008,59 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
             hipLaunchKernelGGL(wband_finalize_kernel<1>, fgrid, dim3(64), 0, stream, partial, sums, xq, gq,
                                (unsigned)a.M, a.N, a.C, pl.splits, dW, dW_acc, ra);
         return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+    }
+
+    // first layers on even strides: input rows staged in LDS (hq_wgrad_stem_kernel)
+    if ((a.C == 3 || a.C == 4) && p->stride % 2 == 0 && p->W % 4 == 0 && p->S <= 8 && p->R <= 8 && a.N <= 64 &&
+        a.N % 16 == 0 && (reinterpret_cast<uintptr_t>(X) & 3) == 0 && (reinterpret_cast<uintptr_t>(dY) & 15) == 0) {
+        WstemArgs sa;
+        sa.w = a;
+        sa.w.direct = 0;
+        const int lp_reads = 4 * (OW - 1) * p->stride + 32, lp_image = 4 * (p->W + p->pad);
+        sa.LP = ((lp_reads > lp_image ? lp_reads : lp_image) + 15) & ~15;
+        sa.groups = p->W / 4;
+        sa.magic_groups = hq_magic32((unsigned)sa.groups);
+        sa.magic_OW = hq_magic32((unsigned)OW);
+        const int nb32 = (a.N + 31) / 32;
+        sa.gpitch = nb32 * 32 + 32;
+        sa.gchunks = nb32 * 2;
+        int rows = 0;
+        for (int r = 1; r <= OH; r++) {
+            const int in_rows = (r - 1) * p->stride + p->R, kpad = (r * OW + 31) / 32 * 32;
+            if ((size_t)in_rows * sa.LP + (size_t)kpad * sa.gpitch > 39 * 1024 || in_rows * sa.groups > WS_XT * HQ_THREADS ||
+                kpad * sa.gchunks > WS_GT * HQ_THREADS)
+                break;
+            rows = r;
+        }
+        if (rows >= 1 && (unsigned long long)p->B * OH * OW < (1ull << 31)) {
+            sa.rows_out = rows;
+            sa.in_rows = (rows - 1) * p->stride + p->R;
+            sa.kpad = (rows * OW + 31) / 32 * 32;
+            sa.bands_per_image = (OH + rows - 1) / rows;
+            sa.nbands = p->B * sa.bands_per_image;
+            const size_t lds = 2 * ((size_t)sa.in_rows * sa.LP + (size_t)sa.kpad * sa.gpitch) + 64;
+            static bool configured = false;
+            if (!configured) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_wgrad_stem_kernel<3>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess ||
+                    hipFuncSetAttribute(reinterpret_cast<const void *>(hq_wgrad_stem_kernel<4>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess)
+                    return HQ_E_HIP;
+                configured = true;
+            }
+            const size_t zwords = sums_bytes / 4;
+            hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((zwords + 255) / 256 > 1024 ? 1024 : (zwords + 255) / 256)),
+                               dim3(256), 0, stream, a.acc, zwords);
+            const int sblocks = sa.nbands < 512 ? sa.nbands : 512;
+            if (a.C == 3) hipLaunchKernelGGL(hq_wgrad_stem_kernel<3>, dim3(sblocks), dim3(HQ_THREADS), lds, stream, sa);
+            else          hipLaunchKernelGGL(hq_wgrad_stem_kernel<4>, dim3(sblocks), dim3(HQ_THREADS), lds, stream, sa);
+            const size_t total = (size_t)a.N * K;
+            unsigned fb = (unsigned)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
+            ra.first = (int)fb;
+            hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(fb + (unsigned)ra.n), dim3(256), 0, stream, a.acc, a.gsum, a.xsum,
+                               xq, gq, (unsigned)a.M, a.N, (int)K, 0, dW, dW_acc, ra);
+            return hipGetLastError() == hipSuccess ? HQ_OK : HQ_E_HIP;
+        }
     }
 
     const bool big = a.N > 64 && a.C > 64, packed = a.C < 16;
