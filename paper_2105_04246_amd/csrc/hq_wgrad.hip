@@ -347,6 +347,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
 struct WstemArgs {
     WgradArgs w;
     int rows_out, in_rows, LP;     // output rows per band, input rows it needs, LDS pitch of an input row
+    int xrows;                     // input rows a buffer has room for: (rows_out - 1) * stride + 8
     int bands_per_image, nbands;
     int groups;                    // 16-byte groups of four pixels per input row: W / 4
     unsigned magic_groups, magic_OW;
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wn = wave >> 1, wk = wave & 1;
     const int zx = a.xq->zero_point;
     const int fill = (int)((unsigned)(zx & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
-    const int xbytes = sa.in_rows * sa.LP, gbytes = sa.kpad * sa.gpitch, buf_bytes = xbytes + gbytes;
+    const int xbytes = sa.xrows * sa.LP, gbytes = sa.kpad * sa.gpitch, buf_bytes = xbytes + gbytes;
     int8_t *zero_row = ws_lds + 2 * (size_t)buf_bytes;              // 64 bytes of 0: the source of pixels past a band
     const bool do_gsum = wk == 0 && zx != 0;                        // column sums of G (times z_x later)
     const bool do_xsum = wn == 0 && a.gq->zero_point != 0;          // column sums of the gathered input
@@ -458,38 +459,44 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
     // half * 16 + j / 2 (and of the row 8 further down) and receives column l % 32 of the 16 pixels of its half
     const int tj = lane & 15, tgrp = (lane >> 4) & 1, thalf = lane >> 5;
     const int tcol = 16 * tgrp + 8 * (tj & 1);
+    typedef LDS_PTR(int8_t) lds_bytes;
+    const lds_bytes lds0 = (lds_bytes)ws_lds;
+    const unsigned zero_off = 2u * (unsigned)buf_bytes + (unsigned)tcol;
     for (int band = band_begin; band < band_end; band++) {
         const int buf = (band - band_begin) & 1;
         int b, oy0, nrows;
         band_rows(band, b, oy0, nrows);
         const int npix = nrows * a.OW, nks = (npix + 31) / 32;
         if (band + 1 < band_end) stage_load(band + 1);
-        const int8_t *xb = ws_lds + (size_t)buf * buf_bytes, *gb = xb + xbytes;
-        for (int ks = 0; ks < nks; ks++) {
-            const v4i gf = read_frag_tr_rt(gb + (size_t)ks * 32 * sa.gpitch + wn * 32, sa.gpitch, lane);
-            // this lane's two pixel rows of the k-step
-            const int8_t *pa[2];
-            int pstep[2];
+        const unsigned xoff = (unsigned)buf * (unsigned)buf_bytes, goff = xoff + (unsigned)xbytes;
+        // fragments of k-step ks: the gradient block and the wavefront's four filter rows (rows past R read rows
+        // of the buffer that exist but hold anything: their sums are dropped at the end)
+        auto load_frags = [&](int ks, v4i &gf, v4i (&xf)[4]) {
+            const unsigned g0 = goff + (unsigned)((ks * 32 + thalf * 16 + (tj >> 1)) * sa.gpitch + wn * 32 + tcol);
+            const tr_v2i glo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(lds0 + g0));
+            const tr_v2i ghi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(lds0 + g0 + 8 * sa.gpitch));
+            gf = v4i{glo[0], glo[1], ghi[0], ghi[1]};
+            unsigned pa[2], pstep[2];
 #pragma unroll
             for (int h = 0; h < 2; h++) {
                 const int px = ks * 32 + thalf * 16 + (tj >> 1) + 8 * h;
                 const bool ok = px < npix;
-                const int orow = (int)hq_magic_div((unsigned)(ok ? px : 0), sa.magic_OW), ox = (ok ? px : 0) - orow * a.OW;
-                pa[h] = ok ? xb + (size_t)(orow * a.stride + wk * 4) * sa.LP + 4 * a.stride * ox + tcol : zero_row + tcol;
-                pstep[h] = ok ? sa.LP : 0;
+                const unsigned q = ok ? (unsigned)px : 0u;
+                const unsigned orow = hq_magic_div(q, sa.magic_OW), ox = q - orow * (unsigned)a.OW;
+                pa[h] = ok ? xoff + (orow * (unsigned)a.stride + (unsigned)(wk * 4)) * (unsigned)sa.LP + 4u * (unsigned)a.stride * ox + (unsigned)tcol
+                           : zero_off;
+                pstep[h] = ok ? (unsigned)sa.LP : 0u;
             }
-            v4i xf[4];
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                if (wk * 4 + j < a.R) {
-                    const tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(pa[0] + j * pstep[0]));
-                    const tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(pa[1] + j * pstep[1]));
-                    xf[j] = v4i{lo[0], lo[1], hi[0], hi[1]};
-                }
+                const tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(lds0 + pa[0] + j * pstep[0]));
+                const tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(lds0 + pa[1] + j * pstep[1]));
+                xf[j] = v4i{lo[0], lo[1], hi[0], hi[1]};
             }
+        };
+        auto multiply = [&](const v4i &gf, const v4i (&xf)[4]) {
 #pragma unroll
-            for (int j = 0; j < 4; j++)
-                if (wk * 4 + j < a.R) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gf, xf[j], acc[j], 0, 0, 0);
+            for (int j = 0; j < 4; j++) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gf, xf[j], acc[j], 0, 0, 0);
             if (do_gsum) {
 #pragma unroll
                 for (int d = 0; d < 4; d++) gs = __builtin_amdgcn_sdot4(gf[d], 0x01010101, gs, false);
@@ -497,11 +504,19 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
             if (do_xsum) {
 #pragma unroll
                 for (int j = 0; j < 4; j++)
-                    if (wk * 4 + j < a.R) {
 #pragma unroll
-                        for (int d = 0; d < 4; d++) xs[j] = __builtin_amdgcn_sdot4(xf[j][d], 0x01010101, xs[j], false);
-                    }
+                    for (int d = 0; d < 4; d++) xs[j] = __builtin_amdgcn_sdot4(xf[j][d], 0x01010101, xs[j], false);
             }
+        };
+        // two fragment sets: the next k-step's reads are on their way while this one is multiplied
+        v4i gfA, gfB, xfA[4], xfB[4];
+        if (nks > 0) load_frags(0, gfA, xfA);
+        for (int ks = 0; ks < nks; ks += 2) {
+            if (ks + 1 < nks) load_frags(ks + 1, gfB, xfB);
+            multiply(gfA, xfA);
+            if (ks + 1 >= nks) break;
+            if (ks + 2 < nks) load_frags(ks + 2, gfA, xfA);
+            multiply(gfB, xfB);
         }
         if (band + 1 < band_end) stage_store(buf ^ 1);
         __syncthreads();
@@ -1027,7 +1042,7 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
         int rows = 0;
         for (int r = 1; r <= OH; r++) {
             const int in_rows = (r - 1) * p->stride + p->R, kpad = (r * OW + 31) / 32 * 32;
-            if ((size_t)in_rows * sa.LP + (size_t)kpad * sa.gpitch > 39 * 1024 || in_rows * sa.groups > WS_XT * HQ_THREADS ||
+            if ((size_t)((r - 1) * p->stride + 8) * sa.LP + (size_t)kpad * sa.gpitch > 39 * 1024 || in_rows * sa.groups > WS_XT * HQ_THREADS ||
                 kpad * sa.gchunks > WS_GT * HQ_THREADS)
                 break;
             rows = r;
@@ -1035,10 +1050,11 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
         if (rows >= 1 && (unsigned long long)p->B * OH * OW < (1ull << 31)) {
             sa.rows_out = rows;
             sa.in_rows = (rows - 1) * p->stride + p->R;
+            sa.xrows = (rows - 1) * p->stride + 8;
             sa.kpad = (rows * OW + 31) / 32 * 32;
             sa.bands_per_image = (OH + rows - 1) / rows;
             sa.nbands = p->B * sa.bands_per_image;
-            const size_t lds = 2 * ((size_t)sa.in_rows * sa.LP + (size_t)sa.kpad * sa.gpitch) + 64;
+            const size_t lds = 2 * ((size_t)sa.xrows * sa.LP + (size_t)sa.kpad * sa.gpitch) + 64;
             static bool configured = false;
             if (!configured) {
                 if (hipFuncSetAttribute(reinterpret_cast<const void *>(hq_wgrad_stem_kernel<3>),
