@@ -136,23 +136,32 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             wrow_ok[k] = n < a.N;
             wsrc[k] = a.Bw + (size_t)(wrow_ok[k] ? n : 0) * wrow + ck * 16;
         }
-        auto issue_weights = [&](int stage, int buf) {
+        // The weights go through registers (two steps = four 16-byte loads per thread, requested at the start of a
+        // stage, written to LDS at its end): the direct-to-LDS path moves about 20 bytes per clock and compute
+        // unit, register loads 30 to 35, and a stage of two workgroups needs 32 KB of weights per 2048 clocks.
+        v4i wreg[2][2];
+        auto load_weights = [&](int stage) {
 #pragma unroll
             for (int u = 0; u < 2; u++) {
-                const int step = 2 * stage + u;
-                if (step >= nsteps) break;
+                const int step = min(2 * stage + u, nsteps - 1);
                 const int cchunk = step / 9, tap = step - cchunk * 9;
                 const int woff = (a.flip ? 8 - tap : tap) * a.C + cchunk * BW_CK;
 #pragma unroll
-                for (int k = 0; k < 2; k++) {
-                    int8_t *dst = Wl + (size_t)(buf * 2 + u) * BW_BN * BW_CK + (size_t)(HQ_THREADS * k + wave * 64) * 16;
-                    hq_global_to_lds16(wrow_ok[k] ? wsrc[k] + woff : zero_src, dst);
-                }
+                for (int k = 0; k < 2; k++)
+                    wreg[u][k] = *(const __attribute__((address_space(1))) v4i *)(wrow_ok[k] ? wsrc[k] + woff : zero_src);
             }
+        };
+        auto store_weights = [&](int buf) {
+#pragma unroll
+            for (int u = 0; u < 2; u++)
+#pragma unroll
+                for (int k = 0; k < 2; k++)
+                    *reinterpret_cast<v4i *>(Wl + (size_t)(buf * 2 + u) * BW_BN * BW_CK + (size_t)(HQ_THREADS * k + tid) * 16) = wreg[u][k];
         };
 
         issue_patch(0, 0);
-        issue_weights(0, 0);
+        load_weights(0);
+        store_weights(0);
 
         // ---- this lane's two pixels: patch row of tap (0, 0), and whether they exist
         int prow[2];
@@ -224,9 +233,9 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
                     for (int j = 0; j < BW_NT; j++)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], af[i], acc[i][j], 0, 0, 0);
             };
+            if (s + 1 < nstages) load_weights(s + 1);
             if (active) {
                 load_frags(0, wfA, afA);
-                if (s + 1 < nstages) issue_weights(s + 1, (s + 1) & 1);
                 if (patch_now) issue_patch(c0 + 1, (c0 + 1) & 1);
                 load_frags(1, wfB, afB);
                 __builtin_amdgcn_sched_barrier(0);
@@ -244,9 +253,10 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
                 }
                 mfmas(wfB, afB);
             } else {
-                if (s + 1 < nstages) issue_weights(s + 1, (s + 1) & 1);
                 if (patch_now) issue_patch(c0 + 1, (c0 + 1) & 1);
             }
+            // the other weight buffer was last read in the previous stage, behind whose barrier every wavefront is
+            if (s + 1 < nstages) store_weights((s + 1) & 1);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
