@@ -162,14 +162,18 @@ class DeviceLayer(Layer):
 def kernel_family(wl, L, op):
     """Name of the kernel the library's dispatch picks for one launch (mirrors the rules of hq_api.hip / the launchers)."""
     k3 = L.kind == wl.CONV and L.R == 3 and L.S == 3 and L.stride == 1 and L.pad == 1
+    first = L.kind == wl.CONV and L.C in (3, 4)
+    staged = first and L.stride % 2 == 0 and L.W % 4 == 0 and L.S <= 8        # input rows staged in LDS
     if op == "wgrad":
         if k3 and L.C % 64 == 0 and L.Cout % 64 == 0:
             return "hq_wgrad_band_kernel + wband_finalize_kernel"
+        if staged and L.R <= 8 and L.Cout <= 64 and L.Cout % 16 == 0:
+            return "hq_wgrad_stem_kernel + wgrad_finalize_kernel"
         return "hq_wgrad_kernel + wgrad_finalize_kernel"
     cin = L.Cout if op == "dgrad" else L.C
     cout = L.C if op == "dgrad" else L.Cout
-    if op == "fwd" and L.kind == wl.CONV and L.C in (3, 4):
-        return "hq_direct_kernel"
+    if op == "fwd" and first:
+        return "hq_stem_kernel" if staged else "hq_direct_kernel"
     if k3 and cin % 64 == 0 and cin >= 128 and cout >= 128:
         return "hq_bandw_kernel"
     if k3 and cin == 64:

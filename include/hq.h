@@ -98,9 +98,12 @@ typedef struct {
  * Supported: C % 4 == 0 and Cout % 4 == 0 for HQ_LINEAR / HQ_CONV2D (full-rate path when the
  * reduced channel count is a multiple of 16); C % 4 == 0 for HQ_DEPTHWISE; B*H*W and
  * B*OH*OW below 2^31.  In addition HQ_CONV2D takes C == 3 (a network's first layer on RGB images,
- * pixels of 3 bytes) in hq_gemm_fwd, hq_gemm_dynamic (forward), hq_gemm_wgrad and
- * hq_weight_prepare, for filters of at most 7 rows and S * 3 <= 32 bytes per row and Cout a
- * multiple of 16 up to 64; the input gradient of such a layer is refused (HQ_E_BADSHAPE).      */
+ * pixels of 3 bytes) with a filter row of S * 3 <= 32 bytes:
+ *   hq_gemm_fwd, hq_gemm_dynamic (forward)   filters of at most 7 rows, Cout a multiple of 16 up to 64;
+ *   hq_gemm_wgrad, hq_gemm_wgrad_update,
+ *   hq_gemm_wgrad_static, hq_weight_prepare  any R, any Cout that is a multiple of 4;
+ *   hq_gemm_dgrad, the stochastic-rounding entries   refused: a first layer has no input gradient.
+ * Anything outside these limits returns HQ_E_BADSHAPE.                                          */
 typedef struct {
     int32_t kind;
     int32_t B, H, W, C;

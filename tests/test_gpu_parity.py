@@ -159,6 +159,25 @@ def test_rgb_first_layer(H, hq, L, g_asym):
     assert e.value.code == hq.HQ_E_BADSHAPE
 
 
+@pytest.mark.parametrize("L", [wl.LayerShape("rgb_wgrad_9x2_n72", wl.CONV, 2, 17, 11, 3, 9, 2, 1, 1, 72),     # more filter rows and output channels than the forward kernel takes
+                               wl.LayerShape("rgb_wgrad_2x10_n4", wl.CONV, 1, 6, 24, 3, 2, 10, 2, 0, 4)], ids=lambda l: l.name)
+def test_rgb_weight_gradient_beyond_the_forward_limits(H, hq, L):
+    """The weight gradient of a 3-channel layer takes any filter height and any output channel count that is a
+    multiple of 4; the forward call refuses the same shape instead of computing it wrongly."""
+    g = np.random.default_rng([78, L.R])
+    X = wl.normal_image(g, wl.in_shape(L))
+    dY = wl.to_asymmetric_codes(g.laplace(0, 1e-3, wl.out_shape(L)).astype(np.float32) + np.float32(4e-4))
+    Xd, dYd = H.DevTensor(X), H.DevTensor(dY)
+    dW, dWa = H.gpu_wgrad(L, Xd, dYd)
+    ref = oracle.wgrad(H.oracle_problem(L), X.codes, X.zero_point, dY.codes, dY.zero_point)
+    assert np.array_equal(dWa, ref)
+    assert np.array_equal(dW, oracle.wgrad_scale(ref, X.scale, dY.scale))
+    Wdev = H.DevWeights(L, wl.he_weight(g, L))
+    with pytest.raises(hq.HqError) as e:
+        H.gpu_quantized_op(L, "fwd", Xd, Wdev, hq.new_range(0.9, False), hq.new_stats(1), "fused")
+    assert e.value.code == hq.HQ_E_BADSHAPE
+
+
 def random_shapes(n, seed):
     """Seeded random layer shapes inside the documented limits (channels % 4 == 0, pad < filter size,
     at least one output pixel): non-square images and filters, strides 1..3, channel counts around the
