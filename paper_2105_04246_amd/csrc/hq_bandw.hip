@@ -144,11 +144,12 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
 #pragma unroll
             for (int u = 0; u < 2; u++) {
                 const int step = min(2 * stage + u, nsteps - 1);
+                const bool real = 2 * stage + u < nsteps;              // an odd count of steps ends on a step of zero weights
                 const int cchunk = step / 9, tap = step - cchunk * 9;
                 const int woff = (a.flip ? 8 - tap : tap) * a.C + cchunk * BW_CK;
 #pragma unroll
                 for (int k = 0; k < 2; k++)
-                    wreg[u][k] = *(const __attribute__((address_space(1))) v4i *)(wrow_ok[k] ? wsrc[k] + woff : zero_src);
+                    wreg[u][k] = *(const __attribute__((address_space(1))) v4i *)(wrow_ok[k] && real ? wsrc[k] + woff : zero_src);
             }
         };
         auto store_weights = [&](int buf) {
@@ -200,7 +201,6 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             // four k-steps (two per (tap, chunk) step) with two fragment register sets: the fragments of
             // k-step kk + 1 are requested before the MFMAs of k-step kk are issued, and the stage's first
             // fragments before the next stage's loads, whose address arithmetic then runs under their latency
-            const bool full = 2 * s + 1 < nsteps;
             const int c0 = (2 * s) / 9, t0 = 2 * s - c0 * 9;
             // the next chunk's patch is requested by the first stage that lies wholly inside this chunk:
             // every reader of the buffer it overwrites finished before that stage's opening barrier
@@ -235,22 +235,33 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             };
             if (s + 1 < nstages) load_weights(s + 1);
             if (active) {
+                // the fragment reads of k-step kk + 1 and their address arithmetic are dealt between the MFMAs of
+                // k-step kk (a wavefront issues in order: an MFMA holds the matrix pipe for 32 cycles, in which it
+                // can issue seven other instructions)
+                auto interleave = [&]() {
+#pragma unroll
+                    for (int q = 0; q < 6; q++) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);     // two vector ALU instructions
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                };
                 load_frags(0, wfA, afA);
                 if (patch_now) issue_patch(c0 + 1, (c0 + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
                 load_frags(1, wfB, afB);
-                __builtin_amdgcn_sched_barrier(0);
                 mfmas(wfA, afA);
+                interleave();
                 __builtin_amdgcn_sched_barrier(0);
-                if (full) {
-                    load_frags(2, wfA, afA);
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfmas(wfB, afB);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_frags(3, wfB, afB);
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfmas(wfA, afA);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                load_frags(2, wfA, afA);
+                mfmas(wfB, afB);
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(3, wfB, afB);
+                mfmas(wfA, afA);
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
                 mfmas(wfB, afB);
             } else {
                 if (patch_now) issue_patch(c0 + 1, (c0 + 1) & 1);
