@@ -385,17 +385,36 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
         oy0 = (band - b * sa.bands_per_image) * sa.rows_out;
         nrows = min(sa.rows_out, a.OH - oy0);
     };
+    // staging plan of this thread, the same for every band: its groups of four input pixels (input row of the
+    // band, source offset from the band's first input row, LDS offset) and its 16-byte chunks of the gradient
+    int x_row[WS_XT], x_src[WS_XT], x_dst[WS_XT];
+#pragma unroll
+    for (int k = 0; k < WS_XT; k++) {
+        const int t = tid + k * HQ_THREADS;
+        const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
+        x_row[k] = row < sa.in_rows ? row : -1;
+        x_src[k] = (row * a.W + 4 * g) * CH;
+        x_dst[k] = row * sa.LP + (a.pad + 4 * g) * 4;
+    }
+    int g_px[WS_GT], g_src[WS_GT], g_dst[WS_GT];
+#pragma unroll
+    for (int k = 0; k < WS_GT; k++) {
+        const int t = tid + k * HQ_THREADS;
+        const int px = t / sa.gchunks, cc = t - px * sa.gchunks;
+        g_px[k] = px < sa.kpad && 16 * cc < a.N ? px : 0x7fffffff;        // never below a band's pixel count
+        g_src[k] = px * a.N + 16 * cc;
+        g_dst[k] = px < sa.kpad ? px * sa.gpitch + 16 * cc : -1;
+    }
     auto stage_load = [&](int band) {
         int b, oy0, nrows;
         band_rows(band, b, oy0, nrows);
         const int iy0 = oy0 * a.stride - a.pad;
+        const int8_t *xrow0 = a.X + ((ptrdiff_t)b * a.H + iy0) * a.W * CH;   // (may lie before the tensor: only rows inside are read)
 #pragma unroll
         for (int k = 0; k < WS_XT; k++) {
-            const int t = tid + k * HQ_THREADS;
-            const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
-            const int iy = iy0 + row;
-            const bool ok = row < sa.in_rows && iy >= 0 && iy < a.H;
-            const int8_t *src = a.X + (ok ? (((size_t)b * a.H + iy) * a.W + 4 * g) * CH : 0);
+            const int iy = iy0 + x_row[k];
+            const bool ok = x_row[k] >= 0 && iy >= 0 && iy < a.H;
+            const int8_t *src = ok ? xrow0 + x_src[k] : a.X;
 #pragma unroll
             for (int c = 0; c < CH; c++) {
                 const int x = reinterpret_cast<const int *>(src)[c];
@@ -403,13 +422,11 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
             }
         }
         const int npix = nrows * a.OW;
-        const size_t m0 = ((size_t)b * a.OH + oy0) * a.OW;
+        const int8_t *g0 = a.G + ((size_t)b * a.OH + oy0) * a.OW * a.N;
 #pragma unroll
         for (int k = 0; k < WS_GT; k++) {
-            const int t = tid + k * HQ_THREADS;
-            const int px = t / sa.gchunks, cc = t - px * sa.gchunks;
-            const bool ok = px < npix && 16 * cc < a.N;
-            const v4i x = *reinterpret_cast<const v4i *>(a.G + (ok ? (m0 + px) * a.N + 16 * cc : 0));
+            const bool ok = g_px[k] < npix;
+            const v4i x = *reinterpret_cast<const v4i *>(ok ? g0 + g_src[k] : a.G);
             stg[k] = ok ? x : v4i{0, 0, 0, 0};
         }
     };
@@ -417,9 +434,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
         int8_t *xb = ws_lds + (size_t)buf * buf_bytes, *gb = xb + xbytes;
 #pragma unroll
         for (int k = 0; k < WS_XT; k++) {
-            const int t = tid + k * HQ_THREADS;
-            const int row = (int)hq_magic_div((unsigned)t, sa.magic_groups), g = t - row * sa.groups;
-            if (row >= sa.in_rows) continue;
+            if (x_row[k] < 0) continue;
             v4i v;
             if (CH == 4) {
                 v = v4i{stx[k][0], stx[k][1], stx[k][2], stx[k][3]};
@@ -430,14 +445,11 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_wgrad_stem_kernel(const Wste
                 v[2] = (int)__builtin_amdgcn_alignbyte(w2, w1, 2);
                 v[3] = (int)(w2 >> 8);
             }
-            *reinterpret_cast<v4i *>(xb + (size_t)row * sa.LP + (size_t)(a.pad + 4 * g) * 4) = v;
+            *reinterpret_cast<v4i *>(xb + x_dst[k]) = v;
         }
 #pragma unroll
-        for (int k = 0; k < WS_GT; k++) {
-            const int t = tid + k * HQ_THREADS;
-            const int px = t / sa.gchunks, cc = t - px * sa.gchunks;
-            if (px < sa.kpad) *reinterpret_cast<v4i *>(gb + (size_t)px * sa.gpitch + 16 * cc) = stg[k];
-        }
+        for (int k = 0; k < WS_GT; k++)
+            if (g_dst[k] >= 0) *reinterpret_cast<v4i *>(gb + g_dst[k]) = stg[k];
     };
 
     v16i acc[4];
