@@ -877,11 +877,14 @@ __global__ __launch_bounds__(64 * TY) void wband_finalize_kernel(const int32_t *
     const int *gsrc = sums + (size_t)(np * cparts) * 2 * WB_SUMS + (n0 & 63) + (tx & 3);    // workgroups with cp == 0
     v4i sum = {0, 0, 0, 0};
     int xs = 0, gs = 0;
+    // a column sum is only ever multiplied by the other operand's zero point: with that at 0 it is neither formed
+    // by the band kernel nor read here (uniform branches)
+    const bool need_xs = gq->zero_point != 0, need_gs = xq->zero_point != 0;
     for (int s = ty; s < splits; s += TY) {
         sum += src[(size_t)s * parts * WB_SLOT_V4];
         const size_t so = (size_t)s * parts * 2 * WB_SUMS;
-        xs += xsrc[so] + xsrc[so + WB_SUMS];
-        if (tx < 4) gs += gsrc[so] + gsrc[so + WB_SUMS];
+        if (need_xs) xs += xsrc[so] + xsrc[so + WB_SUMS];
+        if (need_gs && tx < 4) gs += gsrc[so] + gsrc[so + WB_SUMS];
     }
     sh[ty][tx] = sum; shx[ty][tx] = xs;
     if (tx < 4) shg[ty][tx] = gs;
