@@ -79,7 +79,6 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // scalar: branches on it are uniform
     const int za = a.aq->zero_point;
-    const int fillw = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const int8_t *fill_src = reinterpret_cast<const int8_t *>(bw_fill_rows.w[za & 0xff]);
     const int8_t *zero_src = reinterpret_cast<const int8_t *>(bw_fill_rows.w[0]);
     const float acc_scale = __fmul_rn(a.aq->scale, a.bq->scale);

@@ -249,13 +249,13 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_stem_kernel(const StemArgs s
     const DirectArgs &a = sa.d;
     extern __shared__ __attribute__((aligned(16))) int8_t stem_lds[];
     __shared__ int red[4 * (HQ_THREADS / 64)];
-    __shared__ __attribute__((aligned(16))) int bzs[32 * NT];       // z_a * bsum[n]
+    __shared__ __attribute__((aligned(16))) int bzs[32 * NT];       // -z_a * bsum[n]: what the accumulators start from
     const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int za = a.aq->zero_point;
     const int fill = (int)((unsigned)(za & 0xff) * 0x01010101u);   // unsigned: the product may set bit 31
     const int buf_bytes = sa.in_rows * sa.LP;
-    if (tid < 32 * NT) bzs[tid] = tid < a.N ? za * a.bsum[tid] : 0;
+    if (tid < 32 * NT) bzs[tid] = tid < a.N ? -(za * a.bsum[tid]) : 0;
     // the frame: every word of both buffers starts as zero-point pixels; staging only ever writes the W image
     // columns of a row, so the columns left and right of the image keep this value
     for (int q = tid; q < 2 * buf_bytes / 16; q += HQ_THREADS)
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_stem_kernel(const StemArgs s
             for (int g = 0; g < 4; g++) {
                 const v4i bz = *reinterpret_cast<const v4i *>(bzs + j * 32 + 16 * half + 4 * g);
 #pragma unroll
-                for (int e = 0; e < 4; e++) acc[j][4 * g + e] = -bz[e];
+                for (int e = 0; e < 4; e++) acc[j][4 * g + e] = bz[e];
             }
 #pragma unroll
         for (int r = 0; r < DR_MAXR; r++) {

@@ -64,17 +64,6 @@ template <int P> __device__ inline v4i read_frag_tr(const int8_t *tile, int lane
     return f;
 }
 
-// The same with the pitch as an argument.
-__device__ inline v4i read_frag_tr_rt(const int8_t *tile, int pitch, int lane)
-{
-    const int j = lane & 15, grp = (lane >> 4) & 1, half = lane >> 5;
-    const int8_t *p = tile + (half * 16 + (j >> 1)) * pitch + 16 * grp + 8 * (j & 1);
-    tr_v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(p));
-    tr_v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(tr_v2i))(p + 8 * pitch));
-    v4i f = {lo[0], lo[1], hi[0], hi[1]};
-    return f;
-}
-
 // PACKED: layers with fewer than 16 input channels (a network's first layer).  The tile's columns
 // then run over (tap, channel) pairs as they lie in a row of G_W, so a 16-byte chunk of the staged
 // tile holds 16 / C taps (one 4-byte load each) instead of one tap padded with zeros.
