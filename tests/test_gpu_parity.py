@@ -111,6 +111,22 @@ def test_small_shapes_all_ops(H, hq, L):
 # ---------------------------------------------------------------------------------------
 # 3-channel (RGB) first layers: forward (fused and dynamic) and weight gradient; 3-byte pixels
 # ---------------------------------------------------------------------------------------
+def random_staged_first_layers(n, seed, C):
+    """Seeded random first layers of the kind whose input rows are staged in LDS: even stride, width a multiple
+    of 4, at most 8 taps per filter row and 7 filter rows, 16 .. 64 output channels."""
+    g = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < n:
+        R, S = int(g.integers(1, 8)), int(g.integers(1, 9))
+        L = wl.LayerShape("staged%d_c%d" % (len(shapes), C), wl.CONV, int(g.choice([1, 2, 3, 5])), int(g.integers(4, 60)),
+                          4 * int(g.integers(2, 40)), C, R, S, int(g.choice([2, 2, 4])), int(g.integers(0, min(R, S))),
+                          16 * int(g.integers(1, 5)))
+        OH, OW = (L.H + 2 * L.pad - L.R) // L.stride + 1, (L.W + 2 * L.pad - L.S) // L.stride + 1
+        if OH >= 1 and OW >= 1 and L.B * OH * OW * L.Cout * L.R * L.S * C < 4e8:
+            shapes.append(L)
+    return shapes
+
+
 RGB = [
     wl.conv("rgb_stem", 2, 37, 3, 64, 7, stride=2),                      # the ResNet stem's geometry on a small odd image
     wl.conv("rgb_3x3", 3, 20, 3, 64, 3),                                 # VGG's first layer
@@ -130,7 +146,10 @@ RGB = [
 ]
 
 
-@pytest.mark.parametrize("L", RGB, ids=[l.name for l in RGB])
+RGB += random_staged_first_layers(16, 31, 3)
+
+
+@pytest.mark.parametrize("L", RGB, ids=["%s_b%d_%dx%d_%dx%d_s%d_p%d_n%d" % (l.name, l.B, l.H, l.W, l.R, l.S, l.stride, l.pad, l.Cout) for l in RGB])
 @pytest.mark.parametrize("g_asym", [False, True], ids=["gsym", "gasym"])
 def test_rgb_first_layer(H, hq, L, g_asym):
     y_track = H.TensorTrack(0.9, False)
@@ -262,7 +281,8 @@ def random_wide_band_shapes(n, seed):
     return shapes
 
 
-RANDOM = random_shapes(40, 20260) + random_shapes(50, 7) + random_fast_path_shapes(48, 11) + random_wide_band_shapes(12, 5)
+RANDOM = (random_shapes(40, 20260) + random_shapes(50, 7) + random_fast_path_shapes(48, 11) + random_wide_band_shapes(12, 5) +
+          random_staged_first_layers(16, 32, 4))
 
 
 @pytest.mark.parametrize("L", RANDOM, ids=["%s_b%d_%dx%d_c%d_%dx%d_s%d_p%d_n%d" % (l.name, l.B, l.H, l.W, l.C, l.R, l.S, l.stride, l.pad, l.Cout)
