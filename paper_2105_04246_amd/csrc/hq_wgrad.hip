@@ -37,6 +37,8 @@ struct WgradArgs {
     int xt, yt, splits;            // tile columns (taps * ctiles), tile rows, pixel splits
     int g16, x16;                  // rows of G / X are 16-byte aligned (N % 16 == 0 / C % 16 == 0)
     int direct;                    // splits == 1: every sum has one writer, plain stores into acc (not zeroed)
+    unsigned magic_OW, magic_OH;   // ceil(2^32 / d) for the pixel decode, or 0, 0 with magic_ok == 0: plain division
+    int magic_ok;
 };
 
 __device__ inline v4i load16(const int8_t *p, int nbytes, bool aligned16)
@@ -189,7 +191,13 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
                 while (pk_ow[i] >= a.OW) { pk_ow[i] -= a.OW; pk_oh[i]++; }
                 while (pk_oh[i] >= a.OH) { pk_oh[i] -= a.OH; pk_b[i]++; }
             } else if (m < m_end && c < a.C) {
-                const int ow = m % a.OW, oh = (m / a.OW) % a.OH, b = m / (a.OW * a.OH);
+                int ow, oh, b;                                    // (a division costs some 40 instructions, three a stage's worth of MFMAs)
+                if (a.magic_ok) {
+                    const unsigned t = hq_magic_div((unsigned)m, a.magic_OW), bb = hq_magic_div(t, a.magic_OH);
+                    ow = (int)((unsigned)m - t * (unsigned)a.OW); oh = (int)(t - bb * (unsigned)a.OH); b = (int)bb;
+                } else {
+                    ow = m % a.OW; oh = (m / a.OW) % a.OH; b = m / (a.OW * a.OH);
+                }
                 const int iy = oh * a.stride - a.pad + tr, ix = ow * a.stride - a.pad + ts;
                 if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) {
                     v = load16(a.X + (((size_t)b * a.H + iy) * a.W + ix) * a.C + c, a.C - c, a.x16);
@@ -1007,6 +1015,9 @@ int hq_launch_wgrad(const hq_problem *p, const int8_t *X, const hq_qparams *xq, 
     a.M = p->B * OH * OW; a.N = p->Cout; a.C = p->C;
     a.R = p->R; a.S = p->S; a.H = p->H; a.W = p->W; a.OH = OH; a.OW = OW; a.stride = p->stride; a.pad = p->pad;
     a.g16 = (a.N % 16) == 0; a.x16 = (a.C % 16) == 0;
+    a.magic_ok = (unsigned long long)a.M * (unsigned long long)(OW > OH ? OW : OH) < (1ull << 32);   // hq_magic_div's range
+    a.magic_OW = a.magic_ok ? hq_magic32((unsigned)OW) : 0u;
+    a.magic_OH = a.magic_ok ? hq_magic32((unsigned)OH) : 0u;
 
     const WbandPlan pl = wband_plan(p);
     if (pl.covered) {
