@@ -37,6 +37,19 @@
 
 namespace {
 
+// 16-byte rows of one repeated byte value, indexed by that value: the source of the lanes of a direct-to-LDS
+// load that have no source of their own (padding taps: zero-point code; rows and chunks past the end: 0), so
+// that a stage's loads need no branch per row.
+struct GemmFillRows {
+    unsigned w[256][4];
+    constexpr GemmFillRows() : w()
+    {
+        for (int v = 0; v < 256; v++)
+            for (int k = 0; k < 4; k++) w[v][k] = (unsigned)v * 0x01010101u;
+    }
+};
+__device__ const GemmFillRows gemm_fill_rows = GemmFillRows();
+
 struct GemmArgs {
     const int8_t *A, *Bw;
     const int32_t *bsum;
@@ -256,11 +269,12 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
 
     // Aligned form: global -> LDS without passing through registers (global_load_lds_dwordx4: lane l
     // of a wavefront writes 16 bytes at base + 16 * l).  Lanes without a source (padding taps, rows
-    // past the end, chunks past the end of K) store the fill value themselves.
+    // past the end, chunks past the end of K) read a row of the fill table instead: no branch per row.
     auto issue_stage = [&](int buf) {
         const bool chunk_ok = chunk < nchunks;
         const int coff = c16 * 16;
-        const v4i fillv = {fill, fill, fill, fill}, zerov = {0, 0, 0, 0};
+        const int8_t *fill_src = reinterpret_cast<const int8_t *>(gemm_fill_rows.w[za & 0xff]);
+        const int8_t *zero_src = reinterpret_cast<const int8_t *>(gemm_fill_rows.w[0]);
         const int tapoff = (CLASSED ? -(tr * a.Ws + ts) : tr * a.Ws + ts) * a.Cs + coff;   // from the row's tap (0, 0)
 #pragma unroll
         for (int i = 0; i < AROWS; i++) {
@@ -272,25 +286,17 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
                 ok = chunk_ok && arow_ok[i] && iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws;
             }
             int8_t *dst = As + (size_t)buf * BM * BKB + 4096 * i + (tid & ~63) * 16;      // this wavefront's 1 KiB
-            if (ok) {
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(arow[i] + tapoff),
-                                                 (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-            } else {
-                *reinterpret_cast<v4i *>(dst + lane * 16) = fillv;
-            }
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ok ? arow[i] + tapoff : fill_src),
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
         }
         const int wtap = CLASSED ? (r0 + a.stride * tr) * a.S + s0 + a.stride * ts : a.flip ? a.taps - 1 - tap : tap;
 #pragma unroll
         for (int i = 0; i < BROWS; i++) {
             if (lrow + RPP * i < BN) {
                 int8_t *dst = Bs + (size_t)buf * BN * BKB + 4096 * i + (tid & ~63) * 16;
-                if (brow_ok[i] && chunk_ok) {
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(bbase[i] + (size_t)wtap * a.Cs + coff),
-                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-                } else {
-                    *reinterpret_cast<v4i *>(dst + lane * 16) = zerov;
-                }
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(brow_ok[i] && chunk_ok ? bbase[i] + (size_t)wtap * a.Cs + coff : zero_src),
+                    (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
             }
         }
         chunk += CPS; c16 += CPS;
