@@ -50,6 +50,15 @@ struct GemmFillRows {
 };
 __device__ const GemmFillRows gemm_fill_rows = GemmFillRows();
 
+// Class form of a strided input gradient: output pixels with (y mod stride, x mod stride) = (ph, pw) see the
+// same taps; such a class is an image of Hc x Wc pixels under a stride-1 stencil of nr x ns taps.
+struct GemmClass {
+    int ph, pw, Hc, Wc;
+    int r0, s0, nr, ns;            // first filter row / column the class sees, and how many (every stride-th)
+    int dh, dw;                    // offset of the class's pixel (y, x) into the gathered tensor
+    unsigned magic_Wc, magic_Hc;   // ceil(2^32 / d)
+};
+
 struct GemmArgs {
     const int8_t *A, *Bw;
     const int32_t *bsum;
@@ -74,6 +83,9 @@ struct GemmArgs {
     int Bn;                        // images (class form)
     int ncls;                      // class form: stride * stride classes, 0 otherwise
     int cls_tile0[17];             // first row tile of each class (prefix sums), [ncls] = m_tiles
+    GemmClass cls[16];             // class form: the stencil of every class, worked out once on the host
+    unsigned magic_Wo, magic_Ho;   // ceil(2^32 / d) for the pixel decode (hq_magic_div)
+    int magic_ok;                  // the decode's operands are in hq_magic_div's range; 0: plain division
     HqSr sr;                       // MODE 2: seed of the stochastic rounding
 };
 
@@ -123,22 +135,29 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
     constexpr bool CLASSED = STRIDED && ALIGNED;
     int Hc = a.Ho, Wc = a.Wo, Mrows = a.M, ph = 0, pw = 0, r0 = 0, s0 = 0, nr = 0, ns = 1, dh = 0, dw = 0;
     int nchunks = a.nchunks;
+    unsigned mWc = a.magic_Wo, mHc = a.magic_Ho;
     if (CLASSED) {
         int cls = 0;
         while (cls + 1 < a.ncls && tile_m >= a.cls_tile0[cls + 1]) cls++;
         tile_m -= a.cls_tile0[cls];
-        ph = cls / a.stride; pw = cls - ph * a.stride;
-        Hc = (a.Ho - ph + a.stride - 1) / a.stride; Wc = (a.Wo - pw + a.stride - 1) / a.stride;
+        const GemmClass &g = a.cls[cls];
+        ph = g.ph; pw = g.pw; Hc = g.Hc; Wc = g.Wc; r0 = g.r0; s0 = g.s0; nr = g.nr; ns = g.ns; dh = g.dh; dw = g.dw;
+        mWc = g.magic_Wc; mHc = g.magic_Hc;
         Mrows = a.Bn * Hc * Wc;
-        r0 = (ph + a.pad) % a.stride; s0 = (pw + a.pad) % a.stride;
-        const int R = a.taps / a.S;
-        nr = r0 < R ? (R - r0 + a.stride - 1) / a.stride : 0;
-        ns = s0 < a.S ? (a.S - s0 + a.stride - 1) / a.stride : 0;
-        dh = (ph + a.pad - r0) / a.stride; dw = (pw + a.pad - s0) / a.stride;
         nchunks = nr * ns * a.cpt;
         if (ns == 0) ns = 1;                       // no taps at all: nchunks == 0, nothing is decoded
     }
     const int m0 = tile_m * BM;
+    // row of the tile's image grid -> (x, y, image): two reciprocal multiplications (a division costs some 40
+    // instructions, and short reductions have few MFMAs to hide them behind)
+    auto decode = [&](int m, int &x, int &y, int &b) {
+        if (a.magic_ok) {
+            const unsigned t = hq_magic_div((unsigned)m, mWc), bb = hq_magic_div(t, mHc);
+            x = (int)((unsigned)m - t * (unsigned)Wc); y = (int)(t - bb * (unsigned)Hc); b = (int)bb;
+        } else {
+            x = m % Wc; const int t = m / Wc; y = t % Hc; b = t / Hc;
+        }
+    };
 
     if (CLASSED && nchunks == 0) {
         // A class no filter tap reaches (1x1 filters with stride 2: three of the four classes): every
@@ -154,7 +173,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
         if (rl < rpp) {
             // the row's pixel is decoded once and then stepped (rpp rows per pass)
             int m = m0 + rl;
-            int x = m % Wc, t = m / Wc, y = t % Hc, b = t / Hc;
+            int x, y, b;
+            decode(m, x, y, b);
             for (int row = rl; row < BM && m < Mrows; row += rpp, m += rpp) {
                 const size_t px = (size_t)(b * a.Ho + ph + a.stride * y) * a.Wo + pw + a.stride * x;
                 const size_t o = px * a.N + n0;
@@ -219,7 +239,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
         const int m = m0 + lrow + RPP * i;
         arow_ok[i] = m < Mrows;
         const int mm = arow_ok[i] ? m : 0;
-        const int x = mm % Wc, y = (mm / Wc) % Hc, b = mm / (Wc * Hc);
+        int x, y, b;
+        decode(mm, x, y, b);
         abase[i] = a.A + (size_t)b * a.Hs * a.Ws * a.Cs;
         ay[i] = CLASSED ? y + dh : STRIDED ? y + a.pad : y * a.stride - a.pad;
         ax[i] = CLASSED ? x + dw : STRIDED ? x + a.pad : x * a.stride - a.pad;
@@ -237,8 +258,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
             arow[i] = abase[i] + ((ptrdiff_t)ay[i] * a.Ws + ax[i]) * a.Cs;
             unsigned long long mk = 0;
             if (use_mask && arow_ok[i]) {
-                for (int t = 0; t < taps_eff; t++) {
-                    const int r = t / tapw_eff, c = t - r * tapw_eff;
+                for (int t = 0, r = 0, c = 0; t < taps_eff; t++, c++) {
+                    if (c == tapw_eff) { c = 0; r++; }
                     const int iy = CLASSED ? ay[i] - r : ay[i] + r, ix = CLASSED ? ax[i] - c : ax[i] + c;
                     if (iy >= 0 && iy < a.Hs && ix >= 0 && ix < a.Ws) mk |= 1ull << t;
                 }
@@ -262,9 +283,9 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
     // swizzle is applied to the chunk the thread fetches instead.
     auto swz = [](int row) { return CPS == 8 ? ((row >> 1) & 7) : ((row >> 2) & (CPS - 1)); };
     const int csrc = ALIGNED ? (cc ^ swz(lrow)) : cc;
-    int chunk = csrc, c16 = csrc % a.cpt, tap = csrc / a.cpt;
     const int tapw = CLASSED ? ns : a.S;             // taps per row of the tap grid the chunks run over
-    int tr = tap / tapw, ts = tap - tr * tapw;
+    int chunk = csrc, c16 = csrc, tap = 0, tr = 0, ts = 0;       // csrc < CPS: a few subtractions instead of divisions
+    while (c16 >= a.cpt) { c16 -= a.cpt; tap++; if (++ts == tapw) { ts = 0; tr++; } }
 
 
     // Aligned form: global -> LDS without passing through registers (global_load_lds_dwordx4: lane l
@@ -447,7 +468,8 @@ __global__ __launch_bounds__(HQ_THREADS, (BKB == 64 && BM == 128 && ALIGNED ? 4 
             int m = m0 + wm * WTM + i * 32 + (lane & 31);
             if (m >= Mrows) continue;
             if (CLASSED) {                                  // row inside the class -> input pixel
-                const int x = m % Wc, y = (m / Wc) % Hc, b = m / (Wc * Hc);
+                int x, y, b;
+                decode(m, x, y, b);
                 m = (b * a.Ho + ph + a.stride * y) * a.Wo + pw + a.stride * x;
             }
 #pragma unroll
@@ -506,12 +528,24 @@ int launch3(GemmArgs &a, hipStream_t s)
     a.m_tiles = (a.M + BM - 1) / BM;
     a.n_tiles = (a.N + BN - 1) / BN;
     a.ncls = 0;
+    a.magic_ok = (unsigned long long)a.M * (unsigned long long)(a.Wo > a.Ho ? a.Wo : a.Ho) < (1ull << 32);
+    a.magic_Wo = hq_magic32((unsigned)a.Wo);
+    a.magic_Ho = hq_magic32((unsigned)a.Ho);
     if (STRIDED && ALIGNED) {
         a.ncls = a.stride * a.stride;
         int t = 0;
         for (int c = 0; c < a.ncls; c++) {
             const int ph = c / a.stride, pw = c % a.stride;
             const int Hc = (a.Ho - ph + a.stride - 1) / a.stride, Wc = (a.Wo - pw + a.stride - 1) / a.stride;
+            GemmClass &g = a.cls[c];
+            g.ph = ph; g.pw = pw; g.Hc = Hc; g.Wc = Wc;
+            g.r0 = (ph + a.pad) % a.stride; g.s0 = (pw + a.pad) % a.stride;
+            const int R = a.taps / a.S;
+            g.nr = g.r0 < R ? (R - g.r0 + a.stride - 1) / a.stride : 0;
+            g.ns = g.s0 < a.S ? (a.S - g.s0 + a.stride - 1) / a.stride : 0;
+            g.dh = (ph + a.pad - g.r0) / a.stride; g.dw = (pw + a.pad - g.s0) / a.stride;
+            g.magic_Wc = Wc > 0 ? hq_magic32((unsigned)Wc) : 0u;
+            g.magic_Hc = Hc > 0 ? hq_magic32((unsigned)Hc) : 0u;
             a.cls_tile0[c] = t;
             t += (a.Bn * Hc * Wc + BM - 1) / BM;
         }
