@@ -43,6 +43,7 @@ struct BandwArgs {
     int PH, PW;                    // patch rows per image (rows + 2) and patch row length (W + 2)
     int patch_px;                  // nimg * PH * PW
     unsigned magic_img, magic_PW;  // ceil(2^32 / (PH * PW)), ceil(2^32 / PW)
+    unsigned magic_HW, magic_W;    // ceil(2^32 / (H * W)), ceil(2^32 / W): a tile pixel -> (image, row, column)
     unsigned long long count;
     HqSr sr;                       // seed of stochastic rounding (epilogue mode 2)
 };
@@ -171,8 +172,9 @@ __global__ __launch_bounds__(HQ_THREADS, 2) void hq_bandw_kernel(const BandwArgs
             const int pt = wave * 64 + i * 32 + (lane & 31);
             ok[i] = pt < npix;
             const int p = ok[i] ? pt : 0;
-            const int il = p / (trows * a.W), r1 = p - il * (trows * a.W);
-            const int oy = r1 / a.W, ox = r1 - oy * a.W;
+            // (tiles of several images hold whole images: trows == H there; p < 256)
+            const int il = a.nimg == 1 ? 0 : (int)hq_magic_div((unsigned)p, a.magic_HW), r1 = p - il * (trows * a.W);
+            const int oy = (int)hq_magic_div((unsigned)r1, a.magic_W), ox = r1 - oy * a.W;
             prow[i] = (il * a.PH + oy) * a.PW + ox;
         }
         const bool active = wave * 64 < npix;                          // scalar
@@ -347,6 +349,8 @@ int hq_try_launch_bandw(const hq_problem *p, int dgrad, const int8_t *A, const h
     a.patch_px = a.nimg * a.PH * a.PW;
     a.magic_img = hq_magic32((unsigned)(a.PH * a.PW));
     a.magic_PW = hq_magic32((unsigned)a.PW);
+    a.magic_HW = hq_magic32((unsigned)(p->H * p->W));
+    a.magic_W = hq_magic32((unsigned)p->W);
     a.count = (unsigned long long)p->B * p->H * p->W * N;
     a.sr = sr_seed ? HqSr{(unsigned)*sr_seed, (unsigned)(*sr_seed >> 32)} : HqSr{0, 0};
     const size_t patch_bytes = ((size_t)a.patch_px * BW_CK + 1023) & ~(size_t)1023;
