@@ -573,6 +573,7 @@ struct WbandArgs {
     int B, H, W, C, N;
     int rows, nimg;                // band: `rows` output rows of one image, or `nimg` whole images (rows == H)
     int bands_per_img;
+    unsigned magic_bpi;            // ceil(2^32 / bands_per_img)
     int nstages, stages_per_block, splits;
     int cparts, nparts;            // C / 64, N / 64
     int npix, npix_pad;            // output pixels of a band, rounded up to a k-step
@@ -640,7 +641,7 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
     v4i xreg[WB_XLD], greg[WB_GLD];
     auto load_stage = [&](int s) {
         int b0, y0;
-        if (a.nimg == 1) { b0 = s / a.bands_per_img; y0 = (s - b0 * a.bands_per_img) * a.rows; }
+        if (a.nimg == 1) { b0 = (int)hq_magic_div((unsigned)s, a.magic_bpi); y0 = (s - b0 * a.bands_per_img) * a.rows; }
         else { b0 = s * a.nimg; y0 = 0; }
         const size_t pix0 = ((size_t)b0 * a.H + y0) * a.W;
         const int8_t *xs = a.X + pix0 * a.C + c0;
@@ -969,6 +970,7 @@ bool launch_wgrad_band(const hq_problem *p, const WbandPlan &pl, const WgradArgs
     a.B = p->B; a.H = p->H; a.W = p->W; a.C = p->C; a.N = p->Cout;
     a.rows = pl.rows; a.nimg = pl.nimg;
     a.bands_per_img = p->H / pl.rows;
+    a.magic_bpi = hq_magic32((unsigned)a.bands_per_img);
     a.nstages = pl.nstages; a.stages_per_block = pl.stages_per_block; a.splits = pl.splits;
     a.cparts = p->C / 64; a.nparts = p->Cout / 64;
     a.npix = pl.npix; a.npix_pad = pl.npix_pad;
