@@ -310,21 +310,34 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
                                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                                         wf[ks][j], af[ks][i], (decltype(first)::value && ks == 0) ? nbz[j] : acc[i][j], 0, 0, 0);
                     };
+                    // the fragment reads of tap t + 1 are dealt between the MFMAs of tap t (a wavefront issues in
+                    // order; an MFMA holds the matrix pipe for 32 cycles in which seven other instructions can go)
+                    auto interleave = [&]() {
+#pragma unroll
+                        for (int q = 0; q < KS * (NT + 2); q++) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
+                            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);     // one vector ALU instruction
+                        }
+                        __builtin_amdgcn_sched_group_barrier(0x008, KS * 2 * NT, 0);
+                    };
                     load_tap(0, wfA, afA);
 #pragma unroll
                     for (int t = 0; t < TAPS; t += 2) {
-                        if (t + 1 < TAPS) load_tap(t + 1, wfB, afB);
                         __builtin_amdgcn_sched_barrier(0);
+                        if (t + 1 < TAPS) load_tap(t + 1, wfB, afB);
                         if (t == 0) mfma_tap(wfA, afA, std::true_type()); else mfma_tap(wfA, afA, std::false_type());
+                        if (t + 1 < TAPS) interleave();
                         __builtin_amdgcn_sched_barrier(0);
                         if (have_pf) {
 #pragma unroll
                             for (int k = t * RPT; k < (t + 1) * RPT && k < PR; k++) prefetch_row(k);
                         }
-                        if (t + 2 < TAPS) load_tap(t + 2, wfA, afA);
                         __builtin_amdgcn_sched_barrier(0);
+                        if (t + 2 < TAPS) load_tap(t + 2, wfA, afA);
                         if (t + 1 < TAPS) {
                             mfma_tap(wfB, afB, std::false_type());
+                            if (t + 2 < TAPS) interleave();
                             __builtin_amdgcn_sched_barrier(0);
                             if (have_pf) {
 #pragma unroll
