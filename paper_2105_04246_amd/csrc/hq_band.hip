@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256 * NG, NG == 1 ? 2 : 1) void hq_band_kernel(cons
     int8_t *Pt = Pl + NG * (size_t)patch_bytes;            // patch of an early last tile (if a.tail_patch)
     int *red = reinterpret_cast<int *>(Pl + (NG + a.tail_patch) * (size_t)patch_bytes);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it are uniform
     const int grp = NG == 2 ? wave >> 2 : 0, gwave = wave & 3, gtid = tid & 255;
     int8_t *Pg = Pl + grp * patch_bytes;                   // this group's patch
 

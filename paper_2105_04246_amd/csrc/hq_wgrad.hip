@@ -88,7 +88,7 @@ __global__ __launch_bounds__(HQ_THREADS) void hq_wgrad_kernel(const WgradArgs a)
     __shared__ __attribute__((aligned(16))) int8_t Gs[2][MB * PG];
     __shared__ __attribute__((aligned(16))) int8_t Xs[2][MB * PX];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it are uniform
     const int wn = wave >> 1, wk = wave & 1;
     // Workgroup -> (tile column bx, tile row by, pixel split bz).  All tile columns and rows of
     // one pixel split read the same X / dY rows; consecutive workgroup ids go round-robin over
@@ -589,7 +589,7 @@ __global__ __launch_bounds__(WB_THREADS) void hq_wgrad_band_kernel(const WbandAr
     int8_t *bufs = smem + ((a.npix_pad * 4 + 15) & ~15);
     const unsigned xbytes = (unsigned)a.prows * a.PW * WB_P;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it are uniform
     const int grp = wave >> 2, cblk = wave & 1, th = (wave >> 1) & 1;
     const int t0 = th ? 5 : 0, nt = th ? 4 : 5;
 
